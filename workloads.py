@@ -1,0 +1,190 @@
+"""Seeded synthetic inputs for the DSGD-CECA hot path.
+
+This module only *draws data*: it holds none of the method's arithmetic (no
+schedule, no gossip weights, no gradients) and imports neither the oracle nor
+the HIP binding, so both sides can be fed the very same arrays.
+
+The five workloads mirror the shapes of the paper's least-squares experiment
+(Sec. 5, "DSGD: least-squares problem": A_i ~ N(0, I), b_i = A_i x* + v_i) and
+of a flat deep-network parameter vector; they stand in for the MNIST / CIFAR-10
+runs of Sec. 5 and App. D, whose datasets are not available here.  Every
+generator takes explicit sizes so tests can shrink a workload while keeping its
+structure.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Optional
+
+import numpy as np
+
+
+@dataclasses.dataclass(frozen=True)
+class WorkloadSpec:
+    """Sizes and hyper-parameters of one workload (nothing is drawn here)."""
+
+    name: str
+    n: int            # agents at the stated port
+    port: int         # 1 or 2
+    d: int            # parameters per agent
+    loss: str         # "lsq" | "logistic" | "quad_center" | "none"
+    N: int = 0        # samples per agent
+    B: int = 0        # minibatch rows per agent per iteration
+    lr: float = 0.0
+    iters: int = 0
+    seed: int = 0
+    noise_std: float = 0.0
+
+
+# The five configurations.  CECA-1P exists for even n only (Table 1), so the two
+# configurations that ask for 1P at an odd n are carried twice: 2P at the stated
+# n and 1P at the nearest even n with the same number of rounds.
+SPECS = {
+    "lsq5_2p": WorkloadSpec("lsq5_2p", n=5, port=2, d=1000, loss="lsq", N=64, B=8, lr=0.01, iters=200, seed=0),
+    "lsq6_1p": WorkloadSpec("lsq6_1p", n=6, port=1, d=1000, loss="lsq", N=64, B=8, lr=0.01, iters=200, seed=0),
+    "logistic6_2p": WorkloadSpec("logistic6_2p", n=6, port=2, d=10_000, loss="logistic", N=2000, B=32,
+                                 lr=0.05, iters=500, seed=1),
+    "gossip100_1p": WorkloadSpec("gossip100_1p", n=100, port=1, d=1 << 20, loss="none", seed=2),
+    "gossip100_2p": WorkloadSpec("gossip100_2p", n=100, port=2, d=1 << 20, loss="none", seed=2),
+    "quad31_2p": WorkloadSpec("quad31_2p", n=31, port=2, d=25_557_032, loss="quad_center", lr=0.1, iters=50,
+                              seed=3, noise_std=0.01),
+    "quad30_1p": WorkloadSpec("quad30_1p", n=30, port=1, d=25_557_032, loss="quad_center", lr=0.1, iters=50,
+                              seed=3, noise_std=0.01),
+    "logistic1023_2p": WorkloadSpec("logistic1023_2p", n=1023, port=2, d=4096, loss="logistic", N=512, B=16,
+                                    lr=0.02, iters=2000, seed=4),
+}
+
+
+def shrink(spec: WorkloadSpec, **kw) -> WorkloadSpec:
+    """The same workload at other sizes (used by tests)."""
+    return dataclasses.replace(spec, **kw)
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    # independent child streams so that shrinking one array does not shift another
+    return np.random.default_rng(np.random.SeedSequence([seed, stream]))
+
+
+def initial_state(n: int, d: int, seed: int, kind: str = "normal") -> np.ndarray:
+    """x(0), shape (n, d) float32.  kind = "normal" (N(0,1) entries) or "zero"."""
+    if kind == "zero":
+        return np.zeros((n, d), dtype=np.float32)
+    return _rng(seed, 0).standard_normal((n, d), dtype=np.float32)
+
+
+def batch_indices(n: int, N: int, B: int, iters: int, seed: int) -> np.ndarray:
+    """Minibatch row numbers, shape (iters, n, B) int32, uniform on [0, N) with replacement."""
+    return _rng(seed, 1).integers(0, N, size=(iters, n, B), dtype=np.int32)
+
+
+def lsq_data(n: int, N: int, d: int, seed: int, obs_noise: float = 0.1):
+    """Least-squares data: A (n, N, d), b (n, N), x_star (d,), all float32."""
+    g = _rng(seed, 2)
+    A = g.standard_normal((n, N, d), dtype=np.float32)
+    x_star = g.standard_normal(d, dtype=np.float32)
+    v = g.standard_normal((n, N), dtype=np.float32)
+    b = (A.astype(np.float64) @ x_star.astype(np.float64) + obs_noise * v).astype(np.float32)
+    return A, b, x_star
+
+
+def logistic_data_hetero(n: int, N: int, d: int, seed: int, mu_std: float = 0.5, label_noise: float = 0.1):
+    """Non-iid logistic data: features N(mu_i, I) with mu_i ~ N(0, mu_std^2 I) per agent,
+    labels sign(a.w* + label_noise*N(0,1)) in {-1,+1} (0 maps to +1).  Returns A (n,N,d), labels (n,N), w_star."""
+    g = _rng(seed, 3)
+    w_star = g.standard_normal(d, dtype=np.float32)
+    A = np.empty((n, N, d), dtype=np.float32)
+    lab = np.empty((n, N), dtype=np.float32)
+    for i in range(n):
+        mu = (mu_std * g.standard_normal(d)).astype(np.float32)
+        A[i] = g.standard_normal((N, d), dtype=np.float32) + mu
+        s = A[i].astype(np.float64) @ w_star.astype(np.float64) + label_noise * g.standard_normal(N)
+        lab[i] = np.where(s >= 0, 1.0, -1.0)
+    return A, lab, w_star
+
+
+def logistic_data_sparse(n: int, N: int, d: int, seed: int, density: float = 0.1, flip: float = 0.05):
+    """Logistic data with N(0,1) features of which a `density` fraction is non-zero (dense storage),
+    labels sign(a.w*) with a `flip` fraction inverted.  Returns A (n,N,d), labels (n,N), w_star."""
+    g = _rng(seed, 4)
+    w_star = g.standard_normal(d, dtype=np.float32)
+    A = np.empty((n, N, d), dtype=np.float32)
+    lab = np.empty((n, N), dtype=np.float32)
+    for i in range(n):
+        Ai = g.standard_normal((N, d), dtype=np.float32)
+        Ai *= (g.random((N, d), dtype=np.float32) < density)
+        A[i] = Ai
+        s = Ai.astype(np.float64) @ w_star.astype(np.float64)
+        y = np.where(s >= 0, 1.0, -1.0)
+        y[g.random(N) < flip] *= -1.0
+        lab[i] = y
+    return A, lab, w_star
+
+
+def quad_centers(n: int, d: int, seed: int) -> np.ndarray:
+    """Per-agent centres c_i ~ N(0,1)^d of the quadratic loss, shape (n, d) float32."""
+    return _rng(seed, 5).standard_normal((n, d), dtype=np.float32)
+
+
+# ---------------------------------------------------------------------------
+# Device-side generation for the workloads that are too large to draw on the
+# host in reasonable time (n*d ~ 8e8).  torch is only a random-number source
+# and an allocator here.
+# ---------------------------------------------------------------------------
+
+def device_normal(shape, seed: int, device: str = "cuda", out=None):
+    """N(0,1) float32 tensor drawn on `device` from a seeded torch generator."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=device)
+    # row by row keeps the transient memory of the generator small for multi-GB tensors
+    if out.dim() >= 2:
+        for i in range(out.shape[0]):
+            out[i].normal_(generator=gen)
+    else:
+        out.normal_(generator=gen)
+    return out
+
+
+def device_logistic_sparse(n: int, N: int, d: int, seed: int, device: str = "cuda",
+                           density: float = 0.1, flip: float = 0.05):
+    """Device version of `logistic_data_sparse` (same structure, torch generator)."""
+    import torch
+
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    w_star = torch.empty(d, dtype=torch.float32, device=device).normal_(generator=gen)
+    A = torch.empty((n, N, d), dtype=torch.float32, device=device)
+    lab = torch.empty((n, N), dtype=torch.float32, device=device)
+    for i in range(n):
+        Ai = A[i]
+        Ai.normal_(generator=gen)
+        mask = torch.empty((N, d), dtype=torch.float32, device=device).uniform_(generator=gen) < density
+        Ai.mul_(mask)
+        s = Ai.double() @ w_star.double()
+        y = torch.where(s >= 0, 1.0, -1.0).float()
+        fl = torch.empty(N, dtype=torch.float32, device=device).uniform_(generator=gen) < flip
+        lab[i] = torch.where(fl, -y, y)
+    return A, lab, w_star
+
+
+def sample_columns(d: int, count: int, seed: int, tile: int = 1024, tail: Optional[int] = None) -> np.ndarray:
+    """Sorted column numbers for sampled full-size parity: the first and last `tile` boundary
+    neighbourhoods, the ragged tail, and uniformly drawn columns in between."""
+    g = _rng(seed, 6)
+    cols = set()
+    edge = [0, 1, 2, 3, tile - 1, tile, tile + 1, d - 1, d - 2, d - 3, d - 4, d - 5, (d // tile) * tile,
+            max((d // tile) * tile - 1, 0), d // 2, d // 2 + 1]
+    for c in edge:
+        if 0 <= c < d:
+            cols.add(int(c))
+    if tail:
+        for c in range(max(d - tail, 0), d):
+            cols.add(c)
+    need = max(count - len(cols), 0)
+    if need:
+        for c in g.integers(0, d, size=need):
+            cols.add(int(c))
+    return np.array(sorted(cols), dtype=np.int64)
