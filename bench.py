@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSGD-CECA hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: one dsgd_ceca_step call
+(gradient + CECA round fused) for the training workloads, one ceca_gossip_round call for the pure
+gossip workloads.  Inputs are generated on the device before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--others] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+import workloads as WL  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+
+# Algorithmic HBM bytes per agent-parameter per call, fp32 state [x; y]: every distinct array element
+# moved once (x, y read; x+, y+ written; centres read once for the fused quadratic step).  The
+# "model" figure also charges the peer row as a separate read, as a row-gather kernel would pay it.
+BYTES = {
+    ("gossip", 1): (16.0, 16.0), ("gossip", 2): (16.0, 20.0),
+    ("quad_center", 1): (20.0, 20.0), ("quad_center", 2): (20.0, 28.0),
+}
+
+
+def minibatch_bytes(B: int):
+    # A_B rows once, z once, x, y read, x+, y+ written | model: A_B twice, z twice, v written and read twice
+    return 4.0 * B + 16.0, 8.0 * B + 36.0
+
+
+def _tau(n):
+    return (n - 1).bit_length()
+
+
+class Timer:
+    """HIP events on the stream the kernels are launched on (torch's current stream) + host clock."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.e0 = torch.cuda.Event(enable_timing=True)
+        self.e1 = torch.cuda.Event(enable_timing=True)
+
+    def __enter__(self):
+        self.torch.cuda.synchronize()
+        self.t0 = time.perf_counter()
+        self.e0.record()
+        return self
+
+    def __exit__(self, *a):
+        self.e1.record()
+        self.torch.cuda.synchronize()
+        self.wall_ms = (time.perf_counter() - self.t0) * 1e3
+        self.event_ms = self.e0.elapsed_time(self.e1)
+
+
+def run_quad(torch, P, Bn, sp, steps, warmup):
+    n, d, port = sp.n, sp.d, sp.port
+    c = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, d), seed=sp.seed, out=c)
+    S = torch.zeros((2 * n, d), dtype=torch.float32, device="cuda")
+    T = S if port == 1 else torch.empty_like(S)
+    tau = _tau(n)
+
+    def step(k):
+        nonlocal S, T
+        P.dsgd_ceca_step(S, T, n, d, Bn.make_quad_center_loss(c, sp.noise_std, sp.seed, k), None, sp.lr,
+                         k % tau, port)
+        if port == 2:
+            S, T = T, S
+
+    for k in range(warmup):
+        step(k)
+    with Timer(torch) as tm:
+        for k in range(warmup, warmup + steps):
+            step(k)
+    return tm, 1, BYTES[("quad_center", port)]
+
+
+def run_gossip(torch, P, Bn, sp, steps, warmup):
+    n, d, port = sp.n, sp.d, sp.port
+    S = torch.empty((2 * n, d), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, d), seed=sp.seed, out=S[:n])
+    S[n:] = S[:n]
+    T = S if port == 1 else torch.empty_like(S)
+    tau = _tau(n)
+
+    def step(k):
+        nonlocal S, T
+        P.ceca_gossip_round(S, T, n, d, k % tau, port)
+        if port == 2:
+            S, T = T, S
+
+    for k in range(warmup):
+        step(k)
+    with Timer(torch) as tm:
+        for k in range(warmup, warmup + steps):
+            step(k)
+    return tm, 1, BYTES[("gossip", port)]
+
+
+def run_minibatch(torch, P, Bn, sp, steps, warmup):
+    n, d, port, N, B = sp.n, sp.d, sp.port, sp.N, sp.B
+    if sp.name.startswith("logistic1023"):
+        A, t, _ = WL.device_logistic_sparse(n, N, d, sp.seed)
+    else:
+        if sp.loss == "lsq":
+            Ah, th, _ = WL.lsq_data(n, N, d, sp.seed)
+        else:
+            Ah, th, _ = WL.logistic_data_hetero(n, N, d, sp.seed)
+        A, t = torch.from_numpy(Ah).cuda(), torch.from_numpy(th).cuda()
+    nidx = min(steps + warmup, 256)
+    idx = torch.from_numpy(WL.batch_indices(n, N, B, nidx, sp.seed)).cuda()
+    loss = Bn.make_minibatch_loss(Bn.LOSS_LSQ if sp.loss == "lsq" else Bn.LOSS_LOGISTIC, A, t, N, B)
+    ws = torch.empty(P.dsgd_ceca_workspace_bytes(n, d, loss), dtype=torch.uint8, device="cuda")
+    S = torch.zeros((2 * n, d), dtype=torch.float32, device="cuda")
+    T = S if port == 1 else torch.empty_like(S)
+    tau = _tau(n)
+
+    def step(k):
+        nonlocal S, T
+        P.dsgd_ceca_step(S, T, n, d, loss, idx[k % nidx], sp.lr, k % tau, port, workspace=ws)
+        if port == 2:
+            S, T = T, S
+
+    for k in range(warmup):
+        step(k)
+    with Timer(torch) as tm:
+        for k in range(warmup, warmup + steps):
+            step(k)
+    return tm, 3, minibatch_bytes(B)
+
+
+def measure(torch, P, Bn, name, steps, warmup):
+    sp = WL.SPECS[name]
+    fn = {"quad_center": run_quad, "none": run_gossip}.get(sp.loss, run_minibatch)
+    tm, launches, (b_alg, b_model) = fn(torch, P, Bn, sp, steps, warmup)
+    torch.cuda.empty_cache()
+    ms = tm.wall_ms / steps
+    ev_ms = tm.event_ms / steps
+    units = sp.n * sp.d
+    return {
+        "workload": name, "n": sp.n, "d": sp.d, "port": sp.port, "loss": sp.loss, "steps": steps,
+        "ms_per_step": ms, "event_ms_per_step": ev_ms, "kernels_per_step": launches,
+        "agent_param_updates_per_s": units / (ms * 1e-3),
+        "bytes_per_agent_param": b_alg, "bytes_per_agent_param_gather_model": b_model,
+        "achieved_GBs": units * b_alg / (ev_ms * 1e-3) / 1e9,
+        "gather_model_GBs": units * b_model / (ev_ms * 1e-3) / 1e9,
+    }
+
+
+def cpu_baseline(sp, target_s=12.0):
+    """The fp64 oracle on this host's cores, on a bounded column sample of the same workload."""
+    from oracle import ceca as OC
+    from oracle import losses as OL
+
+    n = sp.n
+    cols_n = 1 << 18
+    cols = np.arange(cols_n, dtype=np.int64)
+    c = WL.quad_centers(n, cols_n, sp.seed)
+    grad = OL.make_quad_center_grad(c, sp.noise_std, sp.seed, columns=cols)
+    x = y = np.zeros((n, cols_n))
+    t0 = time.perf_counter()
+    iters = 0
+    while True:
+        x, y = OC.dsgd_ceca_step(x, y, iters, sp.port, sp.lr, grad, store32=True)
+        iters += 1
+        el = time.perf_counter() - t0
+        if el > target_s or iters >= sp.iters:
+            break
+    threads = 1   # the oracle is numpy elementwise code: one thread
+    return {"value": n * cols_n * iters / el, "unit": "agent-param updates/s", "cores": threads, "kind": "oracle",
+            "sample": f"{iters} iterations of {sp.name} on the first {cols_n} of {sp.d} columns "
+                      f"(all {n} agents), fp64 numpy, {el:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="quad31_2p", choices=sorted(WL.SPECS))
+    ap.add_argument("--others", action="store_true", help="also time the remaining workloads (reported under 'others')")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (all agents are simulated on one device); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2306_00256_amd as P
+    from paper_2306_00256_amd import binding as Bn
+
+    P.lib()     # raises if the HIP library is missing: there is no fallback path
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    main_res = measure(torch, P, Bn, args.workload, args.steps, args.warmup)
+    sp = WL.SPECS[args.workload]
+    out = {
+        "metric": "agent-param updates/s per DSGD-CECA round",
+        "value": main_res["agent_param_updates_per_s"],
+        "unit": "agent-param updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "n_agents": sp.n, "d": sp.d, "port": sp.port, "loss": sp.loss,
+                   "lr": sp.lr, "state_bytes": 2 * sp.n * sp.d * 4},
+        "roofline": {
+            "bound": "hbm",
+            "achieved": main_res["achieved_GBs"],
+            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": main_res["achieved_GBs"] / HBM_PEAK_GBS,
+            "traffic": None,
+            "bytes_per_agent_param": main_res["bytes_per_agent_param"],
+            "kernel_ms": main_res["event_ms_per_step"] / main_res["kernels_per_step"],
+            "gather_model_GBs": main_res["gather_model_GBs"],
+        },
+    }
+    if args.others:
+        out["others"] = []
+        for name in sorted(WL.SPECS):
+            if name == args.workload:
+                continue
+            sp_o = WL.SPECS[name]
+            k = 50 if sp_o.loss in ("quad_center",) else (70 if sp_o.loss == "none" else 200)
+            out["others"].append(measure(torch, P, Bn, name, k, 5))
+    if not args.no_cpu:
+        base_sp = sp if sp.loss == "quad_center" else WL.SPECS["quad31_2p"]
+        out["cpu_baseline"] = cpu_baseline(base_sp)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,139 @@
+/*
+ * ceca.h -- C ABI of the DSGD-CECA hot path for one AMD MI355X (gfx950).
+ *
+ * All n agents of a decentralized run are simulated on one device as rows of a
+ * stacked state S = [x; y]: 2n rows of `ld` floats, rows 0..n-1 hold the models
+ * x_i, rows n..2n-1 the auxiliary models y_i (stacked notation of Sec. 4.1 and
+ * App. A of the DSGD-CECA paper, arXiv 2306.00256).  One iteration = one local
+ * stochastic-gradient step per agent plus one CECA communication round
+ * (Algorithm 1); tau = ceil(log2 n) gradient-free rounds leave every x_i equal
+ * to the global mean for any n (Sec. 3).
+ *
+ * Conventions
+ *   - Every function returns an int32 status (0 = CECA_OK, negative = error) or a
+ *     byte count; nothing aborts or throws.  ceca_last_error() gives a message for
+ *     the calling thread's most recent failure.
+ *   - "device" pointers are HIP device memory owned by the caller; the library
+ *     never allocates, frees or retains them.  "host" pointers are ordinary memory.
+ *   - Device calls are asynchronous on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream); the library never synchronizes.
+ *   - Agents and rounds are 0-based: row i is the paper's agent i+1, r = k mod tau
+ *     is the ordinary remainder in [0, tau) (Algorithm 1).
+ *   - Any base pointer / leading dimension is accepted; 16-byte aligned bases with
+ *     leading dimensions that are multiples of 4 take the vectorized kernels, other
+ *     layouts silently take a scalar kernel with identical results.
+ */
+#ifndef CECA_H
+#define CECA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CECA_OK = 0,
+  CECA_EINVAL = -1,     /* bad size, round, port, leading dimension, null pointer, or forbidden aliasing */
+  CECA_EODD1P = -2,     /* port == 1 with odd n: CECA-1P exists for even n only (Table 1, Sec. 3.2) */
+  CECA_EWORKSPACE = -3, /* workspace missing or smaller than the matching *_workspace_bytes() */
+  CECA_EHIP = -4        /* a HIP runtime call failed; see ceca_last_hip_error() */
+};
+
+enum { CECA_LOSS_LSQ = 0, CECA_LOSS_LOGISTIC = 1, CECA_LOSS_QUAD_CENTER = 2 };
+
+/* One CECA round, as Algorithm 1 uses it (Sec. 3.1 Eqs. (2), (3); Sec. 4.1). */
+typedef struct {
+  int32_t n, tau, r, port;
+  int32_t delta;        /* delta_r: bit tau-1-r of n-1 (Eq. (2), most significant first) */
+  int32_t n_r;          /* window size before the round (Eq. (3)) */
+  int32_t shift;        /* 2 ports: n_r + delta_r, row i receives from row i - shift (Eqs. (5), (6));
+                           1 port: 2 n_r + 1, even rows pair with i + shift, odd rows with i - shift (Eq. (7)) */
+  int32_t exchange_y;   /* 0: z = x travels (delta_r = 1);  1: z = y travels (delta_r = 0) */
+  int32_t a_num, a_den; /* self-weight a of the x update: 1/2 or (n_r+1)/(2 n_r+1) */
+  int32_t b_num, b_den; /* self-weight b of the y update: n_r/(2 n_r+1) or 1/2 */
+  float a, a_peer;      /* (float)((double)a_num/a_den), (float)((double)(a_den-a_num)/a_den) */
+  float b, b_peer;      /* same for b */
+} ceca_round_t;
+
+/* Per-agent stochastic gradient e_i = grad F(z_i; xi_i), evaluated once per agent per
+ * iteration at z_i (Algorithm 1).  Minibatch losses average over the B sampled rows:
+ *   LSQ         e_i = 1/B sum_j (a_ij . z_i - t_ij) a_ij          (least squares of Sec. 5)
+ *   LOGISTIC    e_i = -1/B sum_j t_ij sigma(-t_ij a_ij . z_i) a_ij,  labels t_ij = +-1
+ *   QUAD_CENTER e_i = z_i - c_i + noise_std * eps_i, eps_i ~ N(0, I) from a counter-based
+ *               generator keyed by (seed, k, agent, column); its definition is in the design doc */
+typedef struct {
+  int32_t kind;         /* CECA_LOSS_* */
+  int32_t N;            /* samples per agent (minibatch losses) */
+  int32_t B;            /* minibatch rows per agent per iteration, 1..64 */
+  uint32_t seed;        /* QUAD_CENTER: noise seed */
+  uint32_t k;           /* QUAD_CENTER: iteration number fed to the noise counter */
+  float noise_std;      /* QUAD_CENTER: noise scale, 0 = none */
+  const float* A;       /* device, n*N rows of lda floats: row i*N + j is sample j of agent i */
+  int64_t lda;          /* >= d */
+  const float* t;       /* device, n*N floats: targets (LSQ) or labels +-1 (LOGISTIC) */
+  const float* c;       /* device, n rows of ldc floats: centres (QUAD_CENTER) */
+  int64_t ldc;          /* >= d */
+} ceca_loss_t;
+
+/* tau = ceil(log2 n), computed as the bit length of n-1 (Sec. 3.1); n = 1 gives 0; n < 1 gives CECA_EINVAL. */
+int32_t ceca_tau(int32_t n);
+
+/* Schedule of round r (host only, integer exact).  `out` (host, may be NULL) receives the round;
+ * `peer` (host, caller-owned, n entries, may be NULL) receives the 0-based receive-from map:
+ * row i combines its own rows with the message of row peer[i] (Eqs. (5)-(7)).
+ * Errors: CECA_EINVAL for n < 2, r outside [0, tau), port not 1 or 2; CECA_EODD1P. */
+int32_t ceca_schedule(int32_t n, int32_t r, int32_t port, ceca_round_t* out, int32_t* peer);
+
+/* One gradient-free CECA round (Sec. 3.1 / 3.2 "Main recursions" with I = x, J = y):
+ *   x_i+ = a x_i + (1-a) z_peer(i),   y_i+ = b y_i + (1-b) z_peer(i),   z = x or y by delta_r.
+ * S_in, S_out: device, 2n rows of ld floats (d used).  port 2 needs S_out disjoint from S_in;
+ * port 1 also accepts S_out == S_in (pairs are closed under the round).  n = 1 copies (r must be 0).
+ * In round 0 (b = 0) the y rows of S_in are not read. */
+int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
+                          int32_t r, int32_t port, void* hip_stream);
+
+/* Bytes of device workspace dsgd_ceca_step needs for this problem (0 for QUAD_CENTER); < 0 on error. */
+int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss);
+
+/* One DSGD-CECA iteration (Algorithm 1, Eqs. (8), (9)) with the gradient fused in:
+ *   e_i = grad at z_i,  v_i = z_i - lr e_i,
+ *   x_i+ = a (x_i - lr e_i) + (1-a) v_peer(i),   y_i+ = b (y_i - lr e_i) + (1-b) v_peer(i).
+ * batch_idx: device, n*B int32 in [0, N), row i = agent i's sampled rows (NULL for QUAD_CENTER).
+ * workspace: device, 256-byte aligned, at least dsgd_ceca_workspace_bytes() (may be NULL when that is 0);
+ * its contents are scratch.  Aliasing rules as ceca_gossip_round.  n = 1: plain SGD on x, y+ = x+. */
+int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
+                       const ceca_loss_t* loss, const int32_t* batch_idx, float lr,
+                       int32_t r, int32_t port, void* workspace, int64_t workspace_bytes,
+                       void* hip_stream);
+
+/* Bytes of device workspace consensus_error needs; < 0 on error. */
+int64_t consensus_error_workspace_bytes(int32_t n, int64_t d);
+
+/* Consensus observables of X (device, n rows of ld floats), accumulated in fp64:
+ *   out[0] = ||X - 1 xbar^T||_F^2      (consensus distance of the descent lemma, App. B.3)
+ *   out[1] = sum_i ||x_i - xbar||      (the residue plotted in Sec. 5, with xbar the current mean)
+ *   out[2] = max_i ||x_i - xbar||
+ *   out[3] = ||xbar||
+ *   out[4] = n
+ * out: device, 5 doubles.  xbar_or_null: device, d floats, receives the mean when not NULL. */
+int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double* out,
+                        float* xbar_or_null, void* workspace, int64_t workspace_bytes,
+                        void* hip_stream);
+
+/* Message for the calling thread's most recent error ("" if none); valid until its next failing call. */
+const char* ceca_last_error(void);
+/* hipError_t value behind the calling thread's most recent CECA_EHIP (0 if none). */
+int32_t ceca_last_hip_error(void);
+
+/* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe against running calls):
+ *   CECA_OPT_SEGMENT  agents a 2-port chain walks before it starts a new one (0 = library default)
+ *   CECA_OPT_UNROLL   16-byte column groups per thread, 1 or 2 (0 = library default)
+ * Returns CECA_EINVAL for an unknown option or value. */
+enum { CECA_OPT_SEGMENT = 1, CECA_OPT_UNROLL = 2 };
+int32_t ceca_set_option(int32_t option, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CECA_H */

@@ -1,0 +1,21 @@
+"""MI355X-native hot path of DSGD-CECA (arXiv 2306.00256): thin Python binding over libceca.so.
+
+Every step of the path runs in the HIP kernels behind the C ABI of include/ceca.h; this package only
+marshals arguments.  PyTorch supplies device memory and streams.  There is no CPU fallback: loading
+fails if the library has not been built (python -m paper_2306_00256_amd.build).
+"""
+from .binding import (  # noqa: F401
+    CecaError,
+    Loss,
+    Round,
+    ceca_gossip_round,
+    ceca_schedule,
+    ceca_set_option,
+    ceca_tau,
+    consensus_error,
+    consensus_error_workspace_bytes,
+    dsgd_ceca_step,
+    dsgd_ceca_workspace_bytes,
+    lib,
+    library_path,
+)

@@ -1,0 +1,154 @@
+"""ctypes binding of include/ceca.h: same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libceca.so")
+
+CECA_OK, CECA_EINVAL, CECA_EODD1P, CECA_EWORKSPACE, CECA_EHIP = 0, -1, -2, -3, -4
+LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER = 0, 1, 2
+OPT_SEGMENT, OPT_UNROLL = 1, 2
+
+EXPORTS = (
+    "ceca_tau", "ceca_schedule", "ceca_gossip_round", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step",
+    "consensus_error_workspace_bytes", "consensus_error", "ceca_last_error", "ceca_last_hip_error",
+    "ceca_set_option",
+)
+
+
+class CecaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"ceca error {code}: {msg}")
+        self.code = code
+
+
+class Round(C.Structure):
+    """ceca_round_t"""
+    _fields_ = [(k, C.c_int32) for k in ("n", "tau", "r", "port", "delta", "n_r", "shift", "exchange_y",
+                                         "a_num", "a_den", "b_num", "b_den")] + \
+               [(k, C.c_float) for k in ("a", "a_peer", "b", "b_peer")]
+
+
+class Loss(C.Structure):
+    """ceca_loss_t"""
+    _fields_ = [("kind", C.c_int32), ("N", C.c_int32), ("B", C.c_int32), ("seed", C.c_uint32), ("k", C.c_uint32),
+                ("noise_std", C.c_float), ("A", C.c_void_p), ("lda", C.c_int64), ("t", C.c_void_p),
+                ("c", C.c_void_p), ("ldc", C.c_int64)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded library; raises if it was never built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_2306_00256_amd.build`")
+        L = C.CDLL(_LIB_PATH)
+        L.ceca_tau.argtypes = [C.c_int32]
+        L.ceca_tau.restype = C.c_int32
+        L.ceca_schedule.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(Round), C.POINTER(C.c_int32)]
+        L.ceca_schedule.restype = C.c_int32
+        L.ceca_gossip_round.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_int32,
+                                        C.c_int32, C.c_void_p]
+        L.ceca_gossip_round.restype = C.c_int32
+        L.dsgd_ceca_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.POINTER(Loss)]
+        L.dsgd_ceca_workspace_bytes.restype = C.c_int64
+        L.dsgd_ceca_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Loss),
+                                     C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
+                                     C.c_void_p]
+        L.dsgd_ceca_step.restype = C.c_int32
+        L.consensus_error_workspace_bytes.argtypes = [C.c_int32, C.c_int64]
+        L.consensus_error_workspace_bytes.restype = C.c_int64
+        L.consensus_error.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_int64, C.c_void_p]
+        L.consensus_error.restype = C.c_int32
+        L.ceca_last_error.restype = C.c_char_p
+        L.ceca_last_hip_error.restype = C.c_int32
+        L.ceca_set_option.argtypes = [C.c_int32, C.c_int32]
+        L.ceca_set_option.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise CecaError(int(rc), lib().ceca_last_error().decode())
+    return int(rc)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    h = int(stream.cuda_stream)
+    return h if h else None
+
+
+def ceca_tau(n: int) -> int:
+    return _check(lib().ceca_tau(n))
+
+
+def ceca_schedule(n: int, r: int, port: int) -> Tuple[Round, List[int]]:
+    """(round description, 0-based receive-from map) of round r."""
+    rd = Round()
+    peer = (C.c_int32 * max(n, 1))()
+    _check(lib().ceca_schedule(n, r, port, C.byref(rd), peer))
+    return rd, list(peer)
+
+
+def ceca_gossip_round(S_in, S_out, n: int, d: int, r: int, port: int, ld: Optional[int] = None, stream=None) -> None:
+    """S_in, S_out: device float32 tensors holding 2n rows of ld floats (x rows, then y rows)."""
+    ld = int(S_in.stride(0)) if ld is None else ld
+    _check(lib().ceca_gossip_round(_ptr(S_in), _ptr(S_out), n, d, ld, r, port, _stream(stream)))
+
+
+def dsgd_ceca_workspace_bytes(n: int, d: int, loss: Loss) -> int:
+    return _check(lib().dsgd_ceca_workspace_bytes(n, d, C.byref(loss)))
+
+
+def dsgd_ceca_step(S_in, S_out, n: int, d: int, loss: Loss, batch_idx, lr: float, r: int, port: int,
+                   workspace=None, ld: Optional[int] = None, stream=None) -> None:
+    ld = int(S_in.stride(0)) if ld is None else ld
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().dsgd_ceca_step(_ptr(S_in), _ptr(S_out), n, d, ld, C.byref(loss), _ptr(batch_idx), lr, r, port,
+                                _ptr(workspace), wbytes, _stream(stream)))
+
+
+def consensus_error_workspace_bytes(n: int, d: int) -> int:
+    return _check(lib().consensus_error_workspace_bytes(n, d))
+
+
+def consensus_error(X, n: int, d: int, out, xbar=None, workspace=None, ld: Optional[int] = None, stream=None) -> None:
+    """out: device float64 tensor of 5; see include/ceca.h for its layout."""
+    ld = int(X.stride(0)) if ld is None else ld
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().consensus_error(_ptr(X), n, d, ld, _ptr(out), _ptr(xbar), _ptr(workspace), wbytes, _stream(stream)))
+
+
+def ceca_set_option(option: int, value: int) -> None:
+    _check(lib().ceca_set_option(option, value))
+
+
+def make_minibatch_loss(kind: int, A, t, N: int, B: int) -> Loss:
+    """A: device (n, N, lda) float32, t: device (n, N) float32."""
+    return Loss(kind=kind, N=N, B=B, seed=0, k=0, noise_std=0.0, A=_ptr(A), lda=int(A.stride(-2)), t=_ptr(t),
+                c=None, ldc=0)
+
+
+def make_quad_center_loss(c, noise_std: float, seed: int, k: int = 0) -> Loss:
+    """c: device (n, ldc) float32 centres."""
+    return Loss(kind=LOSS_QUAD_CENTER, N=0, B=0, seed=seed & 0xFFFFFFFF, k=k & 0xFFFFFFFF, noise_std=noise_std,
+                A=None, lda=0, t=None, c=_ptr(c), ldc=int(c.stride(0)))

@@ -1,0 +1,362 @@
+// C ABI of the DSGD-CECA hot path: argument checking, round schedule, launch shapes.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <numeric>
+
+#include "ceca.h"
+#include "launch.h"
+#include "schedule.h"
+
+namespace {
+
+thread_local char g_msg[256] = "";
+thread_local int32_t g_hip = 0;
+std::atomic<int32_t> g_opt_segment{0};
+std::atomic<int32_t> g_opt_unroll{0};
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_msg, sizeof g_msg, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int32_t hip_fail(hipError_t e, const char* what) {
+  g_hip = (int32_t)e;
+  (void)hipGetLastError();   // clear the sticky launch error so later calls start clean
+  return fail(CECA_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+inline bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a0 < b0 + (uintptr_t)nb && b0 < a0 + (uintptr_t)na;
+}
+
+// Shared checks of the two state-updating calls.  On success fills `rd` (left zeroed with n = 1).
+int32_t check_state_call(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, int32_t r,
+                         int32_t port, ceca_round_t* rd) {
+  if (!S_in || !S_out) return fail(CECA_EINVAL, "null state pointer");
+  if (n < 1) return fail(CECA_EINVAL, "n = %d: need at least one agent", n);
+  if (d < 1 || ld < d) return fail(CECA_EINVAL, "need 1 <= d <= ld (d = %lld, ld = %lld)", (long long)d, (long long)ld);
+  if (port != 1 && port != 2) return fail(CECA_EINVAL, "port = %d: must be 1 or 2", port);
+  const int32_t tau = ceca::tau_of(n);
+  if (n == 1 ? r != 0 : (r < 0 || r >= tau)) return fail(CECA_EINVAL, "round r = %d outside [0, tau = %d)", r, tau);
+  if (port == 1 && n > 1 && (n & 1)) return fail(CECA_EODD1P, "one-port CECA needs an even number of agents (n = %d)", n);
+  const int64_t bytes = 2 * (int64_t)n * ld * (int64_t)sizeof(float);
+  const bool same = (const void*)S_in == (const void*)S_out;
+  if (overlaps(S_in, bytes, S_out, bytes) && !(same && (port == 1 || n == 1)))
+    return fail(CECA_EINVAL, "S_out overlaps S_in: only a one-port round may run in place");
+  *rd = ceca_round_t{};
+  rd->n = n;
+  if (n > 1) ceca::fill_round(n, r, port, rd);
+  return CECA_OK;
+}
+
+// Chain shape for the round: which cycles the walk has and how they are cut into stretches.
+void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups, int unroll, ceca::ChainArgs* a) {
+  a->n = n;
+  if (n == 1) {
+    // a lone agent: one closed stretch of one row; weights make x+ = x - lr e, and y+ follows the call
+    a->stride = 0; a->cyc_len = 1; a->segs_per_cycle = 1; a->seg_len = 1; a->c0_mul = 1;
+    return;
+  }
+  a->stride = rd.shift;
+  if (port == 1) {
+    // pairs (2j, 2j + shift): closed two-row cycles starting at the even rows (Eq. (7))
+    a->cyc_len = 2; a->segs_per_cycle = 1; a->seg_len = 2; a->c0_mul = 2;
+    return;
+  }
+  const int32_t g = std::gcd(n, rd.shift);   // a shift by s splits the ring into gcd(n, s) cycles
+  const int32_t len = n / g;
+  a->cyc_len = len;
+  a->c0_mul = 1;
+  const int64_t tiles = (groups + (int64_t)ceca::kBlock * unroll - 1) / ((int64_t)ceca::kBlock * unroll);
+  int32_t seg_len = g_opt_segment.load();
+  if (seg_len <= 0) {
+    // enough workgroups to keep every CU's wave slots busy, stretches of at least 4 and at most 32 rows
+    const int64_t want_blocks = 8192;
+    int64_t segs = (want_blocks + tiles * g - 1) / (tiles * g);
+    const int64_t max_segs = len / 4 > 0 ? len / 4 : 1;
+    if (segs > max_segs) segs = max_segs;
+    const int64_t min_segs = (len + 31) / 32;
+    if (segs < min_segs) segs = min_segs;
+    if (segs < 1) segs = 1;
+    seg_len = (int32_t)((len + segs - 1) / segs);
+  }
+  if (seg_len > len) seg_len = len;
+  a->seg_len = seg_len;
+  a->segs_per_cycle = (len + seg_len - 1) / seg_len;
+}
+
+int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ceca_round_t& rd, int32_t port,
+                  hipStream_t st) {
+  int unroll = g_opt_unroll.load();
+  if (unroll != 2) unroll = 1;
+  const int64_t d4 = can_vec ? d / 4 : 0;
+  if (d4 > 0) {
+    a.col0 = 0;
+    a.ngroups = d4;
+    shape_chain(rd, a.n, port, d4, unroll, &a);
+    const hipError_t e = ceca::launch_chain(a, mode, true, unroll, st);
+    if (e != hipSuccess) return hip_fail(e, "chain kernel launch");
+  }
+  const int64_t rest = d - 4 * d4;
+  if (rest > 0) {
+    a.col0 = 4 * d4;
+    a.ngroups = rest;
+    shape_chain(rd, a.n, port, rest, 1, &a);
+    const hipError_t e = ceca::launch_chain(a, mode, false, 1, st);
+    if (e != hipSuccess) return hip_fail(e, "chain kernel launch (scalar columns)");
+  }
+  return CECA_OK;
+}
+
+void set_weights(const ceca_round_t& rd, int32_t n, bool gossip_only, ceca::ChainArgs* a) {
+  if (n == 1) {
+    // x+ = x - lr e;  y+ = y for a gossip "round" of one agent, y+ = x+ for a training step
+    a->a = 1.0f; a->ap = 0.0f;
+    a->b = gossip_only ? 1.0f : 0.0f; a->bp = gossip_only ? 0.0f : 1.0f;
+    a->exch_y = 0; a->read_y = gossip_only ? 1 : 0;
+    return;
+  }
+  a->a = rd.a; a->ap = rd.a_peer; a->b = rd.b; a->bp = rd.b_peer;
+  a->exch_y = rd.exchange_y;
+  a->read_y = (rd.b_num != 0) ? 1 : 0;
+}
+
+struct GemvPlan {
+  int64_t ldv, v_bytes, partial_bytes;
+  int32_t nchunks_max;
+};
+
+GemvPlan gemv_plan(int32_t n, int64_t d, int32_t B) {
+  GemvPlan p;
+  p.ldv = round_up(d, 4);
+  p.v_bytes = round_up((int64_t)n * p.ldv * (int64_t)sizeof(float), 256);
+  const int64_t scalar_chunk = (int64_t)ceca::kBlock * ceca::kChunkGroups;     // the narrowest chunk in use
+  p.nchunks_max = (int32_t)((d + scalar_chunk - 1) / scalar_chunk);
+  p.partial_bytes = round_up((int64_t)n * p.nchunks_max * B * (int64_t)sizeof(float), 256);
+  return p;
+}
+
+int32_t check_loss(const ceca_loss_t* loss, int64_t d, bool need_batch, const int32_t* batch_idx) {
+  if (!loss) return fail(CECA_EINVAL, "null loss");
+  switch (loss->kind) {
+    case CECA_LOSS_LSQ:
+    case CECA_LOSS_LOGISTIC:
+      if (loss->N < 1 || loss->B < 1 || loss->B > 64)
+        return fail(CECA_EINVAL, "need N >= 1 and 1 <= B <= 64 (N = %d, B = %d)", loss->N, loss->B);
+      if (!loss->A || !loss->t || loss->lda < d) return fail(CECA_EINVAL, "minibatch loss needs A, t and lda >= d");
+      if (need_batch && !batch_idx) return fail(CECA_EINVAL, "minibatch loss needs batch_idx");
+      return CECA_OK;
+    case CECA_LOSS_QUAD_CENTER:
+      if (!loss->c || loss->ldc < d) return fail(CECA_EINVAL, "quadratic-centre loss needs c and ldc >= d");
+      if (!(loss->noise_std >= 0.0f)) return fail(CECA_EINVAL, "noise_std must be >= 0");
+      return CECA_OK;
+    default:
+      return fail(CECA_EINVAL, "unknown loss kind %d", loss->kind);
+  }
+}
+
+struct ConsPlan {
+  int64_t ntiles;
+  int32_t agent_groups, agents_per_group, dev_agents;
+  int64_t off_norm, off_devpart, off_dev2, total;
+};
+
+ConsPlan cons_plan(int32_t n, int64_t d) {
+  ConsPlan p;
+  p.ntiles = (d + ceca::kConsTile - 1) / ceca::kConsTile;
+  // column sums: slice the agents when there are too few column tiles to fill the device
+  int64_t want = (1024 + p.ntiles - 1) / p.ntiles;
+  if (want > (n + 3) / 4) want = (n + 3) / 4;
+  if (want < 1) want = 1;
+  p.agents_per_group = (int32_t)((n + want - 1) / want);
+  p.agent_groups = (n + p.agents_per_group - 1) / p.agents_per_group;
+  // deviations: one workgroup walks dev_agents rows of its column tile with the mean in registers
+  int64_t rows = (4096 + p.ntiles - 1) / p.ntiles;      // wanted workgroups along the agents
+  int64_t per = (n + rows - 1) / rows;
+  if (per < 1) per = 1;
+  while ((n + per - 1) / per > 65535) ++per;
+  p.dev_agents = (int32_t)per;
+  int64_t off = round_up((int64_t)p.agent_groups * d * 8, 256);
+  p.off_norm = off;     off += round_up(p.ntiles * 8, 256);
+  p.off_devpart = off;  off += round_up((int64_t)n * p.ntiles * 8, 256);
+  p.off_dev2 = off;     off += round_up((int64_t)n * 8, 256);
+  p.total = off;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ceca_last_error(void) { return g_msg; }
+int32_t ceca_last_hip_error(void) { return g_hip; }
+
+int32_t ceca_set_option(int32_t option, int32_t value) {
+  switch (option) {
+    case CECA_OPT_SEGMENT:
+      if (value < 0) return fail(CECA_EINVAL, "segment length must be >= 0");
+      g_opt_segment.store(value);
+      return CECA_OK;
+    case CECA_OPT_UNROLL:
+      if (value < 0 || value > 2) return fail(CECA_EINVAL, "unroll must be 0, 1 or 2");
+      g_opt_unroll.store(value);
+      return CECA_OK;
+    default:
+      return fail(CECA_EINVAL, "unknown option %d", option);
+  }
+}
+
+int32_t ceca_tau(int32_t n) {
+  if (n < 1) return fail(CECA_EINVAL, "n = %d: need at least one agent", n);
+  return ceca::tau_of(n);
+}
+
+int32_t ceca_schedule(int32_t n, int32_t r, int32_t port, ceca_round_t* out, int32_t* peer) {
+  if (n < 2) return fail(CECA_EINVAL, "n = %d: a schedule needs at least two agents", n);
+  if (port != 1 && port != 2) return fail(CECA_EINVAL, "port = %d: must be 1 or 2", port);
+  const int32_t tau = ceca::tau_of(n);
+  if (r < 0 || r >= tau) return fail(CECA_EINVAL, "round r = %d outside [0, tau = %d)", r, tau);
+  if (port == 1 && (n & 1)) return fail(CECA_EODD1P, "one-port CECA needs an even number of agents (n = %d)", n);
+  ceca_round_t rd;
+  ceca::fill_round(n, r, port, &rd);
+  if (out) *out = rd;
+  if (peer)
+    for (int32_t i = 0; i < n; ++i) peer[i] = ceca::peer_of(rd, i);
+  return CECA_OK;
+}
+
+int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, int32_t r,
+                          int32_t port, void* hip_stream) {
+  ceca_round_t rd;
+  const int32_t rc = check_state_call(S_in, S_out, n, d, ld, r, port, &rd);
+  if (rc != CECA_OK) return rc;
+  ceca::ChainArgs a{};
+  a.xin = S_in;  a.yin = S_in + (int64_t)n * ld;
+  a.xout = S_out; a.yout = S_out + (int64_t)n * ld;
+  a.ld = ld;
+  a.n = n;
+  set_weights(rd, n, /*gossip_only=*/true, &a);
+  const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
+  return run_chain(a, ceca::MODE_GOSSIP, d, can_vec, rd, port, (hipStream_t)hip_stream);
+}
+
+int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss) {
+  if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
+  const int32_t rc = check_loss(loss, d, false, nullptr);
+  if (rc != CECA_OK) return rc;
+  if (loss->kind == CECA_LOSS_QUAD_CENTER) return 0;
+  const GemvPlan p = gemv_plan(n, d, loss->B);
+  return p.v_bytes + p.partial_bytes;
+}
+
+int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, const ceca_loss_t* loss,
+                       const int32_t* batch_idx, float lr, int32_t r, int32_t port, void* workspace,
+                       int64_t workspace_bytes, void* hip_stream) {
+  ceca_round_t rd;
+  int32_t rc = check_state_call(S_in, S_out, n, d, ld, r, port, &rd);
+  if (rc != CECA_OK) return rc;
+  rc = check_loss(loss, d, true, batch_idx);
+  if (rc != CECA_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+
+  ceca::ChainArgs a{};
+  a.xin = S_in;  a.yin = S_in + (int64_t)n * ld;
+  a.xout = S_out; a.yout = S_out + (int64_t)n * ld;
+  a.ld = ld;
+  a.n = n;
+  a.lr = lr;
+  set_weights(rd, n, /*gossip_only=*/false, &a);
+  const bool state_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
+
+  if (loss->kind == CECA_LOSS_QUAD_CENTER) {
+    const int64_t sbytes = 2 * (int64_t)n * ld * 4, cbytes = (int64_t)n * loss->ldc * 4;
+    if (overlaps(loss->c, cbytes, S_out, sbytes)) return fail(CECA_EINVAL, "centres overlap S_out");
+    a.aux = loss->c;
+    a.ldaux = loss->ldc;
+    a.noise_std = loss->noise_std;
+    a.seed = loss->seed;
+    a.k = loss->k;
+    const bool can_vec = state_vec && aligned16(loss->c) && loss->ldc % 4 == 0;
+    return run_chain(a, ceca::MODE_QUAD, d, can_vec, rd, port, st);
+  }
+
+  // GEMV-shaped losses: margins -> messages v (workspace) -> combine
+  if (n > 65535) return fail(CECA_EINVAL, "minibatch losses support at most 65535 agents");
+  const GemvPlan p = gemv_plan(n, d, loss->B);
+  if (!workspace || workspace_bytes < p.v_bytes + p.partial_bytes)
+    return fail(CECA_EWORKSPACE, "workspace of %lld bytes needed, %lld given", (long long)(p.v_bytes + p.partial_bytes),
+                (long long)(workspace ? workspace_bytes : 0));
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(CECA_EWORKSPACE, "workspace must be 256-byte aligned");
+  if (overlaps(workspace, p.v_bytes + p.partial_bytes, S_out, 2 * (int64_t)n * ld * 4) ||
+      overlaps(workspace, p.v_bytes + p.partial_bytes, S_in, 2 * (int64_t)n * ld * 4))
+    return fail(CECA_EINVAL, "workspace overlaps the state");
+
+  ceca::GemvArgs g{};
+  g.zin = a.exch_y ? a.yin : a.xin;
+  g.ld = ld;
+  g.A = loss->A;  g.lda = loss->lda;  g.t = loss->t;
+  g.batch_idx = batch_idx;
+  g.v = reinterpret_cast<float*>(workspace);
+  g.ldv = p.ldv;
+  g.partial = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + p.v_bytes);
+  g.d = d;
+  g.n = n;  g.N = loss->N;  g.B = loss->B;  g.kind = loss->kind;
+  g.lr = lr;
+  const bool gemv_vec = aligned16(S_in) && ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
+  g.chunk_cols = ceca::kBlock * ceca::kChunkGroups * (gemv_vec ? 4 : 1);
+  g.nchunks = (int32_t)((d + g.chunk_cols - 1) / g.chunk_cols);
+  hipError_t e = ceca::launch_margins(g, gemv_vec, st);
+  if (e != hipSuccess) return hip_fail(e, "margins kernel launch");
+  e = ceca::launch_halfstep(g, gemv_vec, st);
+  if (e != hipSuccess) return hip_fail(e, "half-step kernel launch");
+
+  a.aux = g.v;
+  a.ldaux = g.ldv;
+  return run_chain(a, ceca::MODE_FROMV, d, state_vec, rd, port, st);
+}
+
+int64_t consensus_error_workspace_bytes(int32_t n, int64_t d) {
+  if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
+  return cons_plan(n, d).total;
+}
+
+int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double* out, float* xbar_or_null,
+                        void* workspace, int64_t workspace_bytes, void* hip_stream) {
+  if (!X || !out) return fail(CECA_EINVAL, "null pointer");
+  if (n < 1 || d < 1 || ld < d) return fail(CECA_EINVAL, "need n >= 1 and 1 <= d <= ld");
+  const ConsPlan p = cons_plan(n, d);
+  if (!workspace || workspace_bytes < p.total)
+    return fail(CECA_EWORKSPACE, "workspace of %lld bytes needed, %lld given", (long long)p.total,
+                (long long)(workspace ? workspace_bytes : 0));
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(CECA_EWORKSPACE, "workspace must be 256-byte aligned");
+  char* w = reinterpret_cast<char*>(workspace);
+  ceca::ConsensusArgs c{};
+  c.X = X;  c.ld = ld;  c.d = d;  c.n = n;
+  c.agent_groups = p.agent_groups;
+  c.agents_per_group = p.agents_per_group;
+  c.dev_agents = p.dev_agents;
+  c.ntiles = p.ntiles;
+  c.colsum = reinterpret_cast<double*>(w);
+  c.normpart = reinterpret_cast<double*>(w + p.off_norm);
+  c.devpart = reinterpret_cast<double*>(w + p.off_devpart);
+  c.dev2 = reinterpret_cast<double*>(w + p.off_dev2);
+  c.out = out;
+  c.xbar = xbar_or_null;
+  const bool vec = aligned16(X) && ld % 4 == 0 && d % 4 == 0;
+  const hipError_t e = ceca::launch_consensus(c, vec, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "consensus kernels launch");
+  return CECA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,565 @@
+// gfx950 kernels of the DSGD-CECA hot path.
+//
+// Layout: the state is 2n rows of ld floats (x rows then y rows); a workgroup is 256 threads
+// (4 wavefronts of 64) and every thread owns 16-byte column groups, so each row access of a
+// workgroup is one contiguous 4 KiB run.
+//
+// Chain walk.  In a round every row i needs the message of exactly one other row, peer(i), and
+// peer is a permutation (Eqs. (5)-(7)): following i -> (i + stride) mod n visits rows in the
+// order in which each one's message is needed by the next.  A thread therefore walks a stretch of
+// such a cycle for its columns, keeping the message of the row it just finished in registers for
+// the row it visits next, and every row is read from memory once per round instead of twice.
+// A stretch that covers a whole cycle ("closed") holds its first row's terms until the walk comes
+// back round; an open stretch fetches only the message of the row before its first one.
+// One-port rounds are the closed two-row case of the same walk.
+#include <hip/hip_runtime.h>
+
+#include "ceca.h"
+#include "launch.h"
+
+namespace ceca {
+
+typedef float vf4 __attribute__((ext_vector_type(4)));
+
+template <int VEC> struct VecOf;
+template <> struct VecOf<4> { using T = vf4; };
+template <> struct VecOf<1> { using T = float; };
+
+template <typename V> __device__ __forceinline__ V ld_stream(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+}
+template <typename V> __device__ __forceinline__ void st_stream(float* p, V v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
+}
+template <typename V> __device__ __forceinline__ V ld_plain(const float* p) {
+  return *reinterpret_cast<const V*>(p);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Counter-based Gaussian noise (definition in ceca.h): one 32-bit word per uniform, Box-Muller
+// on column pairs.  Transcendentals use the hardware's log2 / sin / cos (arguments in turns).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t mix32(uint32_t h) {
+  h ^= h >> 16; h *= 0x7feb352du;
+  h ^= h >> 15; h *= 0x846ca68bu;
+  h ^= h >> 16;
+  return h;
+}
+__device__ __forceinline__ uint32_t noise_word(uint32_t c, uint32_t k0, uint32_t k1) {
+  uint32_t h = c ^ k0;
+  h ^= h >> 16; h *= 0x7feb352du;
+  h ^= h >> 15; h += k1; h *= 0x846ca68bu;
+  h ^= h >> 16;
+  return h;
+}
+struct NoiseKeys { uint32_t k0, k1; };
+__device__ __forceinline__ NoiseKeys noise_keys(uint32_t seed, uint32_t k, uint32_t agent) {
+  NoiseKeys nk;
+  nk.k0 = mix32(mix32(seed + 0x9e3779b9u * k) ^ agent);
+  nk.k1 = mix32(nk.k0 + 0x85ebca6bu);
+  return nk;
+}
+__device__ __forceinline__ void normal_pair(uint32_t q, NoiseKeys nk, float& e0, float& e1) {
+  const uint32_t w1 = noise_word(2u * q, nk.k0, nk.k1);
+  const uint32_t w2 = noise_word(2u * q + 1u, nk.k0, nk.k1);
+  const float u1 = (float)((w1 >> 8) + 1u) * 0x1p-24f;   // (0, 1], exact in fp32
+  const float u2 = (float)(w2 >> 8) * 0x1p-24f;          // [0, 1), exact in fp32
+  // -2 ln u1 = (-2 ln 2) log2 u1
+  const float rad = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u1));
+  e0 = rad * __builtin_amdgcn_cosf(u2);
+  e1 = rad * __builtin_amdgcn_sinf(u2);
+}
+template <typename V> __device__ __forceinline__ V noise_group(int64_t col, NoiseKeys nk);
+template <> __device__ __forceinline__ vf4 noise_group<vf4>(int64_t col, NoiseKeys nk) {
+  vf4 e;
+  float a, b;
+  const uint32_t q = (uint32_t)(col >> 1);     // col is a multiple of 4 on this path
+  normal_pair(q, nk, a, b);
+  e.x = a; e.y = b;
+  normal_pair(q + 1u, nk, a, b);
+  e.z = a; e.w = b;
+  return e;
+}
+template <> __device__ __forceinline__ float noise_group<float>(int64_t col, NoiseKeys nk) {
+  float a, b;
+  normal_pair((uint32_t)(col >> 1), nk, a, b);
+  return (col & 1) ? b : a;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Chain-walk kernel: gossip round, fused quadratic-centre step, and combine-from-messages.
+// ---------------------------------------------------------------------------------------------
+template <typename V, int MODE, bool READ_Y> struct Raw { V x, y, aux; };
+
+template <typename V, int MODE, bool READ_Y>
+__device__ __forceinline__ Raw<V, MODE, READ_Y> load_raw(const ChainArgs& A, int agent, int64_t col) {
+  Raw<V, MODE, READ_Y> r;
+  const int64_t off = (int64_t)agent * A.ld + col;
+  r.x = ld_stream<V>(A.xin + off);
+  if (READ_Y) r.y = ld_stream<V>(A.yin + off); else r.y = V(0.0f);
+  if (MODE != MODE_GOSSIP) r.aux = ld_stream<V>(A.aux + (int64_t)agent * A.ldaux + col); else r.aux = V(0.0f);
+  return r;
+}
+
+// Self terms xs = x - lr e, ys = y - lr e and message v = z - lr e of one agent (Eqs. (8), (9)).
+template <typename V, int MODE, bool EXCH_Y, bool READ_Y>
+__device__ __forceinline__ void agent_terms(const ChainArgs& A, const Raw<V, MODE, READ_Y>& r, int agent,
+                                            int64_t col, V& xs, V& ys, V& v) {
+  // no fused multiply-add here or in message_only: a message must have the same bits whether its
+  // own stretch or a neighbouring one computes it, so results do not depend on the launch shape
+#pragma clang fp contract(off)
+  const V z = EXCH_Y ? r.y : r.x;
+  if (MODE == MODE_GOSSIP) {
+    xs = r.x; ys = r.y; v = z;
+  } else if (MODE == MODE_QUAD) {
+    V e = z - r.aux;
+    if (A.noise_std != 0.0f) e += A.noise_std * noise_group<V>(col, noise_keys(A.seed, A.k, (uint32_t)agent));
+    const V ge = A.lr * e;
+    xs = r.x - ge; ys = r.y - ge; v = z - ge;
+  } else {  // MODE_FROMV: aux = v, so -lr e = v - z
+    v = r.aux;
+    const V dz = v - z;
+    xs = EXCH_Y ? r.x + dz : v;
+    ys = EXCH_Y ? v : r.y + dz;
+  }
+}
+
+// w * self + wp * msg, with one fixed rounding order wherever it is evaluated.
+__device__ __forceinline__ float combine(float w, float self, float wp, float msg) {
+#pragma clang fp contract(off)
+  const float t = wp * msg;
+  return __builtin_fmaf(w, self, t);
+}
+__device__ __forceinline__ vf4 combine(float w, vf4 self, float wp, vf4 msg) {
+  vf4 o;
+  o.x = combine(w, self.x, wp, msg.x); o.y = combine(w, self.y, wp, msg.y);
+  o.z = combine(w, self.z, wp, msg.z); o.w = combine(w, self.w, wp, msg.w);
+  return o;
+}
+
+// Message of an agent whose own update belongs to another chain stretch.
+template <typename V, int MODE, bool EXCH_Y>
+__device__ __forceinline__ V message_only(const ChainArgs& A, int agent, int64_t col) {
+#pragma clang fp contract(off)
+  const int64_t off = (int64_t)agent * A.ld + col;
+  if (MODE == MODE_FROMV) return ld_plain<V>(A.aux + (int64_t)agent * A.ldaux + col);
+  const V z = ld_plain<V>((EXCH_Y ? A.yin : A.xin) + off);
+  if (MODE == MODE_GOSSIP) return z;
+  V e = z - ld_plain<V>(A.aux + (int64_t)agent * A.ldaux + col);
+  if (A.noise_std != 0.0f) e += A.noise_std * noise_group<V>(col, noise_keys(A.seed, A.k, (uint32_t)agent));
+  const V ge = A.lr * e;
+  return z - ge;
+}
+
+template <int VEC, int MODE, bool EXCH_Y, bool READ_Y, int UNR>
+__global__ __launch_bounds__(kBlock) void chain_kernel(const ChainArgs A) {
+  using V = typename VecOf<VEC>::T;
+  using R = Raw<V, MODE, READ_Y>;
+
+  // which stretch of which cycle this workgroup walks; column tiles vary fastest across the grid
+  const uint32_t seg = blockIdx.x / A.tiles;
+  const uint32_t tile = blockIdx.x - seg * A.tiles;
+  const int cyc = (int)(seg / (uint32_t)A.segs_per_cycle);
+  const int q = (int)seg - cyc * A.segs_per_cycle;
+  const int t0 = q * A.seg_len;
+  const int len = min(A.seg_len, A.cyc_len - t0);
+  const bool closed = (A.segs_per_cycle == 1);
+  int c = (int)(((int64_t)cyc * A.c0_mul + (int64_t)t0 * A.stride) % A.n);
+
+  int64_t col[UNR];
+  bool on[UNR];
+#pragma unroll
+  for (int u = 0; u < UNR; ++u) {
+    const int64_t g = (int64_t)tile * (kBlock * UNR) + u * kBlock + threadIdx.x;
+    on[u] = g < A.ngroups;
+    col[u] = A.col0 + g * VEC;
+  }
+
+  V vprev[UNR], xs0[UNR], ys0[UNR];
+  R cur[UNR];
+  const int c_first = c;
+  int k = 0;
+  if (closed) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (on[u]) {
+        R r0 = load_raw<V, MODE, READ_Y>(A, c, col[u]);
+        agent_terms<V, MODE, EXCH_Y, READ_Y>(A, r0, c, col[u], xs0[u], ys0[u], vprev[u]);
+      }
+    k = 1;
+    c += A.stride; if (c >= A.n) c -= A.n;
+  } else {
+    int pred = c - A.stride; if (pred < 0) pred += A.n;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (on[u]) vprev[u] = message_only<V, MODE, EXCH_Y>(A, pred, col[u]);
+  }
+
+  if (k < len) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (on[u]) cur[u] = load_raw<V, MODE, READ_Y>(A, c, col[u]);
+  }
+  for (; k < len; ++k) {
+    int cn = c + A.stride; if (cn >= A.n) cn -= A.n;
+    R nxt[UNR];
+    if (k + 1 < len) {
+#pragma unroll
+      for (int u = 0; u < UNR; ++u)
+        if (on[u]) nxt[u] = load_raw<V, MODE, READ_Y>(A, cn, col[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (on[u]) {
+        V xs, ys, v;
+        agent_terms<V, MODE, EXCH_Y, READ_Y>(A, cur[u], c, col[u], xs, ys, v);
+        const int64_t off = (int64_t)c * A.ld + col[u];
+        st_stream<V>(A.xout + off, combine(A.a, xs, A.ap, vprev[u]));
+        st_stream<V>(A.yout + off, READ_Y ? combine(A.b, ys, A.bp, vprev[u]) : A.bp * vprev[u]);
+        vprev[u] = v;
+      }
+    if (k + 1 < len) {
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) cur[u] = nxt[u];
+    }
+    c = cn;
+  }
+  if (closed) {
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (on[u]) {
+        const int64_t off = (int64_t)c_first * A.ld + col[u];
+        st_stream<V>(A.xout + off, combine(A.a, xs0[u], A.ap, vprev[u]));
+        st_stream<V>(A.yout + off, READ_Y ? combine(A.b, ys0[u], A.bp, vprev[u]) : A.bp * vprev[u]);
+      }
+  }
+}
+
+template <int VEC, int MODE, int UNR>
+static hipError_t launch_chain_t(ChainArgs a, hipStream_t st) {
+  const int64_t per_block = (int64_t)kBlock * UNR;
+  const int64_t tiles = (a.ngroups + per_block - 1) / per_block;
+  const int64_t ncyc = (int64_t)a.n / a.cyc_len;   // cycles are equal-length and cover all agents
+  const int64_t blocks = tiles * ncyc * a.segs_per_cycle;
+  // the runtime addresses at most 2^32 threads per launch
+  if (tiles < 1 || blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
+  a.tiles = (uint32_t)tiles;
+  dim3 grid((unsigned)blocks), block(kBlock);
+  if (a.exch_y) {
+    // y travels only when delta_r = 0, and then b = 1/2: y is always read
+    chain_kernel<VEC, MODE, true, true, UNR><<<grid, block, 0, st>>>(a);
+  } else if (a.read_y) {
+    chain_kernel<VEC, MODE, false, true, UNR><<<grid, block, 0, st>>>(a);
+  } else {
+    chain_kernel<VEC, MODE, false, false, UNR><<<grid, block, 0, st>>>(a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int unroll, hipStream_t st) {
+  if (a.ngroups <= 0) return hipSuccess;
+#define CECA_CHAIN(M)                                                                      \
+  do {                                                                                     \
+    if (!vec4) return launch_chain_t<1, M, 1>(a, st);                                      \
+    return unroll == 2 ? launch_chain_t<4, M, 2>(a, st) : launch_chain_t<4, M, 1>(a, st); \
+  } while (0)
+  switch (mode) {
+    case MODE_GOSSIP: CECA_CHAIN(MODE_GOSSIP);
+    case MODE_QUAD: CECA_CHAIN(MODE_QUAD);
+    case MODE_FROMV: CECA_CHAIN(MODE_FROMV);
+  }
+#undef CECA_CHAIN
+  return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Minibatch gradients of the GEMV-shaped losses: margins a_ij . z_i, then e_i and the message.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float dot_v(vf4 a, vf4 b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }
+__device__ __forceinline__ float dot_v(float a, float b) { return a * b; }
+
+// partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col]
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
+  using V = typename VecOf<VEC>::T;
+  __shared__ float red[kBlock / 64][64];
+  const int agent = blockIdx.y;
+  const int chunk = blockIdx.x;
+  const int64_t c_lo = (int64_t)chunk * G.chunk_cols;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  V z[kChunkGroups];
+  int64_t col[kChunkGroups];
+  bool on[kChunkGroups];
+#pragma unroll
+  for (int u = 0; u < kChunkGroups; ++u) {
+    col[u] = c_lo + ((int64_t)u * kBlock + threadIdx.x) * VEC;
+    on[u] = col[u] + VEC <= G.d;
+    z[u] = on[u] ? ld_plain<V>(G.zin + (int64_t)agent * G.ld + col[u]) : V(0.0f);
+  }
+  const int32_t* idx = G.batch_idx + (int64_t)agent * G.B;
+  for (int j0 = 0; j0 < G.B; j0 += 4) {
+    float acc[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      acc[jj] = 0.0f;
+      if (j0 + jj < G.B) {
+        const float* row = G.A + ((int64_t)agent * G.N + idx[j0 + jj]) * G.lda;
+#pragma unroll
+        for (int u = 0; u < kChunkGroups; ++u)
+          if (on[u]) acc[jj] += dot_v(ld_plain<V>(row + col[u]), z[u]);
+      }
+    }
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const float s = wave_sum(acc[jj]);
+      if (lane == 0 && j0 + jj < G.B) red[wave][j0 + jj] = s;
+    }
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < G.B) {
+    float s = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) s += red[w][threadIdx.x];
+    G.partial[((int64_t)agent * G.nchunks + chunk) * G.B + threadIdx.x] = s;
+  }
+}
+
+// v_i = z_i - lr * e_i with e_i = sum_j coef_j a_ij; coef_j folds the loss derivative and the 1/B.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
+  using V = typename VecOf<VEC>::T;
+  __shared__ float coef[64];
+  __shared__ int32_t rowid[64];
+  const int agent = blockIdx.y;
+  if ((int)threadIdx.x < G.B) {
+    const int j = threadIdx.x;
+    float m = 0.0f;
+    for (int ch = 0; ch < G.nchunks; ++ch) m += G.partial[((int64_t)agent * G.nchunks + ch) * G.B + j];
+    const int32_t row = G.batch_idx[(int64_t)agent * G.B + j];
+    const float t = G.t[(int64_t)agent * G.N + row];
+    float cf;
+    if (G.kind == CECA_LOSS_LSQ) {
+      cf = m - t;
+    } else {
+      // -t * sigma(-t m) with sigma(-u) = 1 / (1 + e^u); e^u = inf gives 0, e^u = 0 gives 1
+      cf = -t / (1.0f + expf(t * m));
+    }
+    coef[j] = cf / (float)G.B;
+    rowid[j] = row;
+  }
+  __syncthreads();
+  const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+  if (col + VEC > G.d) return;
+  V e = V(0.0f);
+  const float* base = G.A + (int64_t)agent * G.N * G.lda + col;
+  for (int j0 = 0; j0 < G.B; j0 += 4) {
+    V r[4];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+      r[jj] = (j0 + jj < G.B) ? ld_plain<V>(base + (int64_t)rowid[j0 + jj] * G.lda) : V(0.0f);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj)
+      if (j0 + jj < G.B) e += coef[j0 + jj] * r[jj];
+  }
+  const V z = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
+  *reinterpret_cast<V*>(G.v + (int64_t)agent * G.ldv + col) = z - G.lr * e;
+}
+
+hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st) {
+  if (g.nchunks < 1 || g.n > 65535) return hipErrorInvalidConfiguration;
+  dim3 grid((unsigned)g.nchunks, (unsigned)g.n), block(kBlock);
+  if (vec4) margins_kernel<4><<<grid, block, 0, st>>>(g);
+  else margins_kernel<1><<<grid, block, 0, st>>>(g);
+  return hipGetLastError();
+}
+
+hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st) {
+  const int vec = vec4 ? 4 : 1;
+  const int64_t groups = (g.d + vec - 1) / vec;
+  const int64_t gx = (groups + kBlock - 1) / kBlock;
+  if (gx < 1 || gx > 0x7fffffffLL || g.n > 65535) return hipErrorInvalidConfiguration;
+  dim3 grid((unsigned)gx, (unsigned)g.n), block(kBlock);
+  if (vec4) halfstep_kernel<4><<<grid, block, 0, st>>>(g);
+  else halfstep_kernel<1><<<grid, block, 0, st>>>(g);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Consensus observables: fp64 column mean, then per-agent squared distance to it.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void acc4(double (&s)[4], vf4 v) { s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w; }
+__device__ __forceinline__ void acc4(double (&s)[4], float v) { s[0] += v; }
+
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void colsum_kernel(const ConsensusArgs C) {
+  using V = typename VecOf<VEC>::T;
+  const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+  if (col + VEC > C.d) return;
+  const int grp = blockIdx.y;
+  const int i_lo = grp * C.agents_per_group;
+  const int i_hi = min(C.n, i_lo + C.agents_per_group);
+  double s[4] = {0.0, 0.0, 0.0, 0.0};
+  int i = i_lo;
+  for (; i + 4 <= i_hi; i += 4) {
+    V r[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r[q] = ld_plain<V>(C.X + (int64_t)(i + q) * C.ld + col);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc4(s, r[q]);
+  }
+  for (; i < i_hi; ++i) acc4(s, ld_plain<V>(C.X + (int64_t)i * C.ld + col));
+  double* dst = C.colsum + (int64_t)grp * C.d + col;
+#pragma unroll
+  for (int q = 0; q < VEC; ++q) dst[q] = s[q];
+}
+
+// slice 0 of colsum <- mean; optional fp32 copy; per-workgroup partial of ||xbar||^2
+__global__ __launch_bounds__(kBlock) void mean_kernel(const ConsensusArgs C) {
+  __shared__ double red[kBlock / 64];
+  double sq = 0.0;
+  const int64_t base = (int64_t)blockIdx.x * kConsTile;
+  for (int q = 0; q < (int)(kConsTile / kBlock); ++q) {
+    const int64_t col = base + q * kBlock + threadIdx.x;
+    if (col < C.d) {
+      double s = 0.0;
+      for (int g = 0; g < C.agent_groups; ++g) s += C.colsum[(int64_t)g * C.d + col];
+      const double m = s / (double)C.n;
+      C.colsum[col] = m;
+      if (C.xbar) C.xbar[col] = (float)m;
+      sq += m * m;
+    }
+  }
+  sq = wave_sum(sq);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+    C.normpart[blockIdx.x] = t;
+  }
+}
+
+__device__ __forceinline__ double sqdev(vf4 v, const double (&m)[4]) {
+  const double a = (double)v.x - m[0], b = (double)v.y - m[1], c = (double)v.z - m[2], d = (double)v.w - m[3];
+  return a * a + b * b + c * c + d * d;
+}
+__device__ __forceinline__ double sqdev(float v, const double (&m)[4]) {
+  const double a = (double)v - m[0];
+  return a * a;
+}
+
+// devpart[agent][tile] = sum over the tile's columns of (x[agent][col] - mean[col])^2
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void dev_kernel(const ConsensusArgs C) {
+  using V = typename VecOf<VEC>::T;
+  __shared__ double red[kBlock / 64];
+  const int64_t tile = blockIdx.x;
+  constexpr int PER = (int)(kConsTile / kBlock) / VEC;   // column groups per thread
+  double m[PER][4];
+  int64_t col[PER];
+  bool on[PER];
+#pragma unroll
+  for (int p = 0; p < PER; ++p) {
+    col[p] = tile * kConsTile + ((int64_t)p * kBlock + threadIdx.x) * VEC;
+    on[p] = col[p] + VEC <= C.d;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) m[p][q] = (on[p] && q < VEC) ? C.colsum[col[p] + q] : 0.0;
+  }
+  const int i_lo = blockIdx.y * C.dev_agents;
+  const int i_hi = min(C.n, i_lo + C.dev_agents);
+  for (int i = i_lo; i < i_hi; ++i) {
+    double s = 0.0;
+#pragma unroll
+    for (int p = 0; p < PER; ++p)
+      if (on[p]) s += sqdev(ld_plain<V>(C.X + (int64_t)i * C.ld + col[p]), m[p]);
+    s = wave_sum(s);
+    __syncthreads();   // red[] of the previous agent has been consumed
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+      C.devpart[(int64_t)i * C.ntiles + tile] = t;
+    }
+  }
+}
+
+// dev2[agent] = sum over tiles of devpart[agent][tile]
+__global__ __launch_bounds__(kBlock) void devsum_kernel(const ConsensusArgs C) {
+  __shared__ double red[kBlock / 64];
+  const int i = blockIdx.x;
+  double s = 0.0;
+  for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) s += C.devpart[(int64_t)i * C.ntiles + t];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+    C.dev2[i] = t;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void finish_kernel(const ConsensusArgs C) {
+  __shared__ double r0[kBlock / 64], r1[kBlock / 64], r2[kBlock / 64], r3[kBlock / 64];
+  double frob = 0.0, resid = 0.0, mx = 0.0, nrm = 0.0;
+  for (int i = threadIdx.x; i < C.n; i += kBlock) {
+    const double d2 = C.dev2[i];
+    const double dv = sqrt(d2);
+    frob += d2; resid += dv; mx = fmax(mx, dv);
+  }
+  for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) nrm += C.normpart[t];
+  frob = wave_sum(frob); resid = wave_sum(resid); mx = wave_max(mx); nrm = wave_sum(nrm);
+  if ((threadIdx.x & 63) == 0) {
+    const int w = threadIdx.x >> 6;
+    r0[w] = frob; r1[w] = resid; r2[w] = mx; r3[w] = nrm;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double a = 0.0, b = 0.0, c = 0.0, d = 0.0;
+    for (int w = 0; w < kBlock / 64; ++w) { a += r0[w]; b += r1[w]; c = fmax(c, r2[w]); d += r3[w]; }
+    C.out[0] = a; C.out[1] = b; C.out[2] = c; C.out[3] = sqrt(d); C.out[4] = (double)C.n;
+  }
+}
+
+hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st) {
+  const int vec = vec4 ? 4 : 1;
+  const int64_t groups = (c.d + vec - 1) / vec;
+  const int64_t gx = (groups + kBlock - 1) / kBlock;
+  const int64_t dev_gy = ((int64_t)c.n + c.dev_agents - 1) / c.dev_agents;
+  if (gx > 0x7fffffffLL || c.ntiles > 0x7fffffffLL || c.agent_groups > 65535 || dev_gy > 65535 || c.n > 0x7fffffff)
+    return hipErrorInvalidConfiguration;
+  dim3 block(kBlock);
+  {
+    dim3 grid((unsigned)gx, (unsigned)c.agent_groups);
+    if (vec4) colsum_kernel<4><<<grid, block, 0, st>>>(c);
+    else colsum_kernel<1><<<grid, block, 0, st>>>(c);
+  }
+  mean_kernel<<<dim3((unsigned)c.ntiles), block, 0, st>>>(c);
+  {
+    dim3 grid((unsigned)c.ntiles, (unsigned)dev_gy);
+    if (vec4) dev_kernel<4><<<grid, block, 0, st>>>(c);
+    else dev_kernel<1><<<grid, block, 0, st>>>(c);
+  }
+  devsum_kernel<<<dim3((unsigned)c.n), block, 0, st>>>(c);
+  finish_kernel<<<dim3(1), block, 0, st>>>(c);
+  return hipGetLastError();
+}
+
+}  // namespace ceca

@@ -1,0 +1,84 @@
+// Internal interface between the C ABI (api.cpp) and the gfx950 kernels (kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace ceca {
+
+// What an agent contributes in one iteration (Algorithm 1): its "self" terms x_i - lr e_i and
+// y_i - lr e_i, and the message v_i = z_i - lr e_i it sends.
+enum ChainMode : int {
+  MODE_GOSSIP = 0,  // e = 0: self terms are x, y and the message is z             (Sec. 3 recursions)
+  MODE_QUAD = 1,    // e = z - c + noise, generated in the kernel                  (fused step)
+  MODE_FROMV = 2    // message v was written by the half-step kernel; x - lr e = x + (v - z)
+};
+
+struct ChainArgs {
+  const float* xin;   // row 0 of x in S_in
+  const float* yin;   // row 0 of y in S_in
+  float* xout;
+  float* yout;
+  int64_t ld;
+  const float* aux;   // MODE_QUAD: centres c;  MODE_FROMV: messages v
+  int64_t ldaux;
+  int64_t col0;       // first column of this launch
+  int64_t ngroups;    // VEC-wide column groups in this launch
+  uint32_t tiles;     // workgroups per chain stretch (set by the launcher)
+  int32_t n;
+  int32_t stride;     // walk step: the agent after c is (c + stride) mod n, and it receives from c
+  int32_t cyc_len;    // agents per cycle of the walk
+  int32_t segs_per_cycle;
+  int32_t seg_len;    // agents per chain segment (last segment of a cycle may be shorter)
+  int32_t c0_mul;     // first agent of cycle j is j * c0_mul
+  int32_t exch_y;     // 1: z = y
+  int32_t read_y;     // 0: b == 0, y rows are not read
+  float a, ap, b, bp;
+  float lr, noise_std;
+  uint32_t seed, k;
+};
+
+struct GemvArgs {
+  const float* zin;       // row 0 of the variable the gradient is taken at (x or y rows of S_in)
+  int64_t ld;
+  const float* A;
+  int64_t lda;
+  const float* t;
+  const int32_t* batch_idx;
+  float* partial;         // [n][nchunks][B] partial margins
+  float* v;               // [n][ldv] messages
+  int64_t ldv;
+  int64_t d;
+  int32_t n, N, B, kind;
+  int32_t nchunks;
+  int32_t chunk_cols;
+  float lr;
+};
+
+struct ConsensusArgs {
+  const float* X;
+  int64_t ld;
+  int64_t d;
+  int32_t n;
+  int32_t agent_groups;    // partial column sums are taken over this many slices of the agents
+  int32_t agents_per_group;
+  int32_t dev_agents;      // agents one workgroup of the deviation kernel walks
+  int64_t ntiles;          // column tiles of 1024
+  double* colsum;          // [agent_groups][d]; slice 0 becomes the fp64 mean
+  double* normpart;        // [ntiles] partial ||xbar||^2
+  double* devpart;         // [n][ntiles] partial squared deviations
+  double* dev2;            // [n]
+  double* out;             // 5 results
+  float* xbar;             // optional
+};
+
+hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int unroll, hipStream_t st);
+hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
+hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
+hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);
+
+constexpr int kBlock = 256;          // threads per workgroup: 4 wavefronts of 64
+constexpr int kChunkGroups = 2;      // column groups per thread in the margins kernel
+constexpr int64_t kConsTile = 1024;  // columns per workgroup in the consensus kernels
+
+}  // namespace ceca

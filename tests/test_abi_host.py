@@ -1,0 +1,87 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and its host-side
+schedule agrees bit for bit with the oracle's (no device call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import schedule as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def api():
+    import paper_2306_00256_amd as P
+    if not os.path.exists(P.library_path()):
+        from paper_2306_00256_amd import build
+        build.build_library(verbose=False)
+    P.lib()
+    return P
+
+
+def test_every_declared_symbol_is_exported(api):
+    hdr = open(os.path.join(ROOT, "include", "ceca.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(?:int32_t|int64_t|const char\*)\s+(\w+)\s*\(", hdr))
+    assert {"ceca_tau", "ceca_schedule", "ceca_gossip_round", "dsgd_ceca_step", "consensus_error"} <= declared
+    L = ctypes.CDLL(api.library_path())
+    for name in declared:
+        assert hasattr(L, name), name
+    from paper_2306_00256_amd import binding
+    assert declared == set(binding.EXPORTS)
+
+
+def test_struct_sizes_match_header(api):
+    from paper_2306_00256_amd import binding
+    assert ctypes.sizeof(binding.Round) == 12 * 4 + 4 * 4
+    assert ctypes.sizeof(binding.Loss) == 24 + 5 * 8
+
+
+@pytest.mark.parametrize("port", [1, 2])
+def test_schedule_bit_exact_against_oracle(api, port):
+    ns = list(range(2, 260)) + [1022, 1023, 1024, 1025, 1026, 4094, 4095, 4096]
+    for n in ns:
+        if port == 1 and n % 2:
+            continue
+        assert api.ceca_tau(n) == S.num_rounds(n)
+        dl, nr = S.delta_bits(n), S.window_sizes(n)
+        for r in range(S.num_rounds(n)):
+            rd, peer = api.ceca_schedule(n, r, port)
+            assert (rd.n, rd.tau, rd.r, rd.port) == (n, S.num_rounds(n), r, port)
+            assert rd.delta == dl[r] and rd.n_r == nr[r]
+            assert rd.exchange_y == (0 if S.exchanged(n, r) == "x" else 1)
+            a, b = S.weights(n, r)
+            assert a == S.Fraction(rd.a_num, rd.a_den) and b == S.Fraction(rd.b_num, rd.b_den)
+            assert peer == S.peers(n, r, port)
+            import numpy as np
+            assert rd.a == np.float32(float(a)) and rd.a_peer == np.float32(float(1 - a))
+            assert rd.b == np.float32(float(b)) and rd.b_peer == np.float32(float(1 - b))
+            assert rd.shift == (nr[r] + dl[r] if port == 2 else 2 * nr[r] + 1)
+
+
+def test_host_side_errors(api):
+    from paper_2306_00256_amd import binding as Bn
+    assert api.ceca_tau(1) == 0
+    with pytest.raises(api.CecaError) as e:
+        api.ceca_tau(0)
+    assert e.value.code == Bn.CECA_EINVAL
+    for n, r, port, code in [(5, 0, 1, Bn.CECA_EODD1P), (31, 2, 1, Bn.CECA_EODD1P), (6, 3, 2, Bn.CECA_EINVAL),
+                             (6, -1, 2, Bn.CECA_EINVAL), (6, 0, 3, Bn.CECA_EINVAL), (1, 0, 2, Bn.CECA_EINVAL)]:
+        with pytest.raises(api.CecaError) as e:
+            api.ceca_schedule(n, r, port)
+        assert e.value.code == code, (n, r, port)
+    # argument checks of the device calls fire before anything touches a device
+    L = api.lib()
+    assert L.ceca_gossip_round(None, None, 6, 8, 8, 0, 2, None) == Bn.CECA_EINVAL
+    buf = (ctypes.c_float * 64)()
+    p = ctypes.addressof(buf)
+    assert L.ceca_gossip_round(p, p, 4, 8, 8, 0, 2, None) == Bn.CECA_EINVAL          # 2-port in place
+    assert L.ceca_gossip_round(p, p, 3, 8, 8, 0, 1, None) == Bn.CECA_EODD1P
+    assert L.ceca_gossip_round(p, p, 4, 8, 4, 0, 1, None) == Bn.CECA_EINVAL          # ld < d
+    assert L.ceca_gossip_round(p, p, 4, 8, 8, 2, 1, None) == Bn.CECA_EINVAL          # r >= tau
+    assert b"in place" in L.ceca_last_error() or L.ceca_last_error() != b""
+    assert api.consensus_error_workspace_bytes(31, 25_557_032) > 0
+    with pytest.raises(api.CecaError):
+        api.ceca_set_option(99, 1)

@@ -1,0 +1,78 @@
+"""GPU parity: consensus_error through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import workloads as WL
+from oracle import consensus as OCONS
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2306_00256_amd as P
+    assert torch.cuda.is_available()
+    P.lib()
+    return torch, P
+
+
+def _consensus(torch, P, X, n, d, want_mean=True):
+    wb = P.consensus_error_workspace_bytes(n, d)
+    ws = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(5, dtype=torch.float64, device="cuda")
+    xbar = torch.zeros(d, dtype=torch.float32, device="cuda") if want_mean else None
+    P.consensus_error(X, n, d, out, xbar=xbar, workspace=ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), (xbar.cpu().numpy() if want_mean else None)
+
+
+@pytest.mark.parametrize("n,d", [(1, 5), (2, 1), (5, 1000), (6, 1027), (31, 4096), (100, 3000), (1023, 4096),
+                                 (3, 70001)])
+def test_matches_oracle(env, n, d):
+    torch, P = env
+    x = WL.initial_state(n, d, seed=n + d) * 3.0 + 1.5
+    X = torch.from_numpy(x).cuda()
+    got, xbar = _consensus(torch, P, X, n, d)
+    want = OCONS.consensus_error(x)
+    assert np.isclose(got[0], want["frob2"], rtol=1e-12)
+    assert np.isclose(got[1], want["residue"], rtol=1e-12)
+    assert np.isclose(got[2], want["max_dev"], rtol=1e-12)
+    assert np.isclose(got[3], want["mean_norm"], rtol=1e-12)
+    assert got[4] == n
+    assert np.allclose(xbar, want["mean"].astype(np.float32), rtol=0, atol=1e-7 * np.abs(want["mean"]).max())
+
+
+def test_padding_and_unaligned(env):
+    torch, P = env
+    n, d, ld = 7, 515, 523
+    x = WL.initial_state(n, d, seed=9)
+    flat = torch.full((n * ld + 1,), 7e7, dtype=torch.float32, device="cuda")
+    X = flat[1:].view(n, ld)
+    X[:, :d] = torch.from_numpy(x).cuda()
+    got, _ = _consensus(torch, P, X, n, d)
+    want = OCONS.consensus_error(x)
+    assert np.isclose(got[0], want["frob2"], rtol=1e-12) and np.isclose(got[3], want["mean_norm"], rtol=1e-12)
+
+
+def test_exact_consensus_reads_zero(env):
+    torch, P = env
+    row = WL.initial_state(1, 2048, seed=4)
+    X = torch.from_numpy(np.repeat(row, 9, axis=0)).cuda()
+    got, _ = _consensus(torch, P, X, 9, 2048, want_mean=False)
+    assert got[0] == 0.0 and got[1] == 0.0 and got[2] == 0.0
+    assert np.isclose(got[3], np.sqrt((row.astype(np.float64) ** 2).sum()), rtol=1e-13)
+
+
+def test_workspace_errors(env):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    X = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    out = torch.zeros(5, dtype=torch.float64, device="cuda")
+    with pytest.raises(P.CecaError) as e:
+        P.consensus_error(X, 4, 64, out, workspace=None)
+    assert e.value.code == Bn.CECA_EWORKSPACE
+    small = torch.empty(64, dtype=torch.uint8, device="cuda")
+    with pytest.raises(P.CecaError) as e:
+        P.consensus_error(X, 4, 64, out, workspace=small)
+    assert e.value.code == Bn.CECA_EWORKSPACE

@@ -1,0 +1,160 @@
+"""GPU parity: ceca_gossip_round through the C ABI against the fp64 oracle (mirror mode)."""
+import numpy as np
+import pytest
+
+import workloads as WL
+from oracle import ceca as OC
+from oracle import consensus as OCONS
+from oracle import schedule as OS
+from gpu_util import make_state, rel_err, split_state
+
+pytestmark = pytest.mark.gpu
+
+TOL_ROUND = 1e-5      # max relative error per gossip round
+TOL_CONS = 1e-6       # consensus error after tau rounds, relative to ||mean||
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2306_00256_amd as P
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    P.lib()
+    return torch, P
+
+
+def _run_rounds(torch, P, x0, port, rounds, ld=None, offset=0, inplace=False, y0=None):
+    n, d = x0.shape
+    S = make_state(torch, x0, y0=y0, ld=ld, offset=offset)
+    T = S if inplace else make_state(torch, np.zeros_like(x0), ld=ld, offset=offset)
+    tau = OS.num_rounds(n)
+    out = []
+    for k in range(rounds):
+        P.ceca_gossip_round(S, T, n, d, k % tau if tau else 0, port)
+        if not inplace:
+            S, T = T, S
+        out.append(split_state(S, n, d))
+    torch.cuda.synchronize()
+    return out, S
+
+
+@pytest.mark.parametrize("n,port", [(2, 1), (2, 2), (3, 2), (5, 2), (6, 1), (6, 2), (7, 2), (12, 1), (12, 2),
+                                    (31, 2), (30, 1), (100, 1), (100, 2), (130, 1), (257, 2)])
+@pytest.mark.parametrize("d", [1000, 2051])
+def test_rounds_match_oracle(env, n, port, d):
+    torch, P = env
+    x0 = WL.initial_state(n, d, seed=100 * n + port)
+    tau = OS.num_rounds(n)
+    got, _ = _run_rounds(torch, P, x0, port, tau + 1)
+    x = y = x0.astype(np.float64)
+    for k in range(tau + 1):
+        x, y = OC.gossip_round(x, y, k % tau, port, store32=True)
+        assert max(rel_err(got[k][0], x)) <= TOL_ROUND, (k, "x")
+        assert max(rel_err(got[k][1], y)) <= TOL_ROUND, (k, "y")
+        if k == tau - 1:
+            m = OCONS.consensus_error(got[k][0])
+            assert m["max_dev"] <= TOL_CONS * m["mean_norm"]
+            assert np.abs(got[k][0] - x0.astype(np.float64).mean(0)).max() <= 2e-6
+
+
+def test_worked_example_n6(env, golden):
+    """The paper's n = 6 tables (App. B.1.1) straight through the device path; J(0) = 0."""
+    torch, P = env
+    for port, name in [(2, "ceca_n6_values_2p.txt"), (1, "ceca_n6_values_1p.txt")]:
+        rows = {int(l.split()[0]): [float(v) for v in l.split()[1:]] for l in golden(name)}
+        u = np.array(rows[0][0::2])[:, None] * np.ones((1, 8))
+        got, _ = _run_rounds(torch, P, u, port, 3, y0=np.zeros_like(u))
+        for r in range(3):
+            assert np.allclose(got[r][0][:, 3], rows[r + 1][0::2], rtol=1e-6)
+            assert np.allclose(got[r][1][:, 5], rows[r + 1][1::2], rtol=1e-6)
+
+
+@pytest.mark.parametrize("n,port", [(5, 2), (6, 1), (100, 2)])
+def test_layout_variants_are_bit_identical(env, n, port):
+    """Padding (ld > d), an unaligned base, in-place one-port rounds and every launch shape give the
+    same bits, and padding columns are never written."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    d = 1543
+    x0 = WL.initial_state(n, d, seed=n)
+    tau = OS.num_rounds(n)
+    ref, _ = _run_rounds(torch, P, x0, port, tau)
+    for ld, off in [(d + 9, 0), (d, 1), (d + 1, 3), (1544, 0)]:
+        got, S = _run_rounds(torch, P, x0, port, tau, ld=ld, offset=off)
+        assert np.array_equal(got[-1][0], ref[-1][0]) and np.array_equal(got[-1][1], ref[-1][1])
+        if ld > d:
+            assert bool((S[:, d:] == 12345.0).all())
+    try:
+        for seg, unr in [(1, 1), (3, 2), (7, 1), (1000, 2), (0, 2)]:
+            P.ceca_set_option(Bn.OPT_SEGMENT, seg)
+            P.ceca_set_option(Bn.OPT_UNROLL, unr)
+            got, _ = _run_rounds(torch, P, x0, port, tau)
+            for k in range(tau):
+                assert np.array_equal(got[k][0], ref[k][0]) and np.array_equal(got[k][1], ref[k][1]), (seg, unr, k)
+    finally:
+        P.ceca_set_option(Bn.OPT_SEGMENT, 0)
+        P.ceca_set_option(Bn.OPT_UNROLL, 0)
+    if port == 1:
+        got, _ = _run_rounds(torch, P, x0, port, tau, inplace=True)
+        assert np.array_equal(got[-1][0], ref[-1][0]) and np.array_equal(got[-1][1], ref[-1][1])
+
+
+def test_degenerate_sizes(env):
+    torch, P = env
+    # one agent: a round is a copy
+    x0 = WL.initial_state(1, 37, seed=1)
+    y0 = WL.initial_state(1, 37, seed=2)
+    got, _ = _run_rounds(torch, P, x0, 2, 1, y0=y0)
+    assert np.array_equal(got[0][0], x0.astype(np.float64)) and np.array_equal(got[0][1], y0.astype(np.float64))
+    # one column, two agents
+    x0 = np.array([[1.0], [3.0]], dtype=np.float32)
+    for port in (1, 2):
+        got, _ = _run_rounds(torch, P, x0, port, 1)
+        assert np.array_equal(got[0][0], [[2.0], [2.0]])
+        assert np.array_equal(got[0][1], [[3.0], [1.0]])      # J = mean of the others
+    # round 0 never reads y: NaNs there must not leak
+    x0 = WL.initial_state(6, 64, seed=3)
+    got, _ = _run_rounds(torch, P, x0, 2, 3, y0=np.full((6, 64), np.nan, dtype=np.float32))
+    assert np.isfinite(got[0][0]).all() and np.isfinite(got[0][1]).all()
+    assert np.abs(got[2][0] - x0.astype(np.float64).mean(0)).max() < 1e-6
+
+
+def test_device_call_errors(env):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    S = torch.zeros((12, 16), dtype=torch.float32, device="cuda")
+    T = torch.zeros_like(S)
+    for args, code in [((S, S, 6, 16, 0, 2), Bn.CECA_EINVAL), ((S, T, 6, 16, 3, 2), Bn.CECA_EINVAL),
+                       ((S[:10], T[:10], 5, 16, 0, 1), Bn.CECA_EODD1P), ((S, T, 6, 0, 0, 2), Bn.CECA_EINVAL)]:
+        with pytest.raises(P.CecaError) as e:
+            P.ceca_gossip_round(*args)
+        assert e.value.code == code
+    # partial overlap is rejected for one port too
+    flat = torch.zeros(12 * 16 + 16, dtype=torch.float32, device="cuda")
+    with pytest.raises(P.CecaError):
+        P.ceca_gossip_round(flat[:192].view(12, 16), flat[16:208].view(12, 16), 6, 16, 0, 1)
+
+
+@pytest.mark.parametrize("port", [1, 2])
+def test_full_size_gossip_sampled_columns(env, port):
+    """n = 100, d = 2^20 in the launch shape the benchmark times; the oracle follows sampled columns
+    (columns are independent CECA instances), consensus is checked over everything."""
+    torch, P = env
+    n, d = 100, 1 << 20
+    S = torch.empty((2 * n, d), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, d), seed=2, out=S[:n])
+    S[n:] = S[:n]
+    T = torch.empty_like(S)
+    cols = WL.sample_columns(d, 2048, seed=2, tail=8)
+    tc = torch.from_numpy(cols).cuda()
+    x = y = S[:n][:, tc].cpu().numpy().astype(np.float64)
+    mean_all = S[:n].double().mean(0)
+    tau = OS.num_rounds(n)
+    for r in range(tau):
+        P.ceca_gossip_round(S, T, n, d, r, port)
+        S, T = T, S
+        x, y = OC.gossip_round(x, y, r, port, store32=True)
+        gx, gy = S[:n][:, tc].cpu().numpy(), S[n:][:, tc].cpu().numpy()
+        assert max(rel_err(gx, x)) <= TOL_ROUND and max(rel_err(gy, y)) <= TOL_ROUND, r
+    dev = (S[:n].double() - mean_all).norm(dim=1).max().item()
+    assert dev <= TOL_CONS * mean_all.norm().item()
