@@ -60,8 +60,17 @@ typedef struct {
  * iteration at z_i (Algorithm 1).  Minibatch losses average over the B sampled rows:
  *   LSQ         e_i = 1/B sum_j (a_ij . z_i - t_ij) a_ij          (least squares of Sec. 5)
  *   LOGISTIC    e_i = -1/B sum_j t_ij sigma(-t_ij a_ij . z_i) a_ij,  labels t_ij = +-1
- *   QUAD_CENTER e_i = z_i - c_i + noise_std * eps_i, eps_i ~ N(0, I) from a counter-based
- *               generator keyed by (seed, k, agent, column); its definition is in the design doc */
+ *   QUAD_CENTER e_i = z_i - c_i + noise_std * eps_i, eps_i ~ N(0, I) from the counter-based
+ *               generator below, keyed by (seed, k, agent, column).
+ *
+ * Noise generator (uint32 arithmetic, wrapping; agent and column 0-based):
+ *   mix(h):   h ^= h >> 16; h *= 0x7feb352d; h ^= h >> 15; h *= 0x846ca68b; h ^= h >> 16
+ *   keys:     k0 = mix(mix(seed + 0x9e3779b9 * k) ^ agent);  k1 = mix(k0 + 0x85ebca6b)
+ *   word(c):  h = c ^ k0; h ^= h >> 16; h *= 0x7feb352d; h ^= h >> 15; h += k1; h *= 0x846ca68b; h ^= h >> 16
+ *   pair q = column >> 1:  u1 = ((word(2q) >> 8) + 1) / 2^24 in (0, 1],  u2 = (word(2q+1) >> 8) / 2^24 in [0, 1)
+ *   Box-Muller: rad = sqrt(-2 ln u1);  eps[2q] = rad cos(2 pi u2),  eps[2q+1] = rad sin(2 pi u2)
+ * The integer part is exact; the device evaluates log / sqrt / sin / cos with its fp32 hardware units
+ * (absolute error of eps below 2e-5). */
 typedef struct {
   int32_t kind;         /* CECA_LOSS_* */
   int32_t N;            /* samples per agent (minibatch losses) */
@@ -87,8 +96,10 @@ int32_t ceca_schedule(int32_t n, int32_t r, int32_t port, ceca_round_t* out, int
 
 /* One gradient-free CECA round (Sec. 3.1 / 3.2 "Main recursions" with I = x, J = y):
  *   x_i+ = a x_i + (1-a) z_peer(i),   y_i+ = b y_i + (1-b) z_peer(i),   z = x or y by delta_r.
- * S_in, S_out: device, 2n rows of ld floats (d used).  port 2 needs S_out disjoint from S_in;
- * port 1 also accepts S_out == S_in (pairs are closed under the round).  n = 1 copies (r must be 0).
+ * S_in, S_out: device, 2n rows of ld floats (d used); S_out is either disjoint from S_in or S_in
+ * itself.  In place, a thread reads every row of a pair (port 1) or of a whole shift cycle (port 2)
+ * before it writes it; out of place, long two-port cycles are cut into shorter stretches, which
+ * exposes more parallelism.  Partial overlap is CECA_EINVAL.  n = 1 copies (r must be 0).
  * In round 0 (b = 0) the y rows of S_in are not read. */
 int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                           int32_t r, int32_t port, void* hip_stream);
@@ -128,9 +139,9 @@ int32_t ceca_last_hip_error(void);
 
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe against running calls):
  *   CECA_OPT_SEGMENT  agents a 2-port chain walks before it starts a new one (0 = library default)
- *   CECA_OPT_UNROLL   16-byte column groups per thread, 1 or 2 (0 = library default)
+ *   CECA_OPT_ROWS     state rows whose loads one thread keeps in flight: 1, 2, 4 or 8 (0 = library default)
  * Returns CECA_EINVAL for an unknown option or value. */
-enum { CECA_OPT_SEGMENT = 1, CECA_OPT_UNROLL = 2 };
+enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2 };
 int32_t ceca_set_option(int32_t option, int32_t value);
 
 #ifdef __cplusplus

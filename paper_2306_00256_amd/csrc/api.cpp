@@ -16,7 +16,7 @@ namespace {
 thread_local char g_msg[256] = "";
 thread_local int32_t g_hip = 0;
 std::atomic<int32_t> g_opt_segment{0};
-std::atomic<int32_t> g_opt_unroll{0};
+std::atomic<int32_t> g_opt_rows{0};
 
 int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -52,8 +52,8 @@ int32_t check_state_call(const float* S_in, float* S_out, int32_t n, int64_t d, 
   if (port == 1 && n > 1 && (n & 1)) return fail(CECA_EODD1P, "one-port CECA needs an even number of agents (n = %d)", n);
   const int64_t bytes = 2 * (int64_t)n * ld * (int64_t)sizeof(float);
   const bool same = (const void*)S_in == (const void*)S_out;
-  if (overlaps(S_in, bytes, S_out, bytes) && !(same && (port == 1 || n == 1)))
-    return fail(CECA_EINVAL, "S_out overlaps S_in: only a one-port round may run in place");
+  if (overlaps(S_in, bytes, S_out, bytes) && !same)
+    return fail(CECA_EINVAL, "S_out partially overlaps S_in");
   *rd = ceca_round_t{};
   rd->n = n;
   if (n > 1) ceca::fill_round(n, r, port, rd);
@@ -61,7 +61,7 @@ int32_t check_state_call(const float* S_in, float* S_out, int32_t n, int64_t d, 
 }
 
 // Chain shape for the round: which cycles the walk has and how they are cut into stretches.
-void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups, int unroll, ceca::ChainArgs* a) {
+void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups, bool in_place, ceca::ChainArgs* a) {
   a->n = n;
   if (n == 1) {
     // a lone agent: one closed stretch of one row; weights make x+ = x - lr e, and y+ follows the call
@@ -78,15 +78,16 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups
   const int32_t len = n / g;
   a->cyc_len = len;
   a->c0_mul = 1;
-  const int64_t tiles = (groups + (int64_t)ceca::kBlock * unroll - 1) / ((int64_t)ceca::kBlock * unroll);
-  int32_t seg_len = g_opt_segment.load();
+  const int64_t tiles = (groups + ceca::kBlock - 1) / ceca::kBlock;
+  int32_t seg_len = in_place ? len : g_opt_segment.load();   // in place only whole cycles are safe
   if (seg_len <= 0) {
-    // enough workgroups to keep every CU's wave slots busy, stretches of at least 4 and at most 32 rows
+    // enough workgroups to keep every CU's wave slots busy, stretches of at least 4 and at most 8 rows
+    // (measured: short stretches beat whole long cycles, the extra message read stays in cache)
     const int64_t want_blocks = 8192;
     int64_t segs = (want_blocks + tiles * g - 1) / (tiles * g);
     const int64_t max_segs = len / 4 > 0 ? len / 4 : 1;
     if (segs > max_segs) segs = max_segs;
-    const int64_t min_segs = (len + 31) / 32;
+    const int64_t min_segs = (len + 7) / 8;
     if (segs < min_segs) segs = min_segs;
     if (segs < 1) segs = 1;
     seg_len = (int32_t)((len + segs - 1) / segs);
@@ -98,22 +99,22 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups
 
 int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ceca_round_t& rd, int32_t port,
                   hipStream_t st) {
-  int unroll = g_opt_unroll.load();
-  if (unroll != 2) unroll = 1;
+  int rows = g_opt_rows.load();
+  if (rows == 0) rows = (mode == ceca::MODE_QUAD) ? 8 : 4;
   const int64_t d4 = can_vec ? d / 4 : 0;
   if (d4 > 0) {
     a.col0 = 0;
     a.ngroups = d4;
-    shape_chain(rd, a.n, port, d4, unroll, &a);
-    const hipError_t e = ceca::launch_chain(a, mode, true, unroll, st);
+    shape_chain(rd, a.n, port, d4, a.xin == a.xout, &a);
+    const hipError_t e = ceca::launch_chain(a, mode, true, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch");
   }
   const int64_t rest = d - 4 * d4;
   if (rest > 0) {
     a.col0 = 4 * d4;
     a.ngroups = rest;
-    shape_chain(rd, a.n, port, rest, 1, &a);
-    const hipError_t e = ceca::launch_chain(a, mode, false, 1, st);
+    shape_chain(rd, a.n, port, rest, a.xin == a.xout, &a);
+    const hipError_t e = ceca::launch_chain(a, mode, false, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch (scalar columns)");
   }
   return CECA_OK;
@@ -208,9 +209,10 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       if (value < 0) return fail(CECA_EINVAL, "segment length must be >= 0");
       g_opt_segment.store(value);
       return CECA_OK;
-    case CECA_OPT_UNROLL:
-      if (value < 0 || value > 2) return fail(CECA_EINVAL, "unroll must be 0, 1 or 2");
-      g_opt_unroll.store(value);
+    case CECA_OPT_ROWS:
+      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+        return fail(CECA_EINVAL, "rows in flight must be 0, 1, 2, 4 or 8");
+      g_opt_rows.store(value);
       return CECA_OK;
     default:
       return fail(CECA_EINVAL, "unknown option %d", option);

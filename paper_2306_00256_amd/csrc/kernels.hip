@@ -25,6 +25,7 @@ template <int VEC> struct VecOf;
 template <> struct VecOf<4> { using T = vf4; };
 template <> struct VecOf<1> { using T = float; };
 
+// State rows are touched once per round: stream them past the caches (nontemporal loads and stores).
 template <typename V> __device__ __forceinline__ V ld_stream(const float* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
 }
@@ -151,94 +152,96 @@ __device__ __forceinline__ V message_only(const ChainArgs& A, int agent, int64_t
   return z - ge;
 }
 
-template <int VEC, int MODE, bool EXCH_Y, bool READ_Y, int UNR>
+// Per-thread walk state: where the thread is on its cycle and the message of the row before.
+template <typename V> struct Walk {
+  int c;        // next row to visit
+  V vprev;      // message of the row visited last
+  V xs0, ys0;   // self terms of a closed stretch's first row, combined when the walk returns to it
+};
+
+template <typename V>
+__device__ __forceinline__ void put_row(const ChainArgs& A, int row, int64_t col, V xs, V ys, V msg, bool read_y) {
+  const int64_t off = (int64_t)row * A.ld + col;
+  st_stream<V>(A.xout + off, combine(A.a, xs, A.ap, msg));
+  st_stream<V>(A.yout + off, read_y ? combine(A.b, ys, A.bp, msg) : A.bp * msg);
+}
+
+// Q consecutive rows of the walk: all their loads are issued first, then the rows are finished in
+// order (only the message passes from one to the next).  FIRST marks the opening block of a closed
+// stretch, whose first row is held back instead of stored.
+template <typename V, int MODE, bool EXCH_Y, bool READ_Y, int Q, bool FIRST>
+__device__ __forceinline__ void walk_block(const ChainArgs& A, int64_t col, Walk<V>& w) {
+  Raw<V, MODE, READ_Y> raw[Q];
+  int row[Q];
+#pragma unroll
+  for (int j = 0; j < Q; ++j) {
+    row[j] = w.c;
+    w.c += A.stride;
+    if (w.c >= A.n) w.c -= A.n;
+  }
+#pragma unroll
+  for (int j = 0; j < Q; ++j) raw[j] = load_raw<V, MODE, READ_Y>(A, row[j], col);
+#pragma unroll
+  for (int j = 0; j < Q; ++j) {
+    V xs, ys, v;
+    agent_terms<V, MODE, EXCH_Y, READ_Y>(A, raw[j], row[j], col, xs, ys, v);
+    if (FIRST && j == 0) {
+      w.xs0 = xs; w.ys0 = ys;
+    } else {
+      put_row<V>(A, row[j], col, xs, ys, w.vprev, READ_Y);
+    }
+    w.vprev = v;
+  }
+}
+
+template <typename V, int MODE, bool EXCH_Y, bool READ_Y, int R, bool FIRST>
+__device__ __forceinline__ int walk_upto(const ChainArgs& A, int64_t col, Walk<V>& w, int remaining) {
+  // one block of min(R, remaining) rows; returns how many rows it took
+  if (remaining >= R) { walk_block<V, MODE, EXCH_Y, READ_Y, R, FIRST>(A, col, w); return R; }
+  if (R > 4 && remaining >= 4) { walk_block<V, MODE, EXCH_Y, READ_Y, 4, FIRST>(A, col, w); return 4; }
+  if (R > 2 && remaining >= 2) { walk_block<V, MODE, EXCH_Y, READ_Y, 2, FIRST>(A, col, w); return 2; }
+  walk_block<V, MODE, EXCH_Y, READ_Y, 1, FIRST>(A, col, w);
+  return 1;
+}
+
+template <int VEC, int MODE, bool EXCH_Y, bool READ_Y, int R>
 __global__ __launch_bounds__(kBlock) void chain_kernel(const ChainArgs A) {
   using V = typename VecOf<VEC>::T;
-  using R = Raw<V, MODE, READ_Y>;
 
   // which stretch of which cycle this workgroup walks; column tiles vary fastest across the grid
   const uint32_t seg = blockIdx.x / A.tiles;
   const uint32_t tile = blockIdx.x - seg * A.tiles;
+  const int64_t g = (int64_t)tile * kBlock + threadIdx.x;
+  if (g >= A.ngroups) return;          // no barriers below: lanes past the last column just leave
+  const int64_t col = A.col0 + g * VEC;
+
   const int cyc = (int)(seg / (uint32_t)A.segs_per_cycle);
   const int q = (int)seg - cyc * A.segs_per_cycle;
   const int t0 = q * A.seg_len;
-  const int len = min(A.seg_len, A.cyc_len - t0);
+  int remaining = min(A.seg_len, A.cyc_len - t0);
   const bool closed = (A.segs_per_cycle == 1);
-  int c = (int)(((int64_t)cyc * A.c0_mul + (int64_t)t0 * A.stride) % A.n);
 
-  int64_t col[UNR];
-  bool on[UNR];
-#pragma unroll
-  for (int u = 0; u < UNR; ++u) {
-    const int64_t g = (int64_t)tile * (kBlock * UNR) + u * kBlock + threadIdx.x;
-    on[u] = g < A.ngroups;
-    col[u] = A.col0 + g * VEC;
-  }
-
-  V vprev[UNR], xs0[UNR], ys0[UNR];
-  R cur[UNR];
-  const int c_first = c;
-  int k = 0;
+  Walk<V> w;
+  w.c = (int)(((int64_t)cyc * A.c0_mul + (int64_t)t0 * A.stride) % A.n);
+  const int c_first = w.c;
   if (closed) {
-#pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      if (on[u]) {
-        R r0 = load_raw<V, MODE, READ_Y>(A, c, col[u]);
-        agent_terms<V, MODE, EXCH_Y, READ_Y>(A, r0, c, col[u], xs0[u], ys0[u], vprev[u]);
-      }
-    k = 1;
-    c += A.stride; if (c >= A.n) c -= A.n;
+    remaining -= walk_upto<V, MODE, EXCH_Y, READ_Y, R, true>(A, col, w, remaining);
   } else {
-    int pred = c - A.stride; if (pred < 0) pred += A.n;
-#pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      if (on[u]) vprev[u] = message_only<V, MODE, EXCH_Y>(A, pred, col[u]);
+    int pred = w.c - A.stride;
+    if (pred < 0) pred += A.n;
+    w.vprev = message_only<V, MODE, EXCH_Y>(A, pred, col);
   }
-
-  if (k < len) {
-#pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      if (on[u]) cur[u] = load_raw<V, MODE, READ_Y>(A, c, col[u]);
+  while (remaining >= R) {
+    walk_block<V, MODE, EXCH_Y, READ_Y, R, false>(A, col, w);
+    remaining -= R;
   }
-  for (; k < len; ++k) {
-    int cn = c + A.stride; if (cn >= A.n) cn -= A.n;
-    R nxt[UNR];
-    if (k + 1 < len) {
-#pragma unroll
-      for (int u = 0; u < UNR; ++u)
-        if (on[u]) nxt[u] = load_raw<V, MODE, READ_Y>(A, cn, col[u]);
-    }
-#pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      if (on[u]) {
-        V xs, ys, v;
-        agent_terms<V, MODE, EXCH_Y, READ_Y>(A, cur[u], c, col[u], xs, ys, v);
-        const int64_t off = (int64_t)c * A.ld + col[u];
-        st_stream<V>(A.xout + off, combine(A.a, xs, A.ap, vprev[u]));
-        st_stream<V>(A.yout + off, READ_Y ? combine(A.b, ys, A.bp, vprev[u]) : A.bp * vprev[u]);
-        vprev[u] = v;
-      }
-    if (k + 1 < len) {
-#pragma unroll
-      for (int u = 0; u < UNR; ++u) cur[u] = nxt[u];
-    }
-    c = cn;
-  }
-  if (closed) {
-#pragma unroll
-    for (int u = 0; u < UNR; ++u)
-      if (on[u]) {
-        const int64_t off = (int64_t)c_first * A.ld + col[u];
-        st_stream<V>(A.xout + off, combine(A.a, xs0[u], A.ap, vprev[u]));
-        st_stream<V>(A.yout + off, READ_Y ? combine(A.b, ys0[u], A.bp, vprev[u]) : A.bp * vprev[u]);
-      }
-  }
+  while (remaining > 0) remaining -= walk_upto<V, MODE, EXCH_Y, READ_Y, R, false>(A, col, w, remaining);
+  if (closed) put_row<V>(A, c_first, col, w.xs0, w.ys0, w.vprev, READ_Y);
 }
 
-template <int VEC, int MODE, int UNR>
+template <int VEC, int MODE, int R>
 static hipError_t launch_chain_t(ChainArgs a, hipStream_t st) {
-  const int64_t per_block = (int64_t)kBlock * UNR;
-  const int64_t tiles = (a.ngroups + per_block - 1) / per_block;
+  const int64_t tiles = (a.ngroups + kBlock - 1) / kBlock;
   const int64_t ncyc = (int64_t)a.n / a.cyc_len;   // cycles are equal-length and cover all agents
   const int64_t blocks = tiles * ncyc * a.segs_per_cycle;
   // the runtime addresses at most 2^32 threads per launch
@@ -247,21 +250,26 @@ static hipError_t launch_chain_t(ChainArgs a, hipStream_t st) {
   dim3 grid((unsigned)blocks), block(kBlock);
   if (a.exch_y) {
     // y travels only when delta_r = 0, and then b = 1/2: y is always read
-    chain_kernel<VEC, MODE, true, true, UNR><<<grid, block, 0, st>>>(a);
+    chain_kernel<VEC, MODE, true, true, R><<<grid, block, 0, st>>>(a);
   } else if (a.read_y) {
-    chain_kernel<VEC, MODE, false, true, UNR><<<grid, block, 0, st>>>(a);
+    chain_kernel<VEC, MODE, false, true, R><<<grid, block, 0, st>>>(a);
   } else {
-    chain_kernel<VEC, MODE, false, false, UNR><<<grid, block, 0, st>>>(a);
+    chain_kernel<VEC, MODE, false, false, R><<<grid, block, 0, st>>>(a);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int unroll, hipStream_t st) {
+hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st) {
   if (a.ngroups <= 0) return hipSuccess;
-#define CECA_CHAIN(M)                                                                      \
-  do {                                                                                     \
-    if (!vec4) return launch_chain_t<1, M, 1>(a, st);                                      \
-    return unroll == 2 ? launch_chain_t<4, M, 2>(a, st) : launch_chain_t<4, M, 1>(a, st); \
+#define CECA_CHAIN(M)                                                   \
+  do {                                                                  \
+    if (!vec4) return launch_chain_t<1, M, 2>(a, st);                   \
+    switch (rows) {                                                     \
+      case 1: return launch_chain_t<4, M, 1>(a, st);                    \
+      case 2: return launch_chain_t<4, M, 2>(a, st);                    \
+      case 8: return launch_chain_t<4, M, 8>(a, st);                    \
+      default: return launch_chain_t<4, M, 4>(a, st);                   \
+    }                                                                   \
   } while (0)
   switch (mode) {
     case MODE_GOSSIP: CECA_CHAIN(MODE_GOSSIP);

@@ -72,7 +72,8 @@ struct ConsensusArgs {
   float* xbar;             // optional
 };
 
-hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int unroll, hipStream_t st);
+// rows: state rows whose loads a thread keeps in flight together (1, 2, 4 or 8)
+hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);

@@ -77,11 +77,12 @@ def test_host_side_errors(api):
     assert L.ceca_gossip_round(None, None, 6, 8, 8, 0, 2, None) == Bn.CECA_EINVAL
     buf = (ctypes.c_float * 64)()
     p = ctypes.addressof(buf)
-    assert L.ceca_gossip_round(p, p, 4, 8, 8, 0, 2, None) == Bn.CECA_EINVAL          # 2-port in place
+    assert L.ceca_gossip_round(p, p + 32, 2, 8, 8, 0, 2, None) == Bn.CECA_EINVAL     # partial overlap
+    assert L.ceca_gossip_round(p, p + 32, 2, 8, 8, 0, 1, None) == Bn.CECA_EINVAL
     assert L.ceca_gossip_round(p, p, 3, 8, 8, 0, 1, None) == Bn.CECA_EODD1P
     assert L.ceca_gossip_round(p, p, 4, 8, 4, 0, 1, None) == Bn.CECA_EINVAL          # ld < d
     assert L.ceca_gossip_round(p, p, 4, 8, 8, 2, 1, None) == Bn.CECA_EINVAL          # r >= tau
-    assert b"in place" in L.ceca_last_error() or L.ceca_last_error() != b""
+    assert b"outside" in L.ceca_last_error()
     assert api.consensus_error_workspace_bytes(31, 25_557_032) > 0
     with pytest.raises(api.CecaError):
         api.ceca_set_option(99, 1)

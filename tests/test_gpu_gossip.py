@@ -85,18 +85,19 @@ def test_layout_variants_are_bit_identical(env, n, port):
         if ld > d:
             assert bool((S[:, d:] == 12345.0).all())
     try:
-        for seg, unr in [(1, 1), (3, 2), (7, 1), (1000, 2), (0, 2)]:
+        for seg, unr in [(1, 1), (3, 2), (7, 4), (1000, 8), (0, 2), (5, 8)]:
             P.ceca_set_option(Bn.OPT_SEGMENT, seg)
-            P.ceca_set_option(Bn.OPT_UNROLL, unr)
+            P.ceca_set_option(Bn.OPT_ROWS, unr)
             got, _ = _run_rounds(torch, P, x0, port, tau)
             for k in range(tau):
                 assert np.array_equal(got[k][0], ref[k][0]) and np.array_equal(got[k][1], ref[k][1]), (seg, unr, k)
     finally:
         P.ceca_set_option(Bn.OPT_SEGMENT, 0)
-        P.ceca_set_option(Bn.OPT_UNROLL, 0)
-    if port == 1:
-        got, _ = _run_rounds(torch, P, x0, port, tau, inplace=True)
-        assert np.array_equal(got[-1][0], ref[-1][0]) and np.array_equal(got[-1][1], ref[-1][1])
+        P.ceca_set_option(Bn.OPT_ROWS, 0)
+    # in place: one-port pairs and whole two-port cycles read every row before they write it
+    got, _ = _run_rounds(torch, P, x0, port, tau, inplace=True)
+    for k in range(tau):
+        assert np.array_equal(got[k][0], ref[k][0]) and np.array_equal(got[k][1], ref[k][1])
 
 
 def test_degenerate_sizes(env):
@@ -124,15 +125,17 @@ def test_device_call_errors(env):
     from paper_2306_00256_amd import binding as Bn
     S = torch.zeros((12, 16), dtype=torch.float32, device="cuda")
     T = torch.zeros_like(S)
-    for args, code in [((S, S, 6, 16, 0, 2), Bn.CECA_EINVAL), ((S, T, 6, 16, 3, 2), Bn.CECA_EINVAL),
+    for args, code in [((S, T, 6, 16, -1, 2), Bn.CECA_EINVAL), ((S, T, 6, 16, 3, 2), Bn.CECA_EINVAL),
                        ((S[:10], T[:10], 5, 16, 0, 1), Bn.CECA_EODD1P), ((S, T, 6, 0, 0, 2), Bn.CECA_EINVAL)]:
         with pytest.raises(P.CecaError) as e:
             P.ceca_gossip_round(*args)
         assert e.value.code == code
-    # partial overlap is rejected for one port too
+    # partial overlap is rejected for either port
     flat = torch.zeros(12 * 16 + 16, dtype=torch.float32, device="cuda")
     with pytest.raises(P.CecaError):
         P.ceca_gossip_round(flat[:192].view(12, 16), flat[16:208].view(12, 16), 6, 16, 0, 1)
+    with pytest.raises(P.CecaError):
+        P.ceca_gossip_round(flat[:192].view(12, 16), flat[16:208].view(12, 16), 6, 16, 0, 2)
 
 
 @pytest.mark.parametrize("port", [1, 2])

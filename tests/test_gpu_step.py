@@ -64,13 +64,14 @@ def test_quad_center_run(env, n, port, d, ld, off):
     grad = OL.make_quad_center_grad(c, std, seed)
     cdev = torch.from_numpy(c).cuda()
     S = make_state(torch, x0, ld=ld, offset=off)
-    T = S if port == 1 else make_state(torch, np.zeros_like(x0), ld=ld, offset=off)
+    inplace = port == 1 or off == 1            # two-port rounds run in place too (whole cycles)
+    T = S if inplace else make_state(torch, np.zeros_like(x0), ld=ld, offset=off)
     x = y = x0.astype(np.float64)
     tau = OS.num_rounds(n)
     for k in range(iters):
         loss = Bn.make_quad_center_loss(cdev, std, seed, k)
         P.dsgd_ceca_step(S, T, n, d, loss, None, lr, k % tau, port)
-        if port == 2:
+        if not inplace:
             S, T = T, S
         x, y = OC.dsgd_ceca_step(x, y, k, port, lr, grad, store32=True)
     gx, gy = split_state(S, n, d)
@@ -87,9 +88,9 @@ def test_quad_center_launch_shapes_bit_identical(env):
     x0 = WL.initial_state(n, d, seed)
     outs = []
     try:
-        for seg, unr in [(0, 0), (1, 1), (5, 2), (31, 1), (64, 2)]:
+        for seg, unr in [(0, 0), (1, 1), (5, 2), (31, 8), (64, 4), (3, 8)]:
             P.ceca_set_option(Bn.OPT_SEGMENT, seg)
-            P.ceca_set_option(Bn.OPT_UNROLL, unr)
+            P.ceca_set_option(Bn.OPT_ROWS, unr)
             S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
             for k in range(5):
                 P.dsgd_ceca_step(S, T, n, d, Bn.make_quad_center_loss(c, 0.01, seed, k), None, 0.1, k % 5, 2)
@@ -97,7 +98,7 @@ def test_quad_center_launch_shapes_bit_identical(env):
             outs.append(S.cpu().numpy())
     finally:
         P.ceca_set_option(Bn.OPT_SEGMENT, 0)
-        P.ceca_set_option(Bn.OPT_UNROLL, 0)
+        P.ceca_set_option(Bn.OPT_ROWS, 0)
     for o in outs[1:]:
         assert np.array_equal(o, outs[0])
 
@@ -266,5 +267,5 @@ def test_step_errors(env):
     with pytest.raises(P.CecaError):
         P.dsgd_ceca_step(S, T, n, d, bad, idx, 0.1, 0, 2, workspace=ws)
     with pytest.raises(P.CecaError) as e:
-        P.dsgd_ceca_step(S, S, n, d, loss, idx, 0.1, 0, 2, workspace=ws)
+        P.dsgd_ceca_step(S, T, n, d, loss, idx, 0.1, 2, 2, workspace=ws)      # r >= tau
     assert e.value.code == Bn.CECA_EINVAL
