@@ -43,6 +43,11 @@ def _tau(n):
     return (n - 1).bit_length()
 
 
+def _ld(d):
+    """Leading dimension of the stacked state: rows start on 256-byte boundaries."""
+    return (d + 63) // 64 * 64
+
+
 class Timer:
     """HIP events on the stream the kernels are launched on (torch's current stream) + host clock."""
 
@@ -66,16 +71,17 @@ class Timer:
 
 def run_quad(torch, P, Bn, sp, steps, warmup):
     n, d, port = sp.n, sp.d, sp.port
-    c = torch.empty((n, d), dtype=torch.float32, device="cuda")
-    WL.device_normal((n, d), seed=sp.seed, out=c)
-    S = torch.zeros((2 * n, d), dtype=torch.float32, device="cuda")
+    ld = _ld(d)
+    c = torch.empty((n, ld), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, ld), seed=sp.seed, out=c)
+    S = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
     T = S if port == 1 else torch.empty_like(S)
     tau = _tau(n)
 
     def step(k):
         nonlocal S, T
         P.dsgd_ceca_step(S, T, n, d, Bn.make_quad_center_loss(c, sp.noise_std, sp.seed, k), None, sp.lr,
-                         k % tau, port)
+                         k % tau, port, ld=ld)
         if port == 2:
             S, T = T, S
 
@@ -89,15 +95,16 @@ def run_quad(torch, P, Bn, sp, steps, warmup):
 
 def run_gossip(torch, P, Bn, sp, steps, warmup):
     n, d, port = sp.n, sp.d, sp.port
-    S = torch.empty((2 * n, d), dtype=torch.float32, device="cuda")
-    WL.device_normal((n, d), seed=sp.seed, out=S[:n])
+    ld = _ld(d)
+    S = torch.empty((2 * n, ld), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, ld), seed=sp.seed, out=S[:n])
     S[n:] = S[:n]
     T = S if port == 1 else torch.empty_like(S)
     tau = _tau(n)
 
     def step(k):
         nonlocal S, T
-        P.ceca_gossip_round(S, T, n, d, k % tau, port)
+        P.ceca_gossip_round(S, T, n, d, k % tau, port, ld=ld)
         if port == 2:
             S, T = T, S
 
@@ -123,13 +130,14 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
     idx = torch.from_numpy(WL.batch_indices(n, N, B, nidx, sp.seed)).cuda()
     loss = Bn.make_minibatch_loss(Bn.LOSS_LSQ if sp.loss == "lsq" else Bn.LOSS_LOGISTIC, A, t, N, B)
     ws = torch.empty(P.dsgd_ceca_workspace_bytes(n, d, loss), dtype=torch.uint8, device="cuda")
-    S = torch.zeros((2 * n, d), dtype=torch.float32, device="cuda")
+    ld = _ld(d)
+    S = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
     T = S if port == 1 else torch.empty_like(S)
     tau = _tau(n)
 
     def step(k):
         nonlocal S, T
-        P.dsgd_ceca_step(S, T, n, d, loss, idx[k % nidx], sp.lr, k % tau, port, workspace=ws)
+        P.dsgd_ceca_step(S, T, n, d, loss, idx[k % nidx], sp.lr, k % tau, port, workspace=ws, ld=ld)
         if port == 2:
             S, T = T, S
 
@@ -192,6 +200,8 @@ def main():
     ap.add_argument("--workload", default="quad31_2p", choices=sorted(WL.SPECS))
     ap.add_argument("--others", action="store_true", help="also time the remaining workloads (reported under 'others')")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="first run one plain 1 GiB device copy (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all agents are simulated on one device); "
@@ -209,6 +219,14 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     main_res = measure(torch, P, Bn, args.workload, args.steps, args.warmup)
     sp = WL.SPECS[args.workload]
     out = {
@@ -220,7 +238,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "n_agents": sp.n, "d": sp.d, "port": sp.port, "loss": sp.loss,
-                   "lr": sp.lr, "state_bytes": 2 * sp.n * sp.d * 4},
+                   "lr": sp.lr, "ld": _ld(sp.d), "state_bytes": 2 * sp.n * _ld(sp.d) * 4},
         "roofline": {
             "bound": "hbm",
             "achieved": main_res["achieved_GBs"],

@@ -140,8 +140,10 @@ int32_t ceca_last_hip_error(void);
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe against running calls):
  *   CECA_OPT_SEGMENT  agents a 2-port chain walks before it starts a new one (0 = library default)
  *   CECA_OPT_ROWS     state rows whose loads one thread keeps in flight: 1, 2, 4 or 8 (0 = library default)
+ *   CECA_OPT_BAND     column tiles (of 1024 columns) per band of the launch order (0 = library default)
+ *   CECA_OPT_WG_PER_CU  cap on workgroups resident per compute unit, 2..8 (0 = library default)
  * Returns CECA_EINVAL for an unknown option or value. */
-enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2 };
+enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4 };
 int32_t ceca_set_option(int32_t option, int32_t value);
 
 #ifdef __cplusplus

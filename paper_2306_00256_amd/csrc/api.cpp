@@ -17,6 +17,8 @@ thread_local char g_msg[256] = "";
 thread_local int32_t g_hip = 0;
 std::atomic<int32_t> g_opt_segment{0};
 std::atomic<int32_t> g_opt_rows{0};
+std::atomic<int32_t> g_opt_band{0};
+std::atomic<int32_t> g_opt_wgs{0};
 
 int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -61,7 +63,7 @@ int32_t check_state_call(const float* S_in, float* S_out, int32_t n, int64_t d, 
 }
 
 // Chain shape for the round: which cycles the walk has and how they are cut into stretches.
-void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups, bool in_place, ceca::ChainArgs* a) {
+void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place, ceca::ChainArgs* a) {
   a->n = n;
   if (n == 1) {
     // a lone agent: one closed stretch of one row; weights make x+ = x - lr e, and y+ follows the call
@@ -78,20 +80,11 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups
   const int32_t len = n / g;
   a->cyc_len = len;
   a->c0_mul = 1;
-  const int64_t tiles = (groups + ceca::kBlock - 1) / ceca::kBlock;
-  int32_t seg_len = in_place ? len : g_opt_segment.load();   // in place only whole cycles are safe
-  if (seg_len <= 0) {
-    // enough workgroups to keep every CU's wave slots busy, stretches of at least 4 and at most 8 rows
-    // (measured: short stretches beat whole long cycles, the extra message read stays in cache)
-    const int64_t want_blocks = 8192;
-    int64_t segs = (want_blocks + tiles * g - 1) / (tiles * g);
-    const int64_t max_segs = len / 4 > 0 ? len / 4 : 1;
-    if (segs > max_segs) segs = max_segs;
-    const int64_t min_segs = (len + 7) / 8;
-    if (segs < min_segs) segs = min_segs;
-    if (segs < 1) segs = 1;
-    seg_len = (int32_t)((len + segs - 1) / segs);
-  }
+  // In place only whole cycles are safe.  Out of place, measurements on MI355X favour one-row
+  // stretches: the device then sweeps the rows of a column band one at a time (few concurrent DRAM
+  // streams), and the message a stretch re-reads is still in L2 from the stretch before it.
+  int32_t seg_len = in_place ? len : g_opt_segment.load();
+  if (seg_len <= 0) seg_len = 1;
   if (seg_len > len) seg_len = len;
   a->seg_len = seg_len;
   a->segs_per_cycle = (len + seg_len - 1) / seg_len;
@@ -100,12 +93,23 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, int64_t groups
 int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ceca_round_t& rd, int32_t port,
                   hipStream_t st) {
   int rows = g_opt_rows.load();
-  if (rows == 0) rows = (mode == ceca::MODE_QUAD) ? 8 : 4;
+  a.band = (uint32_t)g_opt_band.load();
+  a.wg_per_cu = g_opt_wgs.load();
+  const bool in_place = a.xin == a.xout;
+  const bool pairs = port == 1 || a.n == 1;
+  // rows in flight per thread: closed pairs and in-place cycles of the fused step like the fattest
+  // variant (it also runs fewer workgroups per CU); one-row stretches want more, lighter workgroups
+  if (rows == 0) rows = (mode == ceca::MODE_QUAD && (pairs || in_place)) ? 8 : 4;
+  // band: about 7-10 MB of traffic between a row's own read and its re-read as a message, so that the
+  // re-read hits L2 (32 MB over 8 XCDs; a tile and its successor land on the same XCD when the band
+  // is a multiple of 8)
+  // closed stretches re-read nothing: they sweep whole rows, one pair or cycle after the other
+  if (a.band == 0 && !(pairs || in_place)) a.band = (mode == ceca::MODE_QUAD) ? 256 : 512;
   const int64_t d4 = can_vec ? d / 4 : 0;
   if (d4 > 0) {
     a.col0 = 0;
     a.ngroups = d4;
-    shape_chain(rd, a.n, port, d4, a.xin == a.xout, &a);
+    shape_chain(rd, a.n, port, in_place, &a);
     const hipError_t e = ceca::launch_chain(a, mode, true, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch");
   }
@@ -113,7 +117,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   if (rest > 0) {
     a.col0 = 4 * d4;
     a.ngroups = rest;
-    shape_chain(rd, a.n, port, rest, a.xin == a.xout, &a);
+    shape_chain(rd, a.n, port, in_place, &a);
     const hipError_t e = ceca::launch_chain(a, mode, false, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch (scalar columns)");
   }
@@ -213,6 +217,14 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
         return fail(CECA_EINVAL, "rows in flight must be 0, 1, 2, 4 or 8");
       g_opt_rows.store(value);
+      return CECA_OK;
+    case CECA_OPT_WG_PER_CU:
+      if (value < 0 || value > 8) return fail(CECA_EINVAL, "workgroups per CU must be 0..8");
+      g_opt_wgs.store(value);
+      return CECA_OK;
+    case CECA_OPT_BAND:
+      if (value < 0) return fail(CECA_EINVAL, "band width must be >= 0");
+      g_opt_band.store(value);
       return CECA_OK;
     default:
       return fail(CECA_EINVAL, "unknown option %d", option);

@@ -208,9 +208,16 @@ template <int VEC, int MODE, bool EXCH_Y, bool READ_Y, int R>
 __global__ __launch_bounds__(kBlock) void chain_kernel(const ChainArgs A) {
   using V = typename VecOf<VEC>::T;
 
-  // which stretch of which cycle this workgroup walks; column tiles vary fastest across the grid
-  const uint32_t seg = blockIdx.x / A.tiles;
-  const uint32_t tile = blockIdx.x - seg * A.tiles;
+  // Which stretch of which cycle this workgroup walks.  Workgroups are numbered band by band: a band
+  // is `band` adjacent column tiles, and inside a band all tiles of one stretch come before the
+  // next stretch along the cycle.  The device then sweeps a few rows of one band at a time, and the
+  // message an open stretch re-reads was fetched by the stretch before it only moments earlier.
+  const uint32_t per_band = A.band * A.nsegs;
+  const uint32_t bnd = blockIdx.x / per_band;
+  const uint32_t rem = blockIdx.x - bnd * per_band;
+  const uint32_t width = min(A.band, A.tiles - bnd * A.band);     // the last band may be narrower
+  const uint32_t seg = rem / width;
+  const uint32_t tile = bnd * A.band + (rem - seg * width);
   const int64_t g = (int64_t)tile * kBlock + threadIdx.x;
   if (g >= A.ngroups) return;          // no barriers below: lanes past the last column just leave
   const int64_t col = A.col0 + g * VEC;
@@ -247,14 +254,23 @@ static hipError_t launch_chain_t(ChainArgs a, hipStream_t st) {
   // the runtime addresses at most 2^32 threads per launch
   if (tiles < 1 || blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
   a.tiles = (uint32_t)tiles;
+  a.nsegs = (uint32_t)(ncyc * a.segs_per_cycle);
+  if (a.band == 0 || a.band > a.tiles) a.band = a.tiles;
   dim3 grid((unsigned)blocks), block(kBlock);
+  // Unused dynamic LDS caps the workgroups resident on a CU (160 KiB of LDS each): fewer, fatter
+  // workgroups keep the rows the device touches at any moment few, which the memory system rewards.
+  size_t lds = 0;
+  if (a.wg_per_cu > 0) {
+    lds = (size_t)(160 * 1024 / a.wg_per_cu) & ~(size_t)1023;
+    if (lds > 64 * 1024) lds = 64 * 1024;
+  }
   if (a.exch_y) {
     // y travels only when delta_r = 0, and then b = 1/2: y is always read
-    chain_kernel<VEC, MODE, true, true, R><<<grid, block, 0, st>>>(a);
+    chain_kernel<VEC, MODE, true, true, R><<<grid, block, lds, st>>>(a);
   } else if (a.read_y) {
-    chain_kernel<VEC, MODE, false, true, R><<<grid, block, 0, st>>>(a);
+    chain_kernel<VEC, MODE, false, true, R><<<grid, block, lds, st>>>(a);
   } else {
-    chain_kernel<VEC, MODE, false, false, R><<<grid, block, 0, st>>>(a);
+    chain_kernel<VEC, MODE, false, false, R><<<grid, block, lds, st>>>(a);
   }
   return hipGetLastError();
 }

@@ -25,6 +25,9 @@ struct ChainArgs {
   int64_t col0;       // first column of this launch
   int64_t ngroups;    // VEC-wide column groups in this launch
   uint32_t tiles;     // workgroups per chain stretch (set by the launcher)
+  uint32_t nsegs;     // stretches over all cycles (set by the launcher)
+  uint32_t band;      // column tiles per band of the launch order (0 = all tiles in one band)
+  int32_t wg_per_cu;  // cap on resident workgroups per CU (0 = whatever fits)
   int32_t n;
   int32_t stride;     // walk step: the agent after c is (c + stride) mod n, and it receives from c
   int32_t cyc_len;    // agents per cycle of the walk
