@@ -26,12 +26,21 @@ import workloads as WL  # noqa: E402
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
 # Algorithmic HBM bytes per agent-parameter per call, fp32 state [x; y]: every distinct array element
-# moved once (x, y read; x+, y+ written; centres read once for the fused quadratic step).  The
-# "model" figure also charges the peer row as a separate read, as a row-gather kernel would pay it.
-BYTES = {
-    ("gossip", 1): (16.0, 16.0), ("gossip", 2): (16.0, 20.0),
-    ("quad_center", 1): (20.0, 20.0), ("quad_center", 2): (20.0, 28.0),
-}
+# moved once.  (read, read in round 0 where b = 0 and y is not needed, written)
+#   gossip round      x, y read (x only in round 0), x+, y+ written
+#   fused quad step   x, y, c read (x, c in round 0), x+, y+ written
+# The "gather model" figure also charges the peer row as a separate read, the way a plain row-gather
+# kernel pays it (+4 for gossip, +8 for the fused step with its centre row); the one-port pair kernel
+# and this build's chain walk do not pay it.
+ALG_BYTES = {"gossip": (8.0, 4.0, 8.0), "quad_center": (12.0, 8.0, 8.0)}
+GATHER_EXTRA = {("gossip", 1): 0.0, ("gossip", 2): 4.0, ("quad_center", 1): 0.0, ("quad_center", 2): 8.0}
+
+
+def chain_bytes(kind: str, port: int, rounds):
+    """Mean algorithmic and gather-model bytes per agent-parameter over the given round numbers."""
+    rd, rd0, wr = ALG_BYTES[kind]
+    alg = sum((rd0 if r == 0 else rd) + wr for r in rounds) / len(rounds)
+    return alg, alg + GATHER_EXTRA[(kind, port)]
 
 
 def minibatch_bytes(B: int):
@@ -90,7 +99,7 @@ def run_quad(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
-    return tm, 1, BYTES[("quad_center", port)]
+    return tm, 1, chain_bytes("quad_center", port, [k % tau for k in range(warmup, warmup + steps)])
 
 
 def run_gossip(torch, P, Bn, sp, steps, warmup):
@@ -113,7 +122,7 @@ def run_gossip(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
-    return tm, 1, BYTES[("gossip", port)]
+    return tm, 1, chain_bytes("gossip", port, [k % tau for k in range(warmup, warmup + steps)])
 
 
 def run_minibatch(torch, P, Bn, sp, steps, warmup):
@@ -167,29 +176,75 @@ def measure(torch, P, Bn, name, steps, warmup):
     }
 
 
+def measured_traffic(name, steps, warmup):
+    """Mean HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if any."""
+    path = os.path.join(ROOT, "profiles", f"{name}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    kv = {}
+    with open(path) as f:
+        for ln in f:
+            if ln.strip() and not ln.startswith("#"):
+                k, v = ln.split()
+                kv[k] = float(v)
+    sp = WL.SPECS[name]
+    tau = _tau(sp.n)
+    r0 = kv["round0_fetch_kib"] * kv["fetch_scale"] + kv["round0_write_kib"] * kv["write_scale"]
+    rr = kv["round_fetch_kib"] * kv["fetch_scale"] + kv["round_write_kib"] * kv["write_scale"]
+    rounds = [k % tau for k in range(warmup, warmup + steps)]
+    return 1024.0 * sum(r0 if r == 0 else rr for r in rounds) / len(rounds)
+
+
 def cpu_baseline(sp, target_s=12.0):
-    """The fp64 oracle on this host's cores, on a bounded column sample of the same workload."""
+    """The fp64 oracle, as it stands, on this host's cores, on a bounded sample of the same workload."""
     from oracle import ceca as OC
     from oracle import losses as OL
 
-    n = sp.n
-    cols_n = 1 << 18
-    cols = np.arange(cols_n, dtype=np.int64)
-    c = WL.quad_centers(n, cols_n, sp.seed)
-    grad = OL.make_quad_center_grad(c, sp.noise_std, sp.seed, columns=cols)
-    x = y = np.zeros((n, cols_n))
+    n, port = sp.n, sp.port
+    if sp.loss in ("quad_center", "none"):
+        # columns are independent instances of the recursion: sample the first 2^18 of them, all agents
+        width = min(sp.d, 1 << 18)
+        cols = np.arange(width, dtype=np.int64)
+        if sp.loss == "quad_center":
+            grad = OL.make_quad_center_grad(WL.quad_centers(n, width, sp.seed), sp.noise_std, sp.seed, columns=cols)
+            x = y = np.zeros((n, width))
+        else:
+            grad = None
+            x = y = WL.initial_state(n, width, sp.seed).astype(np.float64)
+        what = f"the first {width} of {sp.d} columns, all {n} agents"
+        max_iters = sp.iters or 10 ** 9
+    else:
+        # minibatch losses couple the columns: keep d and B, cut the agent count and the sample pool
+        n = min(n, 127)
+        N = min(sp.N, 64)
+        if sp.name.startswith("logistic1023"):
+            A, t, _ = WL.logistic_data_sparse(n, N, sp.d, sp.seed)
+        elif sp.loss == "lsq":
+            A, t, _ = WL.lsq_data(n, N, sp.d, sp.seed)
+        else:
+            A, t, _ = WL.logistic_data_hetero(n, N, sp.d, sp.seed)
+        max_iters = min(sp.iters, 2000)
+        idx = WL.batch_indices(n, N, sp.B, max_iters, sp.seed)
+        grad = OL.make_minibatch_grad(sp.loss, A, t, idx)
+        x = y = np.zeros((n, sp.d))
+        width = sp.d
+        what = f"{n} of {sp.n} agents, {N} of {sp.N} samples each, all {sp.d} columns"
+    tau = _tau(n)
     t0 = time.perf_counter()
     iters = 0
     while True:
-        x, y = OC.dsgd_ceca_step(x, y, iters, sp.port, sp.lr, grad, store32=True)
+        if grad is None:
+            x, y = OC.gossip_round(x, y, iters % tau, port, store32=True)
+        else:
+            x, y = OC.dsgd_ceca_step(x, y, iters, port, sp.lr, grad, store32=True)
         iters += 1
         el = time.perf_counter() - t0
-        if el > target_s or iters >= sp.iters:
+        if el > target_s or iters >= max_iters:
             break
-    threads = 1   # the oracle is numpy elementwise code: one thread
-    return {"value": n * cols_n * iters / el, "unit": "agent-param updates/s", "cores": threads, "kind": "oracle",
-            "sample": f"{iters} iterations of {sp.name} on the first {cols_n} of {sp.d} columns "
-                      f"(all {n} agents), fp64 numpy, {el:.1f} s"}
+    # numpy elementwise code runs on one thread; the small per-agent matrix products of the minibatch
+    # losses are below the size at which the BLAS library would start more
+    return {"value": n * width * iters / el, "unit": "agent-param updates/s", "cores": 1, "kind": "oracle",
+            "sample": f"{iters} iterations of {sp.name} on {what}; fp64 numpy oracle, {el:.1f} s"}
 
 
 def main():
@@ -244,7 +299,9 @@ def main():
             "achieved": main_res["achieved_GBs"],
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": main_res["achieved_GBs"] / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": measured_traffic(args.workload, args.steps, args.warmup),
+            "algorithmic_bytes_per_launch": main_res["bytes_per_agent_param"] * sp.n * sp.d
+            / main_res["kernels_per_step"],
             "bytes_per_agent_param": main_res["bytes_per_agent_param"],
             "kernel_ms": main_res["event_ms_per_step"] / main_res["kernels_per_step"],
             "gather_model_GBs": main_res["gather_model_GBs"],
@@ -259,8 +316,7 @@ def main():
             k = 50 if sp_o.loss in ("quad_center",) else (70 if sp_o.loss == "none" else 200)
             out["others"].append(measure(torch, P, Bn, name, k, 5))
     if not args.no_cpu:
-        base_sp = sp if sp.loss == "quad_center" else WL.SPECS["quad31_2p"]
-        out["cpu_baseline"] = cpu_baseline(base_sp)
+        out["cpu_baseline"] = cpu_baseline(sp)
     print(json.dumps(out), flush=True)
 
 
