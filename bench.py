@@ -155,7 +155,9 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
-    return tm, 3, minibatch_bytes(B)
+    # one-pass gradient + combine when the sampled rows fit the register tile, else margins + half step + combine
+    launches = 2 if (B <= 16 and d <= 4096) or (B <= 8 and d <= 8192) or (B <= 4 and d <= 16384) else 3
+    return tm, launches, minibatch_bytes(B)
 
 
 def measure(torch, P, Bn, name, steps, warmup):

@@ -19,6 +19,7 @@ std::atomic<int32_t> g_opt_segment{0};
 std::atomic<int32_t> g_opt_rows{0};
 std::atomic<int32_t> g_opt_band{0};
 std::atomic<int32_t> g_opt_wgs{0};
+std::atomic<int32_t> g_opt_onepass{1};
 
 int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -222,6 +223,9 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       if (value < 0 || value > 8) return fail(CECA_EINVAL, "workgroups per CU must be 0..8");
       g_opt_wgs.store(value);
       return CECA_OK;
+    case CECA_OPT_ONEPASS:
+      g_opt_onepass.store(value != 0);
+      return CECA_OK;
     case CECA_OPT_BAND:
       if (value < 0) return fail(CECA_EINVAL, "band width must be >= 0");
       g_opt_band.store(value);
@@ -330,10 +334,16 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   const bool gemv_vec = aligned16(S_in) && ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
   g.chunk_cols = ceca::kBlock * ceca::kChunkGroups * (gemv_vec ? 4 : 1);
   g.nchunks = (int32_t)((d + g.chunk_cols - 1) / g.chunk_cols);
-  hipError_t e = ceca::launch_margins(g, gemv_vec, st);
-  if (e != hipSuccess) return hip_fail(e, "margins kernel launch");
-  e = ceca::launch_halfstep(g, gemv_vec, st);
-  if (e != hipSuccess) return hip_fail(e, "half-step kernel launch");
+  hipError_t e = hipSuccess;
+  const bool onepass = gemv_vec && g_opt_onepass.load() != 0 && ceca::launch_grad_onepass(g, st, &e);
+  if (onepass) {
+    if (e != hipSuccess) return hip_fail(e, "one-pass gradient kernel launch");
+  } else {
+    e = ceca::launch_margins(g, gemv_vec, st);
+    if (e != hipSuccess) return hip_fail(e, "margins kernel launch");
+    e = ceca::launch_halfstep(g, gemv_vec, st);
+    if (e != hipSuccess) return hip_fail(e, "half-step kernel launch");
+  }
 
   a.aux = g.v;
   a.ldaux = g.ldv;

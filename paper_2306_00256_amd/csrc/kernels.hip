@@ -314,8 +314,39 @@ __device__ __forceinline__ double wave_max(double v) {
   for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
   return v;
 }
+// Sums N per-lane values across the 64 lanes of a wavefront at once.  Each butterfly step halves the
+// number of values a lane carries (partners swap the halves they do not keep), so N values cost
+// N - 1 + (6 - log2 N) lane exchanges instead of 6 N.  On return lane l < N holds the complete sum
+// of value number `which`.
+template <int N>
+__device__ __forceinline__ float wave_sum_many(float (&m)[N], int lane, int& which) {
+  static_assert(N >= 1 && N <= 64 && (N & (N - 1)) == 0, "N must be a power of two");
+  which = 0;
+  int bit = 0;
+#pragma unroll
+  for (int len = N; len > 1; len >>= 1, ++bit) {
+    const bool up = (lane >> bit) & 1;
+    const int half = len / 2;
+#pragma unroll
+    for (int k = 0; k < half; ++k) {
+      const float send = up ? m[k] : m[k + half];
+      const float keep = up ? m[k + half] : m[k];
+      m[k] = keep + __shfl_xor(send, 1 << bit, 64);
+    }
+    which += up ? half : 0;
+  }
+  float v = m[0];
+#pragma unroll
+  for (int b = bit; b < 6; ++b) v += __shfl_xor(v, 1 << b, 64);
+  return v;
+}
+
 __device__ __forceinline__ float dot_v(vf4 a, vf4 b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }
 __device__ __forceinline__ float dot_v(float a, float b) { return a * b; }
+
+// Minibatch row numbers are the same for every lane: keep them in scalar registers so that row
+// addresses are scalar and all row loads can be issued back to back.
+__device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
 // partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col]
 template <int VEC>
@@ -327,33 +358,38 @@ __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
   const int64_t c_lo = (int64_t)chunk * G.chunk_cols;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
+  // lanes past the last column read column 0 instead and carry z = 0: no branch surrounds a load
   V z[kChunkGroups];
   int64_t col[kChunkGroups];
-  bool on[kChunkGroups];
 #pragma unroll
   for (int u = 0; u < kChunkGroups; ++u) {
-    col[u] = c_lo + ((int64_t)u * kBlock + threadIdx.x) * VEC;
-    on[u] = col[u] + VEC <= G.d;
-    z[u] = on[u] ? ld_plain<V>(G.zin + (int64_t)agent * G.ld + col[u]) : V(0.0f);
+    const int64_t c = c_lo + ((int64_t)u * kBlock + threadIdx.x) * VEC;
+    const bool on = c + VEC <= G.d;
+    col[u] = on ? c : 0;
+    const V zv = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col[u]);
+    z[u] = on ? zv : V(0.0f);
   }
   const int32_t* idx = G.batch_idx + (int64_t)agent * G.B;
+  const float* Abase = G.A + (int64_t)agent * G.N * G.lda;
   for (int j0 = 0; j0 < G.B; j0 += 4) {
+    V a[4][kChunkGroups];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      const int32_t rj = uniform_i32(idx[min(j0 + jj, G.B - 1)]);   // rows past B repeat the last one
+      const float* row = Abase + (int64_t)rj * G.lda;
+#pragma unroll
+      for (int u = 0; u < kChunkGroups; ++u) a[jj][u] = ld_stream<V>(row + col[u]);
+    }
     float acc[4];
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
       acc[jj] = 0.0f;
-      if (j0 + jj < G.B) {
-        const float* row = G.A + ((int64_t)agent * G.N + idx[j0 + jj]) * G.lda;
 #pragma unroll
-        for (int u = 0; u < kChunkGroups; ++u)
-          if (on[u]) acc[jj] += dot_v(ld_plain<V>(row + col[u]), z[u]);
-      }
+      for (int u = 0; u < kChunkGroups; ++u) acc[jj] += dot_v(a[jj][u], z[u]);
     }
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const float s = wave_sum(acc[jj]);
-      if (lane == 0 && j0 + jj < G.B) red[wave][j0 + jj] = s;
-    }
+    int jj;
+    const float s = wave_sum_many<4>(acc, lane, jj);
+    if (lane < 4 && j0 + jj < G.B) red[wave][j0 + jj] = s;
   }
   __syncthreads();
   if ((int)threadIdx.x < G.B) {
@@ -364,28 +400,29 @@ __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
   }
 }
 
+// Loss derivative at margin m with target / label t, already divided by the batch size.
+__device__ __forceinline__ float loss_coef(int kind, float m, float t, int B) {
+  // LOGISTIC: -t * sigma(-t m) with sigma(-u) = 1 / (1 + e^u); e^u = inf gives 0, e^u = 0 gives 1
+  const float cf = (kind == CECA_LOSS_LSQ) ? (m - t) : (-t / (1.0f + expf(t * m)));
+  return cf / (float)B;
+}
+
 // v_i = z_i - lr * e_i with e_i = sum_j coef_j a_ij; coef_j folds the loss derivative and the 1/B.
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
   using V = typename VecOf<VEC>::T;
-  __shared__ float coef[64];
-  __shared__ int32_t rowid[64];
+  __shared__ float coef[64 + 4];
+  __shared__ int32_t rowid[64 + 4];
   const int agent = blockIdx.y;
-  if ((int)threadIdx.x < G.B) {
-    const int j = threadIdx.x;
+  if ((int)threadIdx.x < 64 + 4) {
+    const int j = min((int)threadIdx.x, G.B - 1);
     float m = 0.0f;
     for (int ch = 0; ch < G.nchunks; ++ch) m += G.partial[((int64_t)agent * G.nchunks + ch) * G.B + j];
     const int32_t row = G.batch_idx[(int64_t)agent * G.B + j];
     const float t = G.t[(int64_t)agent * G.N + row];
-    float cf;
-    if (G.kind == CECA_LOSS_LSQ) {
-      cf = m - t;
-    } else {
-      // -t * sigma(-t m) with sigma(-u) = 1 / (1 + e^u); e^u = inf gives 0, e^u = 0 gives 1
-      cf = -t / (1.0f + expf(t * m));
-    }
-    coef[j] = cf / (float)G.B;
-    rowid[j] = row;
+    // entries past B repeat the last row with coefficient 0, so the row loop needs no bounds test
+    coef[threadIdx.x] = ((int)threadIdx.x < G.B) ? loss_coef(G.kind, m, t, G.B) : 0.0f;
+    rowid[threadIdx.x] = row;
   }
   __syncthreads();
   const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
@@ -395,14 +432,95 @@ __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
   for (int j0 = 0; j0 < G.B; j0 += 4) {
     V r[4];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj)
-      r[jj] = (j0 + jj < G.B) ? ld_plain<V>(base + (int64_t)rowid[j0 + jj] * G.lda) : V(0.0f);
+    for (int jj = 0; jj < 4; ++jj) r[jj] = ld_stream<V>(base + (int64_t)uniform_i32(rowid[j0 + jj]) * G.lda);
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj)
-      if (j0 + jj < G.B) e += coef[j0 + jj] * r[jj];
+    for (int jj = 0; jj < 4; ++jj) e += coef[j0 + jj] * r[jj];
   }
   const V z = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
   *reinterpret_cast<V*>(G.v + (int64_t)agent * G.ldv + col) = z - G.lr * e;
+}
+
+// One pass over the minibatch rows: a workgroup owns an agent, keeps its B sampled rows of A in
+// registers (B x G 16-byte groups per thread), reduces the B margins across the workgroup, and forms
+// v = z - lr * e from the same registers, so A is read from memory once per iteration.
+template <int THREADS, int BMAX, int G>
+__global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P) {
+  constexpr int WAVES = THREADS / 64;
+  __shared__ float red[WAVES][BMAX];
+  __shared__ float coef[BMAX];
+  const int agent = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // lanes past the last column read column 0 instead and carry z = 0: no branch surrounds a load
+  int64_t col[G];
+  bool on[G];
+  vf4 z[G];
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * 4;
+    on[u] = c < P.d;                       // d is a multiple of 4 on this path
+    col[u] = on[u] ? c : 0;
+    const vf4 zv = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
+    z[u] = on[u] ? zv : vf4(0.0f);
+  }
+  const int32_t* idx = P.batch_idx + (int64_t)agent * P.B;
+  const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
+  int32_t rowid[BMAX];
+#pragma unroll
+  for (int j = 0; j < BMAX; ++j) rowid[j] = uniform_i32(idx[min(j, P.B - 1)]);   // rows past B repeat the last
+  vf4 a[BMAX][G];
+#pragma unroll
+  for (int j = 0; j < BMAX; ++j) {
+    const float* row = Abase + (int64_t)rowid[j] * P.lda;
+#pragma unroll
+    for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
+  }
+  float m[BMAX];
+#pragma unroll
+  for (int j = 0; j < BMAX; ++j) {
+    m[j] = 0.0f;
+#pragma unroll
+    for (int u = 0; u < G; ++u) m[j] += dot_v(a[j][u], z[u]);
+  }
+  int jrow;
+  const float msum = wave_sum_many<BMAX>(m, lane, jrow);
+  if (lane < BMAX) red[wave][jrow] = msum;
+  __syncthreads();
+  if ((int)threadIdx.x < BMAX) {
+    const int j = threadIdx.x;
+    float m = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) m += red[w][j];
+    const float t = P.t[(int64_t)agent * P.N + idx[min(j, P.B - 1)]];
+    coef[j] = (j < P.B) ? loss_coef(P.kind, m, t, P.B) : 0.0f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    vf4 e = vf4(0.0f);
+#pragma unroll
+    for (int j = 0; j < BMAX; ++j) e += coef[j] * a[j][u];
+    if (on[u]) *reinterpret_cast<vf4*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * e;
+  }
+}
+
+// Picks the one-pass variant whose register tile covers (B, d); false if none does.
+bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
+  const int64_t d4 = g.d / 4;
+  dim3 grid((unsigned)g.n);
+#define CECA_ONEPASS(T, BM, GG)                                          \
+  if (g.B <= BM && d4 <= (int64_t)T * GG) {                              \
+    grad_onepass_kernel<T, BM, GG><<<grid, dim3(T), 0, st>>>(g);         \
+    *err = hipGetLastError();                                            \
+    return true;                                                         \
+  }
+  CECA_ONEPASS(256, 16, 1)
+  CECA_ONEPASS(256, 32, 1)
+  CECA_ONEPASS(1024, 8, 1)
+  CECA_ONEPASS(1024, 16, 1)
+  CECA_ONEPASS(1024, 8, 2)
+  CECA_ONEPASS(1024, 4, 4)
+#undef CECA_ONEPASS
+  return false;
 }
 
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st) {

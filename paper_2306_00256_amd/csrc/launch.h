@@ -77,6 +77,8 @@ struct ConsensusArgs {
 
 // rows: state rows whose loads a thread keeps in flight together (1, 2, 4 or 8)
 hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
+// one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
+bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);

@@ -197,9 +197,22 @@ def test_least_squares_full_run(env, name):
 @pytest.mark.parametrize("kind", ["lsq", "logistic"])
 @pytest.mark.parametrize("n,port,d,B,off,ld", [(1, 2, 300, 4, 0, None), (2, 1, 1000, 1, 0, None),
                                               (7, 2, 2500, 9, 0, 2504), (6, 1, 1027, 33, 0, None),
-                                              (12, 2, 1024, 64, 1, None), (9, 2, 5000, 16, 0, None)])
-def test_minibatch_step_variants(env, kind, n, port, d, B, off, ld):
+                                              (12, 2, 1024, 64, 1, None), (9, 2, 5000, 16, 0, None),
+                                              (9, 2, 4096, 16, 0, None), (5, 2, 8192, 8, 0, 8200),
+                                              (4, 1, 16384, 4, 0, None), (4, 2, 1000, 32, 0, None),
+                                              (3, 2, 4100, 7, 0, None)])
+@pytest.mark.parametrize("onepass", [1, 0])
+def test_minibatch_step_variants(env, kind, n, port, d, B, off, ld, onepass):
     torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    P.ceca_set_option(Bn.OPT_ONEPASS, onepass)
+    try:
+        _minibatch_variant(torch, P, kind, n, port, d, B, off, ld)
+    finally:
+        P.ceca_set_option(Bn.OPT_ONEPASS, 1)
+
+
+def _minibatch_variant(torch, P, kind, n, port, d, B, off, ld):
     N, iters = 40, 7
     if kind == "lsq":
         A, t, _ = WL.lsq_data(n, N, d, seed=n)
