@@ -104,6 +104,17 @@ int32_t ceca_schedule(int32_t n, int32_t r, int32_t port, ceca_round_t* out, int
 int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                           int32_t r, int32_t port, void* hip_stream);
 
+/* `rounds` consecutive gradient-free CECA rounds r = 0, 1, ..., taken cyclically (round t uses
+ * r = t mod tau), in one pass over the state: rounds = tau leaves every x_i at the global mean
+ * (Sec. 3.1 problem statement; matrix-consensus lemma, first identity), rounds = tau + 1 also every
+ * y_i (Lemma 4.2) -- the global averaging that Theorem 4.3 asks for before the first iteration.
+ * The result has the same bits as `rounds` calls of ceca_gossip_round.  Because the sequence starts
+ * at round 0, the y rows of S_in are never read.  S_out may be S_in or disjoint from it.
+ * Up to 4096 agents and 64 rounds run as one kernel that moves 12 bytes per agent-parameter; larger
+ * cases fall back to one launch per round (in place on S_out after the first). */
+int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
+                           int32_t rounds, int32_t port, void* hip_stream);
+
 /* Bytes of device workspace dsgd_ceca_step needs for this problem (0 for QUAD_CENTER); < 0 on error. */
 int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss);
 

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     Loss,
     Round,
     ceca_gossip_round,
+    ceca_gossip_rounds,
     ceca_schedule,
     ceca_set_option,
     ceca_tau,

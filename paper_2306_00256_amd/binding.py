@@ -13,7 +13,7 @@ LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER = 0, 1, 2
 OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS = 1, 2, 3, 4, 5
 
 EXPORTS = (
-    "ceca_tau", "ceca_schedule", "ceca_gossip_round", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step",
+    "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step",
     "consensus_error_workspace_bytes", "consensus_error", "ceca_last_error", "ceca_last_hip_error",
     "ceca_set_option",
 )
@@ -60,6 +60,9 @@ def lib():
         L.ceca_gossip_round.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_int32,
                                         C.c_int32, C.c_void_p]
         L.ceca_gossip_round.restype = C.c_int32
+        L.ceca_gossip_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_int32,
+                                         C.c_int32, C.c_void_p]
+        L.ceca_gossip_rounds.restype = C.c_int32
         L.dsgd_ceca_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.POINTER(Loss)]
         L.dsgd_ceca_workspace_bytes.restype = C.c_int64
         L.dsgd_ceca_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Loss),
@@ -113,6 +116,13 @@ def ceca_gossip_round(S_in, S_out, n: int, d: int, r: int, port: int, ld: Option
     """S_in, S_out: device float32 tensors holding 2n rows of ld floats (x rows, then y rows)."""
     ld = int(S_in.stride(0)) if ld is None else ld
     _check(lib().ceca_gossip_round(_ptr(S_in), _ptr(S_out), n, d, ld, r, port, _stream(stream)))
+
+
+def ceca_gossip_rounds(S_in, S_out, n: int, d: int, rounds: int, port: int, ld: Optional[int] = None,
+                       stream=None) -> None:
+    """`rounds` gradient-free rounds starting at round 0, fused into one pass."""
+    ld = int(S_in.stride(0)) if ld is None else ld
+    _check(lib().ceca_gossip_rounds(_ptr(S_in), _ptr(S_out), n, d, ld, rounds, port, _stream(stream)))
 
 
 def dsgd_ceca_workspace_bytes(n: int, d: int, loss: Loss) -> int:

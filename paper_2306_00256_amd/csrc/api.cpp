@@ -182,7 +182,9 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
   ConsPlan p;
   p.ntiles = (d + ceca::kConsTile - 1) / ceca::kConsTile;
   // column sums: slice the agents when there are too few column tiles to fill the device
+  // (at most 32 slices: the mean kernel adds them up serially per column)
   int64_t want = (1024 + p.ntiles - 1) / p.ntiles;
+  if (want > 32) want = 32;
   if (want > (n + 3) / 4) want = (n + 3) / 4;
   if (want < 1) want = 1;
   p.agents_per_group = (int32_t)((n + want - 1) / want);
@@ -267,6 +269,52 @@ int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d,
   set_weights(rd, n, /*gossip_only=*/true, &a);
   const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
   return run_chain(a, ceca::MODE_GOSSIP, d, can_vec, rd, port, (hipStream_t)hip_stream);
+}
+
+int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, int32_t rounds,
+                           int32_t port, void* hip_stream) {
+  ceca_round_t rd;
+  const int32_t rc = check_state_call(S_in, S_out, n, d, ld, 0, port, &rd);
+  if (rc != CECA_OK) return rc;
+  if (rounds < 1) return fail(CECA_EINVAL, "rounds = %d: need at least one", rounds);
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int32_t tau = ceca::tau_of(n);
+  int32_t row_lanes = 1;
+  while (row_lanes * ceca::kMultiRows < n) row_lanes *= 2;
+  if (n == 1 || rounds > ceca::kMultiMaxRounds || row_lanes > ceca::kBlock) {
+    // too many agents for one workgroup's registers (or nothing to fuse): one launch per round, the
+    // first from S_in to S_out, the rest in place on S_out (whole cycles / pairs read before they write)
+    for (int32_t t = 0; t < rounds; ++t) {
+      const int32_t r1 = ceca_gossip_round(t == 0 ? S_in : S_out, S_out, n, d, ld, n == 1 ? 0 : t % tau, port, st);
+      if (r1 != CECA_OK) return r1;
+    }
+    return CECA_OK;
+  }
+  ceca::MultiArgs m{};
+  m.xin = S_in;
+  m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
+  m.ld = ld;
+  m.n = n;  m.port = port;  m.rounds = rounds;
+  m.row_lanes = row_lanes;
+  for (int32_t t = 0; t < rounds; ++t) {
+    ceca::fill_round(n, t % tau, port, &rd);
+    ceca::MultiRound& R = m.round[t];
+    R.shift = rd.shift;  R.exch_y = rd.exchange_y;  R.read_y = rd.b_num != 0;
+    R.a = rd.a;  R.ap = rd.a_peer;  R.b = rd.b;  R.bp = rd.b_peer;
+  }
+  const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
+  const int64_t d4 = can_vec ? d / 4 : 0;
+  if (d4 > 0) {
+    m.col0 = 0;  m.ngroups = d4;
+    const hipError_t e = ceca::launch_multi_round(m, true, st);
+    if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch");
+  }
+  if (d - 4 * d4 > 0) {
+    m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+    const hipError_t e = ceca::launch_multi_round(m, false, st);
+    if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch (scalar columns)");
+  }
+  return CECA_OK;
 }
 
 int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss) {

@@ -41,6 +41,27 @@ struct ChainArgs {
   uint32_t seed, k;
 };
 
+// One round of the multi-round kernel: weights and travelling variable (Algorithm 1's a, b, z).
+struct MultiRound {
+  int32_t shift, exch_y, read_y;
+  float a, ap, b, bp;
+};
+
+constexpr int kMultiRows = 16;       // rows of (x, y) a thread of the multi-round kernel keeps in registers
+constexpr int kMultiMaxRounds = 64;
+
+struct MultiArgs {
+  const float* xin;    // row 0 of x in S_in (y of S_in is not read: round 0 overwrites it)
+  float* xout;
+  float* yout;
+  int64_t ld;
+  int64_t col0;
+  int64_t ngroups;
+  int32_t n, port, rounds;
+  int32_t row_lanes;   // power of two >= ceil(n / kMultiRows): threads of a workgroup that share a column group
+  MultiRound round[kMultiMaxRounds];
+};
+
 struct GemvArgs {
   const float* zin;       // row 0 of the variable the gradient is taken at (x or y rows of S_in)
   int64_t ld;
@@ -79,6 +100,7 @@ struct ConsensusArgs {
 hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
 // one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
+hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);

@@ -161,3 +161,49 @@ def test_full_size_gossip_sampled_columns(env, port):
         assert max(rel_err(gx, x)) <= TOL_ROUND and max(rel_err(gy, y)) <= TOL_ROUND, r
     dev = (S[:n].double() - mean_all).norm(dim=1).max().item()
     assert dev <= TOL_CONS * mean_all.norm().item()
+
+
+@pytest.mark.parametrize("n,port", [(2, 1), (3, 2), (5, 2), (6, 1), (16, 2), (17, 2), (31, 2), (32, 1), (33, 2),
+                                    (100, 1), (100, 2), (258, 1), (1023, 2), (1026, 1)])
+def test_fused_rounds_equal_separate_rounds(env, n, port):
+    """ceca_gossip_rounds: same bits as the sequence of single rounds, and the oracle's values."""
+    torch, P = env
+    d = 1037 if n < 200 else 203
+    x0 = WL.initial_state(n, d, seed=7 * n + port)
+    tau = OS.num_rounds(n)
+    for rounds in (1, tau, tau + 1, 2 * tau + 3):
+        ref, _ = _run_rounds(torch, P, x0, port, rounds)
+        S = make_state(torch, x0, y0=np.full_like(x0, np.nan))      # y(0) must not be read
+        T = make_state(torch, np.zeros_like(x0))
+        P.ceca_gossip_rounds(S, T, n, d, rounds, port)
+        gx, gy = split_state(T, n, d)
+        assert np.array_equal(gx, ref[-1][0]) and np.array_equal(gy, ref[-1][1]), rounds
+    x, y = OC.run(x0, port, 0.0, None, tau + 1, store32=True)
+    assert max(rel_err(gx, OC.run(x0, port, 0.0, None, 2 * tau + 3, store32=True)[0])) <= TOL_ROUND
+    # in place and from an unaligned, padded layout
+    S = make_state(torch, x0, ld=d + 5, offset=1)
+    P.ceca_gossip_rounds(S, S, n, d, tau + 1, port)
+    gx, gy = split_state(S, n, d)
+    assert max(rel_err(gx, x)) <= TOL_ROUND and max(rel_err(gy, y)) <= TOL_ROUND
+    mean = x0.astype(np.float64).mean(0)
+    assert np.abs(gx - mean).max() <= 2e-6 and np.abs(gy - mean).max() <= 2e-6
+    assert bool((S[:, d:] == 12345.0).all())
+
+
+def test_fused_rounds_fallbacks(env):
+    torch, P = env
+    # one agent: copies; more agents than one workgroup can hold: one launch per round
+    x0 = WL.initial_state(1, 33, seed=5)
+    S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
+    P.ceca_gossip_rounds(S, T, 1, 33, 3, 2)
+    assert np.array_equal(split_state(T, 1, 33)[0], x0.astype(np.float64))
+    n, d = 4100, 40
+    x0 = WL.initial_state(n, d, seed=6)
+    tau = OS.num_rounds(n)
+    for port in (1, 2):
+        S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
+        P.ceca_gossip_rounds(S, T, n, d, tau, port)
+        gx, _ = split_state(T, n, d)
+        assert np.abs(gx - x0.astype(np.float64).mean(0)).max() <= 2e-6
+    with pytest.raises(P.CecaError):
+        P.ceca_gossip_rounds(S, T, n, d, 0, 2)
