@@ -131,14 +131,24 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
         A, t, _ = WL.device_logistic_sparse(n, N, d, sp.seed)
     else:
         if sp.loss == "lsq":
-            Ah, th, _ = WL.lsq_data(n, N, d, sp.seed)
+            Ah, th, _ = WL.lsq_data(n, N, d, sp.seed, obs_noise=sp.obs_noise)
         else:
             Ah, th, _ = WL.logistic_data_hetero(n, N, d, sp.seed)
         A, t = torch.from_numpy(Ah).cuda(), torch.from_numpy(th).cuda()
-    nidx = min(steps + warmup, 256)
-    idx = torch.from_numpy(WL.batch_indices(n, N, B, nidx, sp.seed)).cuda()
-    loss = Bn.make_minibatch_loss(Bn.LOSS_LSQ if sp.loss == "lsq" else Bn.LOSS_LOGISTIC, A, t, N, B)
-    ws = torch.empty(P.dsgd_ceca_workspace_bytes(n, d, loss), dtype=torch.uint8, device="cuda")
+    if sp.B == sp.N:
+        idx_h = WL.full_batch_indices(n, N)
+    else:
+        idx_h = WL.batch_indices(n, N, B, min(steps + warmup, 256), sp.seed)
+    nidx = idx_h.shape[0]
+    idx = torch.from_numpy(idx_h).cuda()
+    kind = Bn.LOSS_LSQ if sp.loss == "lsq" else Bn.LOSS_LOGISTIC
+
+    def make_loss(k):
+        return Bn.make_minibatch_loss(kind, A, t, N, B, grad_scale=sp.grad_scale, noise_std=sp.noise_std,
+                                      seed=sp.seed, k=k)
+
+    loss0 = make_loss(0)
+    ws = torch.empty(max(P.dsgd_ceca_workspace_bytes(n, d, loss0), 256), dtype=torch.uint8, device="cuda")
     ld = _ld(d)
     S = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
     T = S if port == 1 else torch.empty_like(S)
@@ -146,7 +156,8 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
 
     def step(k):
         nonlocal S, T
-        P.dsgd_ceca_step(S, T, n, d, loss, idx[k % nidx], sp.lr, k % tau, port, workspace=ws, ld=ld)
+        loss = make_loss(k) if sp.noise_std else loss0
+        P.dsgd_ceca_step(S, T, n, d, loss, idx[k % nidx], WL.step_size(sp, k), k % tau, port, workspace=ws, ld=ld)
         if port == 2:
             S, T = T, S
 
@@ -226,8 +237,10 @@ def cpu_baseline(sp, target_s=12.0):
         else:
             A, t, _ = WL.logistic_data_hetero(n, N, sp.d, sp.seed)
         max_iters = min(sp.iters, 2000)
-        idx = WL.batch_indices(n, N, sp.B, max_iters, sp.seed)
-        grad = OL.make_minibatch_grad(sp.loss, A, t, idx)
+        B = min(sp.B, N)
+        idx = WL.full_batch_indices(n, N) if sp.B == sp.N else WL.batch_indices(n, N, B, max_iters, sp.seed)
+        grad = OL.make_minibatch_grad(sp.loss, A, t, idx, grad_scale=sp.grad_scale, noise_std=sp.noise_std,
+                                      seed=sp.seed)
         x = y = np.zeros((n, sp.d))
         width = sp.d
         what = f"{n} of {sp.n} agents, {N} of {sp.N} samples each, all {sp.d} columns"
@@ -238,7 +251,7 @@ def cpu_baseline(sp, target_s=12.0):
         if grad is None:
             x, y = OC.gossip_round(x, y, iters % tau, port, store32=True)
         else:
-            x, y = OC.dsgd_ceca_step(x, y, iters, port, sp.lr, grad, store32=True)
+            x, y = OC.dsgd_ceca_step(x, y, iters, port, WL.step_size(sp, iters), grad, store32=True)
         iters += 1
         el = time.perf_counter() - t0
         if el > target_s or iters >= max_iters:

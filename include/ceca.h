@@ -57,11 +57,13 @@ typedef struct {
 } ceca_round_t;
 
 /* Per-agent stochastic gradient e_i = grad F(z_i; xi_i), evaluated once per agent per
- * iteration at z_i (Algorithm 1).  Minibatch losses average over the B sampled rows:
- *   LSQ         e_i = 1/B sum_j (a_ij . z_i - t_ij) a_ij          (least squares of Sec. 5)
- *   LOGISTIC    e_i = -1/B sum_j t_ij sigma(-t_ij a_ij . z_i) a_ij,  labels t_ij = +-1
- *   QUAD_CENTER e_i = z_i - c_i + noise_std * eps_i, eps_i ~ N(0, I) from the counter-based
- *               generator below, keyed by (seed, k, agent, column).
+ * iteration at z_i (Algorithm 1).  With s = grad_scale (0 selects the minibatch mean, s = 1/B):
+ *   LSQ         e_i = s sum_j (a_ij . z_i - t_ij) a_ij + noise_std * eps_i
+ *               (s = 1, B = N, batch_idx = 0..N-1 and noise_std = sigma_n give the least-squares
+ *               experiment of Sec. 5: full gradient of 1/2 ||A_i x - b_i||^2 plus N(0, sigma_n^2 I))
+ *   LOGISTIC    e_i = -s sum_j t_ij sigma(-t_ij a_ij . z_i) a_ij + noise_std * eps_i,  labels t_ij = +-1
+ *   QUAD_CENTER e_i = z_i - c_i + noise_std * eps_i
+ * eps_i ~ N(0, I) comes from the counter-based generator below, keyed by (seed, k, agent, column).
  *
  * Noise generator (uint32 arithmetic, wrapping; agent and column 0-based):
  *   mix(h):   h ^= h >> 16; h *= 0x7feb352d; h ^= h >> 15; h *= 0x846ca68b; h ^= h >> 16
@@ -75,9 +77,10 @@ typedef struct {
   int32_t kind;         /* CECA_LOSS_* */
   int32_t N;            /* samples per agent (minibatch losses) */
   int32_t B;            /* minibatch rows per agent per iteration, 1..64 */
-  uint32_t seed;        /* QUAD_CENTER: noise seed */
-  uint32_t k;           /* QUAD_CENTER: iteration number fed to the noise counter */
-  float noise_std;      /* QUAD_CENTER: noise scale, 0 = none */
+  uint32_t seed;        /* noise seed */
+  uint32_t k;           /* iteration number fed to the noise counter */
+  float noise_std;      /* scale of the additive Gaussian gradient noise, 0 = none */
+  float grad_scale;     /* minibatch losses: factor s on the summed gradient; 0 = 1/B */
   const float* A;       /* device, n*N rows of lda floats: row i*N + j is sample j of agent i */
   int64_t lda;          /* >= d */
   const float* t;       /* device, n*N floats: targets (LSQ) or labels +-1 (LOGISTIC) */

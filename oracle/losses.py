@@ -34,17 +34,28 @@ def logistic_loss_and_grad(Ab: np.ndarray, lab: np.ndarray, z: np.ndarray):
     return loss, -(Ab.T @ (lab * sig)) / B
 
 
-def make_minibatch_grad(kind: str, A: np.ndarray, t: np.ndarray, batch_idx: np.ndarray, k0: int = 0):
+def make_minibatch_grad(kind: str, A: np.ndarray, t: np.ndarray, batch_idx: np.ndarray, k0: int = 0,
+                        grad_scale: float = 0.0, noise_std: float = 0.0, seed: int = 0):
     """A (n, N, d), t (n, N) targets or labels, batch_idx (iters, n, B) rows drawn by the caller;
-    iteration k uses batch_idx[k - k0]."""
+    iteration k uses batch_idx[(k - k0) mod iters].  grad_scale = 0 is the mean over the batch; grad_scale = s
+    multiplies the *summed* gradient by s (s = 1 with the full batch is the gradient of 1/2 ||A_i x - b_i||^2,
+    the local loss of the least-squares experiment, Sec. 5).  noise_std adds N(0, noise_std^2 I) drawn by
+    oracle/noise.py, as that experiment does."""
     fn = {"lsq": lsq_loss_and_grad, "logistic": logistic_loss_and_grad}[kind]
+    d = A.shape[2]
+    cols = np.arange(d, dtype=np.int64)
 
     def grad(z: np.ndarray, k: int) -> np.ndarray:
         e = np.empty_like(z)
         for i in range(z.shape[0]):
-            rows = batch_idx[k - k0, i]
+            rows = batch_idx[(k - k0) % batch_idx.shape[0], i]
             Ab = A[i, rows].astype(np.float64)
-            e[i] = fn(Ab, t[i, rows].astype(np.float64), z[i])[1]
+            g = fn(Ab, t[i, rows].astype(np.float64), z[i])[1]          # mean over the B rows
+            if grad_scale:
+                g = g * (len(rows) * grad_scale)
+            if noise_std:
+                g = g + noise_std * noise.normals(seed, k, i, cols)
+            e[i] = g
         return e
 
     return grad

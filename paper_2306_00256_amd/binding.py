@@ -35,7 +35,7 @@ class Round(C.Structure):
 class Loss(C.Structure):
     """ceca_loss_t"""
     _fields_ = [("kind", C.c_int32), ("N", C.c_int32), ("B", C.c_int32), ("seed", C.c_uint32), ("k", C.c_uint32),
-                ("noise_std", C.c_float), ("A", C.c_void_p), ("lda", C.c_int64), ("t", C.c_void_p),
+                ("noise_std", C.c_float), ("grad_scale", C.c_float), ("A", C.c_void_p), ("lda", C.c_int64), ("t", C.c_void_p),
                 ("c", C.c_void_p), ("ldc", C.c_int64)]
 
 
@@ -152,13 +152,14 @@ def ceca_set_option(option: int, value: int) -> None:
     _check(lib().ceca_set_option(option, value))
 
 
-def make_minibatch_loss(kind: int, A, t, N: int, B: int) -> Loss:
-    """A: device (n, N, lda) float32, t: device (n, N) float32."""
-    return Loss(kind=kind, N=N, B=B, seed=0, k=0, noise_std=0.0, A=_ptr(A), lda=int(A.stride(-2)), t=_ptr(t),
-                c=None, ldc=0)
+def make_minibatch_loss(kind: int, A, t, N: int, B: int, grad_scale: float = 0.0, noise_std: float = 0.0,
+                        seed: int = 0, k: int = 0) -> Loss:
+    """A: device (n, N, lda) float32, t: device (n, N) float32.  grad_scale = 0 means the mean over the batch."""
+    return Loss(kind=kind, N=N, B=B, seed=seed & 0xFFFFFFFF, k=k & 0xFFFFFFFF, noise_std=noise_std,
+                grad_scale=grad_scale, A=_ptr(A), lda=int(A.stride(-2)), t=_ptr(t), c=None, ldc=0)
 
 
 def make_quad_center_loss(c, noise_std: float, seed: int, k: int = 0) -> Loss:
     """c: device (n, ldc) float32 centres."""
     return Loss(kind=LOSS_QUAD_CENTER, N=0, B=0, seed=seed & 0xFFFFFFFF, k=k & 0xFFFFFFFF, noise_std=noise_std,
-                A=None, lda=0, t=None, c=_ptr(c), ldc=int(c.stride(0)))
+                grad_scale=0.0, A=None, lda=0, t=None, c=_ptr(c), ldc=int(c.stride(0)))

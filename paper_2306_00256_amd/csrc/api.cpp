@@ -162,6 +162,8 @@ int32_t check_loss(const ceca_loss_t* loss, int64_t d, bool need_batch, const in
         return fail(CECA_EINVAL, "need N >= 1 and 1 <= B <= 64 (N = %d, B = %d)", loss->N, loss->B);
       if (!loss->A || !loss->t || loss->lda < d) return fail(CECA_EINVAL, "minibatch loss needs A, t and lda >= d");
       if (need_batch && !batch_idx) return fail(CECA_EINVAL, "minibatch loss needs batch_idx");
+      if (!(loss->noise_std >= 0.0f) || !(loss->grad_scale >= 0.0f))
+        return fail(CECA_EINVAL, "noise_std and grad_scale must be >= 0");
       return CECA_OK;
     case CECA_LOSS_QUAD_CENTER:
       if (!loss->c || loss->ldc < d) return fail(CECA_EINVAL, "quadratic-centre loss needs c and ldc >= d");
@@ -379,6 +381,10 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   g.d = d;
   g.n = n;  g.N = loss->N;  g.B = loss->B;  g.kind = loss->kind;
   g.lr = lr;
+  g.scale = loss->grad_scale > 0.0f ? loss->grad_scale : 1.0f / (float)loss->B;
+  g.noise_std = loss->noise_std;
+  g.seed = loss->seed;
+  g.k = loss->k;
   const bool gemv_vec = aligned16(S_in) && ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
   g.chunk_cols = ceca::kBlock * ceca::kChunkGroups * (gemv_vec ? 4 : 1);
   g.nchunks = (int32_t)((d + g.chunk_cols - 1) / g.chunk_cols);

@@ -477,10 +477,10 @@ __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
 }
 
 // Loss derivative at margin m with target / label t, already divided by the batch size.
-__device__ __forceinline__ float loss_coef(int kind, float m, float t, int B) {
+__device__ __forceinline__ float loss_coef(int kind, float m, float t, float scale) {
   // LOGISTIC: -t * sigma(-t m) with sigma(-u) = 1 / (1 + e^u); e^u = inf gives 0, e^u = 0 gives 1
   const float cf = (kind == CECA_LOSS_LSQ) ? (m - t) : (-t / (1.0f + expf(t * m)));
-  return cf / (float)B;
+  return cf * scale;
 }
 
 // v_i = z_i - lr * e_i with e_i = sum_j coef_j a_ij; coef_j folds the loss derivative and the 1/B.
@@ -497,7 +497,7 @@ __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
     const int32_t row = G.batch_idx[(int64_t)agent * G.B + j];
     const float t = G.t[(int64_t)agent * G.N + row];
     // entries past B repeat the last row with coefficient 0, so the row loop needs no bounds test
-    coef[threadIdx.x] = ((int)threadIdx.x < G.B) ? loss_coef(G.kind, m, t, G.B) : 0.0f;
+    coef[threadIdx.x] = ((int)threadIdx.x < G.B) ? loss_coef(G.kind, m, t, G.scale) : 0.0f;
     rowid[threadIdx.x] = row;
   }
   __syncthreads();
@@ -512,6 +512,7 @@ __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) e += coef[j0 + jj] * r[jj];
   }
+  if (G.noise_std != 0.0f) e += G.noise_std * noise_group<V>(col, noise_keys(G.seed, G.k, (uint32_t)agent));
   const V z = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
   *reinterpret_cast<V*>(G.v + (int64_t)agent * G.ldv + col) = z - G.lr * e;
 }
@@ -567,7 +568,7 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) m += red[w][j];
     const float t = P.t[(int64_t)agent * P.N + idx[min(j, P.B - 1)]];
-    coef[j] = (j < P.B) ? loss_coef(P.kind, m, t, P.B) : 0.0f;
+    coef[j] = (j < P.B) ? loss_coef(P.kind, m, t, P.scale) : 0.0f;
   }
   __syncthreads();
 #pragma unroll
@@ -575,6 +576,7 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
     vf4 e = vf4(0.0f);
 #pragma unroll
     for (int j = 0; j < BMAX; ++j) e += coef[j] * a[j][u];
+    if (P.noise_std != 0.0f) e += P.noise_std * noise_group<vf4>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
     if (on[u]) *reinterpret_cast<vf4*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * e;
   }
 }

@@ -77,6 +77,9 @@ struct GemvArgs {
   int32_t nchunks;
   int32_t chunk_cols;
   float lr;
+  float scale;            // factor on sum_j coef_j a_ij: 1/B, or the caller's grad_scale
+  float noise_std;        // additive Gaussian gradient noise (0 = none), keyed by (seed, k)
+  uint32_t seed, k;
 };
 
 struct ConsensusArgs {

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(api):
 def test_struct_sizes_match_header(api):
     from paper_2306_00256_amd import binding
     assert ctypes.sizeof(binding.Round) == 12 * 4 + 4 * 4
-    assert ctypes.sizeof(binding.Loss) == 24 + 5 * 8
+    assert ctypes.sizeof(binding.Loss) == 32 + 5 * 8
 
 
 @pytest.mark.parametrize("port", [1, 2])

@@ -111,9 +111,10 @@ def test_full_size_quad_center_sampled_columns(env, name):
     from paper_2306_00256_amd import binding as Bn
     sp = WL.SPECS[name]
     n, d, port = sp.n, sp.d, sp.port
-    c = torch.empty((n, d), dtype=torch.float32, device="cuda")
-    WL.device_normal((n, d), seed=sp.seed, out=c)
-    S = torch.zeros((2 * n, d), dtype=torch.float32, device="cuda")
+    ld = (d + 63) // 64 * 64                     # the row pitch bench.py uses: rows start on 256-byte boundaries
+    c = torch.empty((n, ld), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, ld), seed=sp.seed, out=c)
+    S = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
     T = S if port == 1 else torch.empty_like(S)
     cols = WL.sample_columns(d, 1536, seed=sp.seed, tail=8)
     tc = torch.from_numpy(cols).cuda()
@@ -122,7 +123,7 @@ def test_full_size_quad_center_sampled_columns(env, name):
     tau = OS.num_rounds(n)
     for k in range(sp.iters):
         loss = Bn.make_quad_center_loss(c, sp.noise_std, sp.seed, k)
-        P.dsgd_ceca_step(S, T, n, d, loss, None, sp.lr, k % tau, port)
+        P.dsgd_ceca_step(S, T, n, d, loss, None, sp.lr, k % tau, port, ld=ld)
         if port == 2:
             S, T = T, S
         x, y = OC.dsgd_ceca_step(x, y, k, port, sp.lr, grad, store32=True)
@@ -130,8 +131,8 @@ def test_full_size_quad_center_sampled_columns(env, name):
             gx, gy = S[:n][:, tc].cpu().numpy(), S[n:][:, tc].cpu().numpy()
             assert max(rel_err(gx, x)) <= TOL_RUN and max(rel_err(gy, y)) <= TOL_RUN, k
     # whole-state property: x_bar(k) = c_bar + (1-lr)^k (x_bar(0) - c_bar) up to the noise mean
-    xbar = S[:n].double().mean(0)
-    cbar = c.double().mean(0)
+    xbar = S[:n, :d].double().mean(0)
+    cbar = c[:, :d].double().mean(0)
     resid = (xbar - cbar * (1 - (1 - sp.lr) ** sp.iters)).abs().max().item()
     assert resid < 0.02        # noise: lr * std * sum of 50 damped N(0, 1/n) draws is ~1e-3
 
@@ -257,6 +258,38 @@ def test_many_agent_logistic(env):
     x0 = WL.initial_state(63, sp.d, sp.seed, kind="zero")
     (gx, gy), (x, y), _ = _run_minibatch(torch, P, "logistic", A, lab, idx, x0, 2, sp.lr, sp.iters)
     assert max(rel_err(gx, x)) <= TOL_RUN and max(rel_err(gy, y)) <= TOL_RUN
+
+
+@pytest.mark.parametrize("name", ["paperlsq258_1p", "paperlsq258_2p"])
+def test_paper_least_squares_experiment(env, name):
+    """The paper's own least-squares setting (Sec. 5): n = 258, d = 10, N = 50, full gradient of
+    1/2 ||A_i x - b_i||^2 plus N(0, 25 I) noise, step 0.02 / 1.5^(k // 20).  d = 10 takes the scalar kernels."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    sp = WL.SPECS[name]
+    n, d, N = sp.n, sp.d, sp.N
+    A, b, xs = WL.lsq_data(n, N, d, sp.seed, obs_noise=sp.obs_noise)
+    idx = WL.full_batch_indices(n, N)
+    grad = OL.make_minibatch_grad("lsq", A, b, idx, grad_scale=sp.grad_scale, noise_std=sp.noise_std, seed=sp.seed)
+    Ad, bd, idd = torch.from_numpy(A).cuda(), torch.from_numpy(b).cuda(), torch.from_numpy(idx[0]).cuda()
+    x0 = WL.initial_state(n, d, sp.seed)
+    S = make_state(torch, x0)
+    T = S if sp.port == 1 else make_state(torch, np.zeros_like(x0))
+    ws = _workspace(torch, P, n, d, Bn.make_minibatch_loss(Bn.LOSS_LSQ, Ad, bd, N, sp.B))
+    x = y = x0.astype(np.float64)
+    tau = OS.num_rounds(n)
+    err0 = np.abs(x.mean(0) - xs).max()
+    for k in range(sp.iters):
+        lr = WL.step_size(sp, k)
+        loss = Bn.make_minibatch_loss(Bn.LOSS_LSQ, Ad, bd, N, sp.B, grad_scale=sp.grad_scale, noise_std=sp.noise_std,
+                                      seed=sp.seed, k=k)
+        P.dsgd_ceca_step(S, T, n, d, loss, idd, lr, k % tau, sp.port, workspace=ws)
+        if sp.port == 2:
+            S, T = T, S
+        x, y = OC.dsgd_ceca_step(x, y, k, sp.port, lr, grad, store32=True)
+    gx, gy = split_state(S, n, d)
+    assert max(rel_err(gx, x)) <= TOL_RUN and max(rel_err(gy, y)) <= TOL_RUN
+    assert np.abs(gx.mean(0) - xs).max() < 0.2 * err0          # the averaged model approaches x*
 
 
 def test_step_errors(env):

@@ -144,3 +144,30 @@ def test_mirror_mode_reaches_fp32_consensus():
         x, _ = C.run(x0, port, 0.0, None, S.num_rounds(n), store32=True)
         m = consensus.consensus_error(x)
         assert m["max_dev"] <= 1e-6 * m["mean_norm"]
+
+
+def test_full_gradient_scale_and_noise_options():
+    """grad_scale = 1 with the full batch is the gradient of 1/2 ||A x - b||^2 (the paper's local loss, Sec. 5);
+    noise_std adds exactly noise_std * eps(seed, k, agent, column)."""
+    n, N, d = 3, 12, 5
+    A, b, _ = WL.lsq_data(n, N, d, seed=8)
+    idx = WL.full_batch_indices(n, N)
+    z = np.random.default_rng(2).standard_normal((n, d))
+    g = losses.make_minibatch_grad("lsq", A, b, idx, grad_scale=1.0)(z, 7)
+    for i in range(n):
+        f = lambda w: 0.5 * float(((A[i].astype(float) @ w - b[i]) ** 2).sum())
+        assert np.allclose(g[i], _fd(f, z[i]), rtol=1e-6, atol=1e-6)
+    gn = losses.make_minibatch_grad("lsq", A, b, idx, grad_scale=1.0, noise_std=5.0, seed=3)(z, 7)
+    for i in range(n):
+        assert np.allclose(gn[i] - g[i], 5.0 * noise.normals(3, 7, i, np.arange(d)), atol=1e-12)
+    # scale 1/B reproduces the default mean
+    gm = losses.make_minibatch_grad("lsq", A, b, idx)(z, 0)
+    gs = losses.make_minibatch_grad("lsq", A, b, idx, grad_scale=1.0 / N)(z, 0)
+    assert np.allclose(gm, gs, atol=1e-14)
+
+
+def test_step_size_schedule():
+    sp = WL.SPECS["paperlsq258_1p"]
+    assert WL.step_size(sp, 0) == 0.02 and WL.step_size(sp, 19) == 0.02
+    assert np.isclose(WL.step_size(sp, 20), 0.02 / 1.5) and np.isclose(WL.step_size(sp, 45), 0.02 / 1.5 ** 2)
+    assert WL.step_size(WL.SPECS["lsq5_2p"], 150) == 0.01

@@ -33,7 +33,11 @@ class WorkloadSpec:
     lr: float = 0.0
     iters: int = 0
     seed: int = 0
-    noise_std: float = 0.0
+    noise_std: float = 0.0     # additive Gaussian gradient noise
+    grad_scale: float = 0.0    # minibatch losses: 0 = mean over the batch, s = factor on the summed gradient
+    obs_noise: float = 0.1     # least squares: standard deviation of the measurement noise in b
+    lr_decay: float = 1.0      # step size is lr / lr_decay^(k // lr_decay_every)
+    lr_decay_every: int = 0
 
 
 # The five configurations.  CECA-1P exists for even n only (Table 1), so the two
@@ -50,9 +54,29 @@ SPECS = {
                               seed=3, noise_std=0.01),
     "quad30_1p": WorkloadSpec("quad30_1p", n=30, port=1, d=25_557_032, loss="quad_center", lr=0.1, iters=50,
                               seed=3, noise_std=0.01),
+    # the paper's own least-squares experiment (Sec. 5): full gradient of 1/2 ||A_i x - b_i||^2 plus N(0, 25 I)
+    # noise, n = 258 agents, d = 10, N = 50, step 0.02 divided by 1.5 every 20 iterations
+    "paperlsq258_1p": WorkloadSpec("paperlsq258_1p", n=258, port=1, d=10, loss="lsq", N=50, B=50, lr=0.02, iters=200,
+                                   seed=5, noise_std=5.0, grad_scale=1.0, obs_noise=0.1, lr_decay=1.5,
+                                   lr_decay_every=20),
+    "paperlsq258_2p": WorkloadSpec("paperlsq258_2p", n=258, port=2, d=10, loss="lsq", N=50, B=50, lr=0.02, iters=200,
+                                   seed=5, noise_std=5.0, grad_scale=1.0, obs_noise=0.1, lr_decay=1.5,
+                                   lr_decay_every=20),
     "logistic1023_2p": WorkloadSpec("logistic1023_2p", n=1023, port=2, d=4096, loss="logistic", N=512, B=16,
                                     lr=0.02, iters=2000, seed=4),
 }
+
+
+def step_size(spec: WorkloadSpec, k: int) -> float:
+    """Step size of iteration k under the workload's decay schedule."""
+    if spec.lr_decay_every:
+        return spec.lr / spec.lr_decay ** (k // spec.lr_decay_every)
+    return spec.lr
+
+
+def full_batch_indices(n: int, N: int) -> np.ndarray:
+    """Every agent uses all of its N rows: shape (1, n, N) int32 (one entry serves every iteration)."""
+    return np.tile(np.arange(N, dtype=np.int32), (1, n, 1))
 
 
 def shrink(spec: WorkloadSpec, **kw) -> WorkloadSpec:
