@@ -1,0 +1,73 @@
+"""HIP-graph capture of the launch-bound training loop: every replay must equal the eager result.
+
+The library only launches kernels on the caller's stream (no allocation, no memset, no synchronization),
+so a caller may capture a window of iterations and replay it."""
+import numpy as np
+import pytest
+
+import workloads as WL
+from oracle import schedule as OS
+from gpu_util import make_state
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2306_00256_amd as P
+    assert torch.cuda.is_available()
+    P.lib()
+    return torch, P
+
+
+@pytest.mark.parametrize("name", ["lsq6_1p", "lsq5_2p"])
+def test_graph_replays_equal_eager(env, name):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    sp = WL.SPECS[name]
+    n, d, N, B, port = sp.n, sp.d, sp.N, sp.B, sp.port
+    tau = OS.num_rounds(n)
+    window = 2 * tau                                   # even, so two-port ping-pong buffers end where they began
+    A, b, _ = WL.lsq_data(n, N, d, sp.seed)
+    idx = torch.from_numpy(WL.batch_indices(n, N, B, window, sp.seed)).cuda()
+    Ad, bd = torch.from_numpy(A).cuda(), torch.from_numpy(b).cuda()
+    loss = Bn.make_minibatch_loss(Bn.LOSS_LSQ, Ad, bd, N, B)
+    ws = torch.empty(P.dsgd_ceca_workspace_bytes(n, d, loss), dtype=torch.uint8, device="cuda")
+    x0 = 0.1 * WL.initial_state(n, d, sp.seed)
+
+    def run_window(S, T):
+        for k in range(window):
+            P.dsgd_ceca_step(S, T, n, d, loss, idx[k], sp.lr, k % tau, port, workspace=ws)
+            if port == 2:
+                S, T = T, S
+
+    replays = 4
+    # eager reference: the same window `replays` times
+    S = make_state(torch, x0)
+    T = S if port == 1 else make_state(torch, np.zeros_like(x0))
+    eager = []
+    for _ in range(replays):
+        run_window(S, T)
+        torch.cuda.synchronize()
+        eager.append(S.cpu().numpy().copy())
+
+    S2 = make_state(torch, x0)
+    T2 = S2 if port == 1 else make_state(torch, np.zeros_like(x0))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_window(S2, T2)                              # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    S2.copy_(make_state(torch, x0))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_window(S2, T2)
+    S2.copy_(make_state(torch, x0))                     # capture does not execute: restore the start state
+    for rep in range(replays):
+        graph.replay()
+        torch.cuda.synchronize()
+        scratch = torch.randn(1024, device="cuda").sum().item()      # unrelated eager work between replays
+        assert np.isfinite(scratch)
+        assert np.array_equal(S2.cpu().numpy(), eager[rep]), rep
