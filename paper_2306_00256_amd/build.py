@@ -20,7 +20,7 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = True) -> str:
+def build_library(verbose: bool = True, out: str = LIB, extra=()) -> str:
     """Compiles every source for gfx950 and links the shared library; always recompiles."""
     cmd = [
         hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -29,13 +29,14 @@ def build_library(verbose: bool = True) -> str:
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-command-line-argument",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+        *extra,
         *[os.path.join(CSRC, s) for s in SOURCES],
-        "-o", LIB,
+        "-o", out,
     ]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True, cwd=ROOT)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
