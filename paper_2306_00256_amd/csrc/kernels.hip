@@ -317,8 +317,10 @@ __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) 
   V x[RT], y[RT];
 #pragma unroll
   for (int k = 0; k < RT; ++k) {
-    const int i = rg + k * M.row_lanes;
-    x[k] = (i < M.n) ? ld_stream<V>(M.xin + (int64_t)i * M.ld + col) : V(0.0f);
+    // rows past the last agent shadow the last one (their values are never stored): no branch
+    // surrounds a load, so all of a thread's rows are in flight together
+    const int i = min(rg + k * M.row_lanes, M.n - 1);
+    x[k] = ld_stream<V>(M.xin + (int64_t)i * M.ld + col);
     y[k] = V(0.0f);                                // round 0 has b = 0: y(0) is never used
   }
   V* zs = reinterpret_cast<V*>(lds_z);
