@@ -101,8 +101,9 @@ int32_t ceca_schedule(int32_t n, int32_t r, int32_t port, ceca_round_t* out, int
  *   x_i+ = a x_i + (1-a) z_peer(i),   y_i+ = b y_i + (1-b) z_peer(i),   z = x or y by delta_r.
  * S_in, S_out: device, 2n rows of ld floats (d used); S_out is either disjoint from S_in or S_in
  * itself.  In place, a thread reads every row of a pair (port 1) or of a whole shift cycle (port 2)
- * before it writes it; out of place, long two-port cycles are cut into shorter stretches, which
- * exposes more parallelism.  Partial overlap is CECA_EINVAL.  n = 1 copies (r must be 0).
+ * before it writes it; out of place, two-port rounds are cut into one-row stretches that sweep the
+ * state band by band, which is the faster form on MI355X.  Partial overlap is CECA_EINVAL.
+ * n = 1 copies (r must be 0).
  * In round 0 (b = 0) the y rows of S_in are not read. */
 int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                           int32_t r, int32_t port, void* hip_stream);
@@ -124,7 +125,8 @@ int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss)
 /* One DSGD-CECA iteration (Algorithm 1, Eqs. (8), (9)) with the gradient fused in:
  *   e_i = grad at z_i,  v_i = z_i - lr e_i,
  *   x_i+ = a (x_i - lr e_i) + (1-a) v_peer(i),   y_i+ = b (y_i - lr e_i) + (1-b) v_peer(i).
- * batch_idx: device, n*B int32 in [0, N), row i = agent i's sampled rows (NULL for QUAD_CENTER).
+ * batch_idx: device, n*B int32 in [0, N), row i = agent i's sampled rows (NULL for QUAD_CENTER);
+ *   values outside [0, N) are clamped into it rather than followed.
  * workspace: device, 256-byte aligned, at least dsgd_ceca_workspace_bytes() (may be NULL when that is 0);
  * its contents are scratch.  Aliasing rules as ceca_gossip_round.  n = 1: plain SGD on x, y+ = x+. */
 int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,

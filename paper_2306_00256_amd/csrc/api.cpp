@@ -64,7 +64,7 @@ int32_t check_state_call(const float* S_in, float* S_out, int32_t n, int64_t d, 
 }
 
 // Chain shape for the round: which cycles the walk has and how they are cut into stretches.
-void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place, ceca::ChainArgs* a) {
+void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place, int64_t groups, ceca::ChainArgs* a) {
   a->n = n;
   if (n == 1) {
     // a lone agent: one closed stretch of one row; weights make x+ = x - lr e, and y+ follows the call
@@ -86,6 +86,10 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place,
   // streams), and the message a stretch re-reads is still in L2 from the stretch before it.
   int32_t seg_len = in_place ? len : g_opt_segment.load();
   if (seg_len <= 0) seg_len = 1;
+  if (seg_len > len) seg_len = len;
+  // a launch addresses fewer than 2^24 workgroups: huge problems walk longer stretches
+  const int64_t tiles = (groups + ceca::kBlock - 1) / ceca::kBlock;
+  while (seg_len < len && tiles * g * ((len + seg_len - 1) / seg_len) >= (1LL << 24)) seg_len *= 2;
   if (seg_len > len) seg_len = len;
   a->seg_len = seg_len;
   a->segs_per_cycle = (len + seg_len - 1) / seg_len;
@@ -110,7 +114,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   if (d4 > 0) {
     a.col0 = 0;
     a.ngroups = d4;
-    shape_chain(rd, a.n, port, in_place, &a);
+    shape_chain(rd, a.n, port, in_place, d4, &a);
     const hipError_t e = ceca::launch_chain(a, mode, true, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch");
   }
@@ -118,7 +122,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   if (rest > 0) {
     a.col0 = 4 * d4;
     a.ngroups = rest;
-    shape_chain(rd, a.n, port, in_place, &a);
+    shape_chain(rd, a.n, port, in_place, rest, &a);
     const hipError_t e = ceca::launch_chain(a, mode, false, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch (scalar columns)");
   }

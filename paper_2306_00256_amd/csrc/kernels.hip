@@ -425,6 +425,8 @@ __device__ __forceinline__ float dot_v(float a, float b) { return a * b; }
 // Minibatch row numbers are the same for every lane: keep them in scalar registers so that row
 // addresses are scalar and all row loads can be issued back to back.
 __device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+// A sampled row number, forced into [0, N): a bad index must not become a wild read.
+__device__ __forceinline__ int32_t sample_row(int32_t v, int32_t N) { return min(max(uniform_i32(v), 0), N - 1); }
 
 // partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col]
 template <int VEC>
@@ -453,7 +455,7 @@ __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
     V a[4][kChunkGroups];
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
-      const int32_t rj = uniform_i32(idx[min(j0 + jj, G.B - 1)]);   // rows past B repeat the last one
+      const int32_t rj = sample_row(idx[min(j0 + jj, G.B - 1)], G.N);   // rows past B repeat the last one
       const float* row = Abase + (int64_t)rj * G.lda;
 #pragma unroll
       for (int u = 0; u < kChunkGroups; ++u) a[jj][u] = ld_stream<V>(row + col[u]);
@@ -496,7 +498,7 @@ __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
     const int j = min((int)threadIdx.x, G.B - 1);
     float m = 0.0f;
     for (int ch = 0; ch < G.nchunks; ++ch) m += G.partial[((int64_t)agent * G.nchunks + ch) * G.B + j];
-    const int32_t row = G.batch_idx[(int64_t)agent * G.B + j];
+    const int32_t row = min(max(G.batch_idx[(int64_t)agent * G.B + j], 0), G.N - 1);
     const float t = G.t[(int64_t)agent * G.N + row];
     // entries past B repeat the last row with coefficient 0, so the row loop needs no bounds test
     coef[threadIdx.x] = ((int)threadIdx.x < G.B) ? loss_coef(G.kind, m, t, G.scale) : 0.0f;
@@ -545,7 +547,7 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
   const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
   int32_t rowid[BMAX];
 #pragma unroll
-  for (int j = 0; j < BMAX; ++j) rowid[j] = uniform_i32(idx[min(j, P.B - 1)]);   // rows past B repeat the last
+  for (int j = 0; j < BMAX; ++j) rowid[j] = sample_row(idx[min(j, P.B - 1)], P.N);   // rows past B repeat the last
   vf4 a[BMAX][G];
 #pragma unroll
   for (int j = 0; j < BMAX; ++j) {
@@ -569,7 +571,7 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
     float m = 0.0f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) m += red[w][j];
-    const float t = P.t[(int64_t)agent * P.N + idx[min(j, P.B - 1)]];
+    const float t = P.t[(int64_t)agent * P.N + min(max(idx[min(j, P.B - 1)], 0), P.N - 1)];
     coef[j] = (j < P.B) ? loss_coef(P.kind, m, t, P.scale) : 0.0f;
   }
   __syncthreads();

@@ -292,6 +292,32 @@ def test_paper_least_squares_experiment(env, name):
     assert np.abs(gx.mean(0) - xs).max() < 0.2 * err0          # the averaged model approaches x*
 
 
+@pytest.mark.parametrize("onepass", [1, 0])
+def test_out_of_range_batch_indices_are_clamped(env, onepass):
+    """Row numbers outside [0, N) are forced into range by the kernels (never followed)."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, N, B = 4, 512, 16, 4
+    A, b, _ = WL.lsq_data(n, N, d, seed=3)
+    idx = WL.batch_indices(n, N, B, 1, seed=3)
+    bad = idx.copy()
+    bad[0, 0, 0], bad[0, 1, 1], bad[0, 3, 3] = -7, N, 2 ** 30
+    good = np.clip(bad, 0, N - 1)
+    x0 = 0.1 * WL.initial_state(n, d, seed=4)
+    P.ceca_set_option(Bn.OPT_ONEPASS, onepass)
+    try:
+        outs = []
+        for ind in (bad, good):
+            Ad, bd, idxd, loss = _minibatch_problem(torch, Bn, "lsq", A, b, ind)
+            ws = _workspace(torch, P, n, d, loss)
+            S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
+            P.dsgd_ceca_step(S, T, n, d, loss, idxd[0], 0.01, 0, 2, workspace=ws)
+            outs.append(split_state(T, n, d))
+    finally:
+        P.ceca_set_option(Bn.OPT_ONEPASS, 1)
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
 def test_step_errors(env):
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
