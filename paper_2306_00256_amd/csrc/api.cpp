@@ -64,7 +64,8 @@ int32_t check_state_call(const float* S_in, float* S_out, int32_t n, int64_t d, 
 }
 
 // Chain shape for the round: which cycles the walk has and how they are cut into stretches.
-void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place, int64_t groups, ceca::ChainArgs* a) {
+void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place, bool round0_pairs, int64_t groups,
+                 ceca::ChainArgs* a) {
   a->n = n;
   if (n == 1) {
     // a lone agent: one closed stretch of one row; weights make x+ = x - lr e, and y+ follows the call
@@ -85,7 +86,7 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place,
   // stretches: the device then sweeps the rows of a column band one at a time (few concurrent DRAM
   // streams), and the message a stretch re-reads is still in L2 from the stretch before it.
   int32_t seg_len = in_place ? len : g_opt_segment.load();
-  if (seg_len <= 0) seg_len = 1;
+  if (seg_len <= 0) seg_len = round0_pairs ? 2 : 1;
   if (seg_len > len) seg_len = len;
   // a launch addresses fewer than 2^24 workgroups: huge problems walk longer stretches
   const int64_t tiles = (groups + ceca::kBlock - 1) / ceca::kBlock;
@@ -104,7 +105,14 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   const bool pairs = port == 1 || a.n == 1;
   // rows in flight per thread: closed pairs and in-place cycles of the fused step like the fattest
   // variant (it also runs fewer workgroups per CU); one-row stretches want more, lighter workgroups
-  if (rows == 0) rows = (mode == ceca::MODE_QUAD && (pairs || in_place)) ? 8 : 4;
+  // round 0 of the fused step (y not read: half the traffic is writes) measured best with the lightest
+  // variant, two-row stretches, wider bands and at most 4 workgroups per CU
+  const bool quad_round0 = mode == ceca::MODE_QUAD && !a.read_y && !(pairs || in_place);
+  if (rows == 0) rows = quad_round0 ? 1 : (mode == ceca::MODE_QUAD && (pairs || in_place)) ? 8 : 4;
+  if (quad_round0) {
+    if (a.band == 0) a.band = 512;
+    if (a.wg_per_cu == 0) a.wg_per_cu = 4;
+  }
   // band: about 7-10 MB of traffic between a row's own read and its re-read as a message, so that the
   // re-read hits L2 (32 MB over 8 XCDs; a tile and its successor land on the same XCD when the band
   // is a multiple of 8)
@@ -114,7 +122,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   if (d4 > 0) {
     a.col0 = 0;
     a.ngroups = d4;
-    shape_chain(rd, a.n, port, in_place, d4, &a);
+    shape_chain(rd, a.n, port, in_place, quad_round0, d4, &a);
     const hipError_t e = ceca::launch_chain(a, mode, true, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch");
   }
@@ -122,7 +130,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   if (rest > 0) {
     a.col0 = 4 * d4;
     a.ngroups = rest;
-    shape_chain(rd, a.n, port, in_place, rest, &a);
+    shape_chain(rd, a.n, port, in_place, quad_round0, rest, &a);
     const hipError_t e = ceca::launch_chain(a, mode, false, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch (scalar columns)");
   }
