@@ -76,3 +76,27 @@ def test_workspace_errors(env):
     with pytest.raises(P.CecaError) as e:
         P.consensus_error(X, 4, 64, out, workspace=small)
     assert e.value.code == Bn.CECA_EWORKSPACE
+
+
+def test_state_consensus_distance_of_x_and_y(env):
+    """The analysis' observable ||phi||_F^2 = ||x - 1 xbar^T||_F^2 + ||y - 1 ybar^T||_F^2 (App. B.3):
+    consensus_error on the x rows and on the y rows of a state, which is zero for both exactly after
+    tau + 1 gossip rounds and for x only after tau."""
+    torch, P = env
+    from oracle import schedule as OS
+    n, d = 12, 1500
+    x0 = WL.initial_state(n, d, seed=12)
+    S = torch.from_numpy(np.vstack([x0, x0])).cuda()
+    T = torch.empty_like(S)
+    tau = OS.num_rounds(n)
+    P.ceca_gossip_rounds(S, T, n, d, tau, 2)
+    gx, _ = _consensus(torch, P, T[:n], n, d, want_mean=False)
+    gy, _ = _consensus(torch, P, T[n:], n, d, want_mean=False)
+    want_y = OCONS.consensus_error((n * x0.astype(np.float64).mean(0) - x0.astype(np.float64)) / (n - 1))
+    assert gx[2] <= 1e-6 * gx[3]
+    assert np.isclose(gy[0], want_y["frob2"], rtol=1e-5)          # y_i = mean of the others: not at consensus yet
+    P.ceca_gossip_rounds(S, T, n, d, tau + 1, 2)
+    gx, _ = _consensus(torch, P, T[:n], n, d, want_mean=False)
+    gy, _ = _consensus(torch, P, T[n:], n, d, want_mean=False)
+    assert gx[2] <= 1e-6 * gx[3] and gy[2] <= 1e-6 * gy[3]
+    assert gx[0] + gy[0] <= 1e-11 * n * gx[3] ** 2

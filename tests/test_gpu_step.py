@@ -341,3 +341,28 @@ def test_step_errors(env):
     with pytest.raises(P.CecaError) as e:
         P.dsgd_ceca_step(S, T, n, d, loss, idx, 0.1, 2, 2, workspace=ws)      # r >= tau
     assert e.value.code == Bn.CECA_EINVAL
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 5])
+def test_tiny_dimensions(env, d):
+    """Fewer columns than one vector group: everything runs on the scalar kernels."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, N, B = 6, 1, 1
+    A, b, _ = WL.lsq_data(n, N, d, seed=d)
+    idx = WL.batch_indices(n, N, B, 4, seed=d)
+    x0 = WL.initial_state(n, d, seed=d + 1)
+    for port in (1, 2):
+        _, _, worst = _run_minibatch(torch, P, "lsq", A, b, idx, x0, port, 0.05, 4, teacher_forced=True)
+        assert worst <= TOL_STEP
+    c = WL.quad_centers(n, d, seed=d)
+    cd = torch.from_numpy(c).cuda()
+    grad = OL.make_quad_center_grad(c, 0.01, 9)
+    S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
+    x = y = x0.astype(np.float64)
+    for k in range(4):
+        P.dsgd_ceca_step(S, T, n, d, Bn.make_quad_center_loss(cd, 0.01, 9, k), None, 0.1, k % 3, 2)
+        S, T = T, S
+        x, y = OC.dsgd_ceca_step(x, y, k, 2, 0.1, grad, store32=True)
+    gx, gy = split_state(S, n, d)
+    assert max(rel_err(gx, x)) <= TOL_RUN and max(rel_err(gy, y)) <= TOL_RUN
