@@ -428,55 +428,44 @@ __device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amd
 // A sampled row number, forced into [0, N): a bad index must not become a wild read.
 __device__ __forceinline__ int32_t sample_row(int32_t v, int32_t N) { return min(max(uniform_i32(v), 0), N - 1); }
 
-// partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col]
+// partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col].
+// A workgroup takes one column chunk of kRowGroup sampled rows of one agent (grid: chunks x agents x row groups),
+// so few agents still spread over many workgroups.
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
   using V = typename VecOf<VEC>::T;
-  __shared__ float red[kBlock / 64][64];
+  __shared__ float red[kBlock / 64][kRowGroup];
   const int agent = blockIdx.y;
   const int chunk = blockIdx.x;
-  const int64_t c_lo = (int64_t)chunk * G.chunk_cols;
+  const int j0 = blockIdx.z * kRowGroup;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
   // lanes past the last column read column 0 instead and carry z = 0: no branch surrounds a load
-  V z[kChunkGroups];
-  int64_t col[kChunkGroups];
-#pragma unroll
-  for (int u = 0; u < kChunkGroups; ++u) {
-    const int64_t c = c_lo + ((int64_t)u * kBlock + threadIdx.x) * VEC;
-    const bool on = c + VEC <= G.d;
-    col[u] = on ? c : 0;
-    const V zv = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col[u]);
-    z[u] = on ? zv : V(0.0f);
-  }
+  const int64_t c = (int64_t)chunk * G.chunk_cols + (int64_t)threadIdx.x * VEC;
+  const bool on = c + VEC <= G.d;
+  const int64_t col = on ? c : 0;
+  const V zv = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
+  const V z = on ? zv : V(0.0f);
   const int32_t* idx = G.batch_idx + (int64_t)agent * G.B;
-  const float* Abase = G.A + (int64_t)agent * G.N * G.lda;
-  for (int j0 = 0; j0 < G.B; j0 += 4) {
-    V a[4][kChunkGroups];
+  const float* Abase = G.A + (int64_t)agent * G.N * G.lda + col;
+  V a[kRowGroup];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      const int32_t rj = sample_row(idx[min(j0 + jj, G.B - 1)], G.N);   // rows past B repeat the last one
-      const float* row = Abase + (int64_t)rj * G.lda;
-#pragma unroll
-      for (int u = 0; u < kChunkGroups; ++u) a[jj][u] = ld_stream<V>(row + col[u]);
-    }
-    float acc[4];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      acc[jj] = 0.0f;
-#pragma unroll
-      for (int u = 0; u < kChunkGroups; ++u) acc[jj] += dot_v(a[jj][u], z[u]);
-    }
-    int jj;
-    const float s = wave_sum_many<4>(acc, lane, jj);
-    if (lane < 4 && j0 + jj < G.B) red[wave][j0 + jj] = s;
+  for (int jj = 0; jj < kRowGroup; ++jj) {
+    const int32_t rj = sample_row(idx[min(j0 + jj, G.B - 1)], G.N);   // rows past B repeat the last one
+    a[jj] = ld_stream<V>(Abase + (int64_t)rj * G.lda);
   }
-  __syncthreads();
-  if ((int)threadIdx.x < G.B) {
-    float s = 0.0f;
+  float acc[kRowGroup];
 #pragma unroll
-    for (int w = 0; w < kBlock / 64; ++w) s += red[w][threadIdx.x];
-    G.partial[((int64_t)agent * G.nchunks + chunk) * G.B + threadIdx.x] = s;
+  for (int jj = 0; jj < kRowGroup; ++jj) acc[jj] = dot_v(a[jj], z);
+  int jj;
+  const float s = wave_sum_many<kRowGroup>(acc, lane, jj);
+  if (lane < kRowGroup) red[wave][jj] = s;
+  __syncthreads();
+  if ((int)threadIdx.x < kRowGroup && j0 + (int)threadIdx.x < G.B) {
+    float t = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w][threadIdx.x];
+    G.partial[((int64_t)agent * G.nchunks + chunk) * G.B + j0 + threadIdx.x] = t;
   }
 }
 
@@ -491,10 +480,10 @@ __device__ __forceinline__ float loss_coef(int kind, float m, float t, float sca
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
   using V = typename VecOf<VEC>::T;
-  __shared__ float coef[64 + 4];
-  __shared__ int32_t rowid[64 + 4];
+  __shared__ float coef[64 + kRowGroup];
+  __shared__ int32_t rowid[64 + kRowGroup];
   const int agent = blockIdx.y;
-  if ((int)threadIdx.x < 64 + 4) {
+  if ((int)threadIdx.x < 64 + kRowGroup) {
     const int j = min((int)threadIdx.x, G.B - 1);
     float m = 0.0f;
     for (int ch = 0; ch < G.nchunks; ++ch) m += G.partial[((int64_t)agent * G.nchunks + ch) * G.B + j];
@@ -509,12 +498,12 @@ __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
   if (col + VEC > G.d) return;
   V e = V(0.0f);
   const float* base = G.A + (int64_t)agent * G.N * G.lda + col;
-  for (int j0 = 0; j0 < G.B; j0 += 4) {
-    V r[4];
+  for (int j0 = 0; j0 < G.B; j0 += kRowGroup) {
+    V r[kRowGroup];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) r[jj] = ld_stream<V>(base + (int64_t)uniform_i32(rowid[j0 + jj]) * G.lda);
+    for (int jj = 0; jj < kRowGroup; ++jj) r[jj] = ld_stream<V>(base + (int64_t)uniform_i32(rowid[j0 + jj]) * G.lda);
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) e += coef[j0 + jj] * r[jj];
+    for (int jj = 0; jj < kRowGroup; ++jj) e += coef[j0 + jj] * r[jj];
   }
   if (G.noise_std != 0.0f) e += G.noise_std * noise_group<V>(col, noise_keys(G.seed, G.k, (uint32_t)agent));
   const V z = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
@@ -607,7 +596,7 @@ bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
 
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st) {
   if (g.nchunks < 1 || g.n > 65535) return hipErrorInvalidConfiguration;
-  dim3 grid((unsigned)g.nchunks, (unsigned)g.n), block(kBlock);
+  dim3 grid((unsigned)g.nchunks, (unsigned)g.n, (unsigned)((g.B + kRowGroup - 1) / kRowGroup)), block(kBlock);
   if (vec4) margins_kernel<4><<<grid, block, 0, st>>>(g);
   else margins_kernel<1><<<grid, block, 0, st>>>(g);
   return hipGetLastError();

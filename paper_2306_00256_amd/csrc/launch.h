@@ -109,7 +109,8 @@ hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);
 
 constexpr int kBlock = 256;          // threads per workgroup: 4 wavefronts of 64
-constexpr int kChunkGroups = 2;      // column groups per thread in the margins kernel
+constexpr int kChunkGroups = 1;      // column groups per thread in the margins kernel
+constexpr int kRowGroup = 8;         // sampled rows whose loads the two-pass gradient kernels keep in flight
 constexpr int64_t kConsTile = 1024;  // columns per workgroup in the consensus kernels
 
 }  // namespace ceca
