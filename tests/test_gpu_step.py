@@ -244,15 +244,33 @@ def test_logistic_hetero_config(env):
 
 
 def test_many_agent_logistic(env):
-    """n = 1023, d = 4096, B = 16 in the benchmark's launch shape (N cut to 64 rows per agent so the
-    oracle's copy of A stays small), 40 free-running iterations; then the whole 2000 at n = 63."""
+    """n = 1023, d = 4096, N = 512, B = 16 at full size, data drawn on the device exactly as bench.py draws it
+    (the oracle works on a host copy), 40 free-running iterations; then the whole 2000 at n = 63."""
     torch, P = env
+    from paper_2306_00256_amd import binding as Bn
     sp = WL.SPECS["logistic1023_2p"]
-    A, lab, _ = WL.logistic_data_sparse(sp.n, 64, sp.d, sp.seed)
-    idx = WL.batch_indices(sp.n, 64, sp.B, 40, sp.seed)
-    x0 = WL.initial_state(sp.n, sp.d, sp.seed, kind="zero")
-    (gx, gy), (x, y), _ = _run_minibatch(torch, P, "logistic", A, lab, idx, x0, 2, sp.lr, 40)
+    n, d, N, B = sp.n, sp.d, sp.N, sp.B
+    Ad, labd, _ = WL.device_logistic_sparse(n, N, d, sp.seed)
+    A, lab = Ad.cpu().numpy(), labd.cpu().numpy()
+    iters = 40
+    idx = WL.batch_indices(n, N, B, iters, sp.seed)
+    idxd = torch.from_numpy(idx).cuda()
+    loss = Bn.make_minibatch_loss(Bn.LOSS_LOGISTIC, Ad, labd, N, B)
+    ws = _workspace(torch, P, n, d, loss)
+    grad = OL.make_minibatch_grad("logistic", A, lab, idx)
+    ld = (d + 63) // 64 * 64
+    S = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
+    T = torch.empty_like(S)
+    x = y = np.zeros((n, d))
+    tau = OS.num_rounds(n)
+    for k in range(iters):
+        P.dsgd_ceca_step(S, T, n, d, loss, idxd[k], sp.lr, k % tau, 2, workspace=ws, ld=ld)
+        S, T = T, S
+        x, y = OC.dsgd_ceca_step(x, y, k, 2, sp.lr, grad, store32=True)
+    gx, gy = split_state(S, n, d)
     assert max(rel_err(gx, x)) <= TOL_RUN and max(rel_err(gy, y)) <= TOL_RUN
+    del Ad, labd, A, lab, S, T
+    torch.cuda.empty_cache()
     A, lab, _ = WL.logistic_data_sparse(63, sp.N, sp.d, sp.seed)
     idx = WL.batch_indices(63, sp.N, sp.B, sp.iters, sp.seed)
     x0 = WL.initial_state(63, sp.d, sp.seed, kind="zero")
