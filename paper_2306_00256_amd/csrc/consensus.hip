@@ -1,0 +1,172 @@
+// Consensus observables for gfx950 (see consensus_error in ceca.h).
+#include <hip/hip_runtime.h>
+
+#include "ceca.h"
+#include "device_util.h"
+#include "launch.h"
+
+namespace ceca {
+
+// ---------------------------------------------------------------------------------------------
+// Consensus observables: fp64 column mean, then per-agent squared distance to it.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void acc4(double (&s)[4], vf4 v) { s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w; }
+__device__ __forceinline__ void acc4(double (&s)[4], float v) { s[0] += v; }
+
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void colsum_kernel(const ConsensusArgs C) {
+  using V = typename VecOf<VEC>::T;
+  const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+  if (col + VEC > C.d) return;
+  const int grp = blockIdx.y;
+  const int i_lo = grp * C.agents_per_group;
+  const int i_hi = min(C.n, i_lo + C.agents_per_group);
+  double s[4] = {0.0, 0.0, 0.0, 0.0};
+  int i = i_lo;
+  for (; i + 4 <= i_hi; i += 4) {
+    V r[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r[q] = ld_plain<V>(C.X + (int64_t)(i + q) * C.ld + col);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc4(s, r[q]);
+  }
+  for (; i < i_hi; ++i) acc4(s, ld_plain<V>(C.X + (int64_t)i * C.ld + col));
+  double* dst = C.colsum + (int64_t)grp * C.d + col;
+#pragma unroll
+  for (int q = 0; q < VEC; ++q) dst[q] = s[q];
+}
+
+// slice 0 of colsum <- mean; optional fp32 copy; per-workgroup partial of ||xbar||^2
+__global__ __launch_bounds__(kBlock) void mean_kernel(const ConsensusArgs C) {
+  __shared__ double red[kBlock / 64];
+  double sq = 0.0;
+  const int64_t base = (int64_t)blockIdx.x * kConsTile;
+  for (int q = 0; q < (int)(kConsTile / kBlock); ++q) {
+    const int64_t col = base + q * kBlock + threadIdx.x;
+    if (col < C.d) {
+      double s = 0.0;
+      for (int g = 0; g < C.agent_groups; ++g) s += C.colsum[(int64_t)g * C.d + col];
+      const double m = s / (double)C.n;
+      C.colsum[col] = m;
+      if (C.xbar) C.xbar[col] = (float)m;
+      sq += m * m;
+    }
+  }
+  sq = wave_sum(sq);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+    C.normpart[blockIdx.x] = t;
+  }
+}
+
+__device__ __forceinline__ double sqdev(vf4 v, const double (&m)[4]) {
+  const double a = (double)v.x - m[0], b = (double)v.y - m[1], c = (double)v.z - m[2], d = (double)v.w - m[3];
+  return a * a + b * b + c * c + d * d;
+}
+__device__ __forceinline__ double sqdev(float v, const double (&m)[4]) {
+  const double a = (double)v - m[0];
+  return a * a;
+}
+
+// devpart[agent][tile] = sum over the tile's columns of (x[agent][col] - mean[col])^2
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void dev_kernel(const ConsensusArgs C) {
+  using V = typename VecOf<VEC>::T;
+  __shared__ double red[kBlock / 64];
+  const int64_t tile = blockIdx.x;
+  constexpr int PER = (int)(kConsTile / kBlock) / VEC;   // column groups per thread
+  double m[PER][4];
+  int64_t col[PER];
+  bool on[PER];
+#pragma unroll
+  for (int p = 0; p < PER; ++p) {
+    col[p] = tile * kConsTile + ((int64_t)p * kBlock + threadIdx.x) * VEC;
+    on[p] = col[p] + VEC <= C.d;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) m[p][q] = (on[p] && q < VEC) ? C.colsum[col[p] + q] : 0.0;
+  }
+  const int i_lo = blockIdx.y * C.dev_agents;
+  const int i_hi = min(C.n, i_lo + C.dev_agents);
+  for (int i = i_lo; i < i_hi; ++i) {
+    double s = 0.0;
+#pragma unroll
+    for (int p = 0; p < PER; ++p)
+      if (on[p]) s += sqdev(ld_plain<V>(C.X + (int64_t)i * C.ld + col[p]), m[p]);
+    s = wave_sum(s);
+    __syncthreads();   // red[] of the previous agent has been consumed
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+      C.devpart[(int64_t)i * C.ntiles + tile] = t;
+    }
+  }
+}
+
+// dev2[agent] = sum over tiles of devpart[agent][tile]
+__global__ __launch_bounds__(kBlock) void devsum_kernel(const ConsensusArgs C) {
+  __shared__ double red[kBlock / 64];
+  const int i = blockIdx.x;
+  double s = 0.0;
+  for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) s += C.devpart[(int64_t)i * C.ntiles + t];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+    C.dev2[i] = t;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void finish_kernel(const ConsensusArgs C) {
+  __shared__ double r0[kBlock / 64], r1[kBlock / 64], r2[kBlock / 64], r3[kBlock / 64];
+  double frob = 0.0, resid = 0.0, mx = 0.0, nrm = 0.0;
+  for (int i = threadIdx.x; i < C.n; i += kBlock) {
+    const double d2 = C.dev2[i];
+    const double dv = sqrt(d2);
+    frob += d2; resid += dv; mx = fmax(mx, dv);
+  }
+  for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) nrm += C.normpart[t];
+  frob = wave_sum(frob); resid = wave_sum(resid); mx = wave_max(mx); nrm = wave_sum(nrm);
+  if ((threadIdx.x & 63) == 0) {
+    const int w = threadIdx.x >> 6;
+    r0[w] = frob; r1[w] = resid; r2[w] = mx; r3[w] = nrm;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double a = 0.0, b = 0.0, c = 0.0, d = 0.0;
+    for (int w = 0; w < kBlock / 64; ++w) { a += r0[w]; b += r1[w]; c = fmax(c, r2[w]); d += r3[w]; }
+    C.out[0] = a; C.out[1] = b; C.out[2] = c; C.out[3] = sqrt(d); C.out[4] = (double)C.n;
+  }
+}
+
+hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st) {
+  const int vec = vec4 ? 4 : 1;
+  const int64_t groups = (c.d + vec - 1) / vec;
+  const int64_t gx = (groups + kBlock - 1) / kBlock;
+  const int64_t dev_gy = ((int64_t)c.n + c.dev_agents - 1) / c.dev_agents;
+  if (gx > 0x7fffffffLL || c.ntiles > 0x7fffffffLL || c.agent_groups > 65535 || dev_gy > 65535 || c.n > 0x7fffffff)
+    return hipErrorInvalidConfiguration;
+  dim3 block(kBlock);
+  {
+    dim3 grid((unsigned)gx, (unsigned)c.agent_groups);
+    if (vec4) colsum_kernel<4><<<grid, block, 0, st>>>(c);
+    else colsum_kernel<1><<<grid, block, 0, st>>>(c);
+  }
+  mean_kernel<<<dim3((unsigned)c.ntiles), block, 0, st>>>(c);
+  {
+    dim3 grid((unsigned)c.ntiles, (unsigned)dev_gy);
+    if (vec4) dev_kernel<4><<<grid, block, 0, st>>>(c);
+    else dev_kernel<1><<<grid, block, 0, st>>>(c);
+  }
+  devsum_kernel<<<dim3((unsigned)c.n), block, 0, st>>>(c);
+  finish_kernel<<<dim3(1), block, 0, st>>>(c);
+  return hipGetLastError();
+}
+
+}  // namespace ceca

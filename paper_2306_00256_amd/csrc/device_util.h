@@ -1,0 +1,137 @@
+// Device-side helpers shared by the gfx950 kernels: vector types, streaming loads and stores,
+// wavefront reductions, the counter-based Gaussian generator and the one rounding order of the
+// CECA combine.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace ceca {
+
+typedef float vf4 __attribute__((ext_vector_type(4)));
+
+template <int VEC> struct VecOf;
+template <> struct VecOf<4> { using T = vf4; };
+template <> struct VecOf<1> { using T = float; };
+
+// State rows are touched once per round: stream them past the caches (nontemporal loads and stores).
+template <typename V> __device__ __forceinline__ V ld_stream(const float* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+}
+template <typename V> __device__ __forceinline__ void st_stream(float* p, V v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
+}
+template <typename V> __device__ __forceinline__ V ld_plain(const float* p) {
+  return *reinterpret_cast<const V*>(p);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// Sums N per-lane values across the 64 lanes of a wavefront at once.  Each butterfly step halves the
+// number of values a lane carries (partners swap the halves they do not keep), so N values cost
+// N - 1 + (6 - log2 N) lane exchanges instead of 6 N.  On return lane l < N holds the complete sum
+// of value number `which`.
+template <int N>
+__device__ __forceinline__ float wave_sum_many(float (&m)[N], int lane, int& which) {
+  static_assert(N >= 1 && N <= 64 && (N & (N - 1)) == 0, "N must be a power of two");
+  which = 0;
+  int bit = 0;
+#pragma unroll
+  for (int len = N; len > 1; len >>= 1, ++bit) {
+    const bool up = (lane >> bit) & 1;
+    const int half = len / 2;
+#pragma unroll
+    for (int k = 0; k < half; ++k) {
+      const float send = up ? m[k] : m[k + half];
+      const float keep = up ? m[k + half] : m[k];
+      m[k] = keep + __shfl_xor(send, 1 << bit, 64);
+    }
+    which += up ? half : 0;
+  }
+  float v = m[0];
+#pragma unroll
+  for (int b = bit; b < 6; ++b) v += __shfl_xor(v, 1 << b, 64);
+  return v;
+}
+
+__device__ __forceinline__ float dot_v(vf4 a, vf4 b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }
+__device__ __forceinline__ float dot_v(float a, float b) { return a * b; }
+
+// ---------------------------------------------------------------------------------------------
+// Counter-based Gaussian noise (definition in ceca.h): one 32-bit word per uniform, Box-Muller
+// on column pairs.  Transcendentals use the hardware's log2 / sin / cos (arguments in turns).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t mix32(uint32_t h) {
+  h ^= h >> 16; h *= 0x7feb352du;
+  h ^= h >> 15; h *= 0x846ca68bu;
+  h ^= h >> 16;
+  return h;
+}
+__device__ __forceinline__ uint32_t noise_word(uint32_t c, uint32_t k0, uint32_t k1) {
+  uint32_t h = c ^ k0;
+  h ^= h >> 16; h *= 0x7feb352du;
+  h ^= h >> 15; h += k1; h *= 0x846ca68bu;
+  h ^= h >> 16;
+  return h;
+}
+struct NoiseKeys { uint32_t k0, k1; };
+__device__ __forceinline__ NoiseKeys noise_keys(uint32_t seed, uint32_t k, uint32_t agent) {
+  NoiseKeys nk;
+  nk.k0 = mix32(mix32(seed + 0x9e3779b9u * k) ^ agent);
+  nk.k1 = mix32(nk.k0 + 0x85ebca6bu);
+  return nk;
+}
+__device__ __forceinline__ void normal_pair(uint32_t q, NoiseKeys nk, float& e0, float& e1) {
+  const uint32_t w1 = noise_word(2u * q, nk.k0, nk.k1);
+  const uint32_t w2 = noise_word(2u * q + 1u, nk.k0, nk.k1);
+  const float u1 = (float)((w1 >> 8) + 1u) * 0x1p-24f;   // (0, 1], exact in fp32
+  const float u2 = (float)(w2 >> 8) * 0x1p-24f;          // [0, 1), exact in fp32
+  // -2 ln u1 = (-2 ln 2) log2 u1
+  const float rad = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u1));
+  e0 = rad * __builtin_amdgcn_cosf(u2);
+  e1 = rad * __builtin_amdgcn_sinf(u2);
+}
+template <typename V> __device__ __forceinline__ V noise_group(int64_t col, NoiseKeys nk);
+template <> __device__ __forceinline__ vf4 noise_group<vf4>(int64_t col, NoiseKeys nk) {
+  vf4 e;
+  float a, b;
+  const uint32_t q = (uint32_t)(col >> 1);     // col is a multiple of 4 on this path
+  normal_pair(q, nk, a, b);
+  e.x = a; e.y = b;
+  normal_pair(q + 1u, nk, a, b);
+  e.z = a; e.w = b;
+  return e;
+}
+template <> __device__ __forceinline__ float noise_group<float>(int64_t col, NoiseKeys nk) {
+  float a, b;
+  normal_pair((uint32_t)(col >> 1), nk, a, b);
+  return (col & 1) ? b : a;
+}
+
+// w * self + wp * msg, with one fixed rounding order wherever it is evaluated.
+__device__ __forceinline__ float combine(float w, float self, float wp, float msg) {
+#pragma clang fp contract(off)
+  const float t = wp * msg;
+  return __builtin_fmaf(w, self, t);
+}
+__device__ __forceinline__ vf4 combine(float w, vf4 self, float wp, vf4 msg) {
+  vf4 o;
+  o.x = combine(w, self.x, wp, msg.x); o.y = combine(w, self.y, wp, msg.y);
+  o.z = combine(w, self.z, wp, msg.z); o.w = combine(w, self.w, wp, msg.w);
+  return o;
+}
+
+}  // namespace ceca

@@ -1,0 +1,201 @@
+// Minibatch gradients of the GEMV-shaped losses for gfx950: margins a_ij . z_i, then e_i and the message.
+#include <hip/hip_runtime.h>
+
+#include "ceca.h"
+#include "device_util.h"
+#include "launch.h"
+
+namespace ceca {
+
+// Minibatch row numbers are the same for every lane: keep them in scalar registers so that row
+// addresses are scalar and all row loads can be issued back to back.
+__device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+// A sampled row number, forced into [0, N): a bad index must not become a wild read.
+__device__ __forceinline__ int32_t sample_row(int32_t v, int32_t N) { return min(max(uniform_i32(v), 0), N - 1); }
+
+// partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col].
+// A workgroup takes one column chunk of kRowGroup sampled rows of one agent (grid: chunks x agents x row groups),
+// so few agents still spread over many workgroups.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
+  using V = typename VecOf<VEC>::T;
+  __shared__ float red[kBlock / 64][kRowGroup];
+  const int agent = blockIdx.y;
+  const int chunk = blockIdx.x;
+  const int j0 = blockIdx.z * kRowGroup;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+  // lanes past the last column read column 0 instead and carry z = 0: no branch surrounds a load
+  const int64_t c = (int64_t)chunk * G.chunk_cols + (int64_t)threadIdx.x * VEC;
+  const bool on = c + VEC <= G.d;
+  const int64_t col = on ? c : 0;
+  const V zv = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
+  const V z = on ? zv : V(0.0f);
+  const int32_t* idx = G.batch_idx + (int64_t)agent * G.B;
+  const float* Abase = G.A + (int64_t)agent * G.N * G.lda + col;
+  V a[kRowGroup];
+#pragma unroll
+  for (int jj = 0; jj < kRowGroup; ++jj) {
+    const int32_t rj = sample_row(idx[min(j0 + jj, G.B - 1)], G.N);   // rows past B repeat the last one
+    a[jj] = ld_stream<V>(Abase + (int64_t)rj * G.lda);
+  }
+  float acc[kRowGroup];
+#pragma unroll
+  for (int jj = 0; jj < kRowGroup; ++jj) acc[jj] = dot_v(a[jj], z);
+  int jj;
+  const float s = wave_sum_many<kRowGroup>(acc, lane, jj);
+  if (lane < kRowGroup) red[wave][jj] = s;
+  __syncthreads();
+  if ((int)threadIdx.x < kRowGroup && j0 + (int)threadIdx.x < G.B) {
+    float t = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w][threadIdx.x];
+    G.partial[((int64_t)agent * G.nchunks + chunk) * G.B + j0 + threadIdx.x] = t;
+  }
+}
+
+// Loss derivative at margin m with target / label t, already divided by the batch size.
+__device__ __forceinline__ float loss_coef(int kind, float m, float t, float scale) {
+  // LOGISTIC: -t * sigma(-t m) with sigma(-u) = 1 / (1 + e^u); e^u = inf gives 0, e^u = 0 gives 1
+  const float cf = (kind == CECA_LOSS_LSQ) ? (m - t) : (-t / (1.0f + expf(t * m)));
+  return cf * scale;
+}
+
+// v_i = z_i - lr * e_i with e_i = sum_j coef_j a_ij; coef_j folds the loss derivative and the 1/B.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
+  using V = typename VecOf<VEC>::T;
+  __shared__ float coef[64 + kRowGroup];
+  __shared__ int32_t rowid[64 + kRowGroup];
+  const int agent = blockIdx.y;
+  if ((int)threadIdx.x < 64 + kRowGroup) {
+    const int j = min((int)threadIdx.x, G.B - 1);
+    float m = 0.0f;
+    for (int ch = 0; ch < G.nchunks; ++ch) m += G.partial[((int64_t)agent * G.nchunks + ch) * G.B + j];
+    const int32_t row = min(max(G.batch_idx[(int64_t)agent * G.B + j], 0), G.N - 1);
+    const float t = G.t[(int64_t)agent * G.N + row];
+    // entries past B repeat the last row with coefficient 0, so the row loop needs no bounds test
+    coef[threadIdx.x] = ((int)threadIdx.x < G.B) ? loss_coef(G.kind, m, t, G.scale) : 0.0f;
+    rowid[threadIdx.x] = row;
+  }
+  __syncthreads();
+  const int64_t col = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+  if (col + VEC > G.d) return;
+  V e = V(0.0f);
+  const float* base = G.A + (int64_t)agent * G.N * G.lda + col;
+  for (int j0 = 0; j0 < G.B; j0 += kRowGroup) {
+    V r[kRowGroup];
+#pragma unroll
+    for (int jj = 0; jj < kRowGroup; ++jj) r[jj] = ld_stream<V>(base + (int64_t)uniform_i32(rowid[j0 + jj]) * G.lda);
+#pragma unroll
+    for (int jj = 0; jj < kRowGroup; ++jj) e += coef[j0 + jj] * r[jj];
+  }
+  if (G.noise_std != 0.0f) e += G.noise_std * noise_group<V>(col, noise_keys(G.seed, G.k, (uint32_t)agent));
+  const V z = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
+  *reinterpret_cast<V*>(G.v + (int64_t)agent * G.ldv + col) = z - G.lr * e;
+}
+
+// One pass over the minibatch rows: a workgroup owns an agent, keeps its B sampled rows of A in
+// registers (B x G 16-byte groups per thread), reduces the B margins across the workgroup, and forms
+// v = z - lr * e from the same registers, so A is read from memory once per iteration.
+template <int THREADS, int BMAX, int G>
+__global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P) {
+  constexpr int WAVES = THREADS / 64;
+  __shared__ float red[WAVES][BMAX];
+  __shared__ float coef[BMAX];
+  const int agent = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // lanes past the last column read column 0 instead and carry z = 0: no branch surrounds a load
+  int64_t col[G];
+  bool on[G];
+  vf4 z[G];
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * 4;
+    on[u] = c < P.d;                       // d is a multiple of 4 on this path
+    col[u] = on[u] ? c : 0;
+    const vf4 zv = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
+    z[u] = on[u] ? zv : vf4(0.0f);
+  }
+  const int32_t* idx = P.batch_idx + (int64_t)agent * P.B;
+  const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
+  int32_t rowid[BMAX];
+#pragma unroll
+  for (int j = 0; j < BMAX; ++j) rowid[j] = sample_row(idx[min(j, P.B - 1)], P.N);   // rows past B repeat the last
+  vf4 a[BMAX][G];
+#pragma unroll
+  for (int j = 0; j < BMAX; ++j) {
+    const float* row = Abase + (int64_t)rowid[j] * P.lda;
+#pragma unroll
+    for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
+  }
+  float m[BMAX];
+#pragma unroll
+  for (int j = 0; j < BMAX; ++j) {
+    m[j] = 0.0f;
+#pragma unroll
+    for (int u = 0; u < G; ++u) m[j] += dot_v(a[j][u], z[u]);
+  }
+  int jrow;
+  const float msum = wave_sum_many<BMAX>(m, lane, jrow);
+  if (lane < BMAX) red[wave][jrow] = msum;
+  __syncthreads();
+  if ((int)threadIdx.x < BMAX) {
+    const int j = threadIdx.x;
+    float m = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) m += red[w][j];
+    const float t = P.t[(int64_t)agent * P.N + min(max(idx[min(j, P.B - 1)], 0), P.N - 1)];
+    coef[j] = (j < P.B) ? loss_coef(P.kind, m, t, P.scale) : 0.0f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    vf4 e = vf4(0.0f);
+#pragma unroll
+    for (int j = 0; j < BMAX; ++j) e += coef[j] * a[j][u];
+    if (P.noise_std != 0.0f) e += P.noise_std * noise_group<vf4>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
+    if (on[u]) *reinterpret_cast<vf4*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * e;
+  }
+}
+
+// Picks the one-pass variant whose register tile covers (B, d); false if none does.
+bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
+  const int64_t d4 = g.d / 4;
+  dim3 grid((unsigned)g.n);
+#define CECA_ONEPASS(T, BM, GG)                                          \
+  if (g.B <= BM && d4 <= (int64_t)T * GG) {                              \
+    grad_onepass_kernel<T, BM, GG><<<grid, dim3(T), 0, st>>>(g);         \
+    *err = hipGetLastError();                                            \
+    return true;                                                         \
+  }
+  CECA_ONEPASS(256, 16, 1)
+  CECA_ONEPASS(256, 32, 1)
+  CECA_ONEPASS(1024, 8, 1)
+  CECA_ONEPASS(1024, 16, 1)
+  CECA_ONEPASS(1024, 8, 2)
+  CECA_ONEPASS(1024, 4, 4)
+#undef CECA_ONEPASS
+  return false;
+}
+
+hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st) {
+  if (g.nchunks < 1 || g.n > 65535) return hipErrorInvalidConfiguration;
+  dim3 grid((unsigned)g.nchunks, (unsigned)g.n, (unsigned)((g.B + kRowGroup - 1) / kRowGroup)), block(kBlock);
+  if (vec4) margins_kernel<4><<<grid, block, 0, st>>>(g);
+  else margins_kernel<1><<<grid, block, 0, st>>>(g);
+  return hipGetLastError();
+}
+
+hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st) {
+  const int vec = vec4 ? 4 : 1;
+  const int64_t groups = (g.d + vec - 1) / vec;
+  const int64_t gx = (groups + kBlock - 1) / kBlock;
+  if (gx < 1 || gx > 0x7fffffffLL || g.n > 65535) return hipErrorInvalidConfiguration;
+  dim3 grid((unsigned)gx, (unsigned)g.n), block(kBlock);
+  if (vec4) halfstep_kernel<4><<<grid, block, 0, st>>>(g);
+  else halfstep_kernel<1><<<grid, block, 0, st>>>(g);
+  return hipGetLastError();
+}
+
+}  // namespace ceca

@@ -1,4 +1,5 @@
-// Internal interface between the C ABI (api.cpp) and the gfx950 kernels (kernels.hip).
+// Internal interface between the C ABI (api.cpp) and the gfx950 kernels (chain.hip, multi_round.hip,
+// gemv.hip, consensus.hip).
 #pragma once
 #include <hip/hip_runtime.h>
 

@@ -1,0 +1,88 @@
+// Fused gossip rounds for gfx950 (see ceca_gossip_rounds in ceca.h).
+#include <hip/hip_runtime.h>
+
+#include "ceca.h"
+#include "device_util.h"
+#include "launch.h"
+
+namespace ceca {
+
+// ---------------------------------------------------------------------------------------------
+// Several gossip rounds in one pass: a workgroup keeps a column tile of every agent's (x, y) in
+// registers and passes the travelling variable through LDS, so `rounds` rounds cost one read of x
+// and one write of x and y (12 bytes per agent-parameter) instead of `rounds` x 16.  Columns are
+// independent instances of the recursion (Sec. 3.1), and every round uses the same combine() as the
+// single-round kernel, so the result has the same bits as `rounds` separate calls.
+// ---------------------------------------------------------------------------------------------
+template <int VEC, int RT>
+__global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) {
+  using V = typename VecOf<VEC>::T;
+  extern __shared__ float lds_z[];                 // [n][lanes] groups of VEC floats
+  const int lanes = kBlock / M.row_lanes;          // column groups per row handled by this workgroup
+  const int cg = threadIdx.x % lanes;              // my column group inside the tile
+  const int rg = threadIdx.x / lanes;              // my first row; I own rows rg, rg + row_lanes, ...
+  const int64_t g = (int64_t)blockIdx.x * lanes + cg;
+  const bool on = g < M.ngroups;
+  const int64_t col = M.col0 + (on ? g : 0) * VEC; // lanes past the last column shadow column group 0
+
+  V x[RT], y[RT];
+#pragma unroll
+  for (int k = 0; k < RT; ++k) {
+    // rows past the last agent shadow the last one (their values are never stored): no branch
+    // surrounds a load, so all of a thread's rows are in flight together
+    const int i = min(rg + k * M.row_lanes, M.n - 1);
+    x[k] = ld_stream<V>(M.xin + (int64_t)i * M.ld + col);
+    y[k] = V(0.0f);                                // round 0 has b = 0: y(0) is never used
+  }
+  V* zs = reinterpret_cast<V*>(lds_z);
+  for (int t = 0; t < M.rounds; ++t) {
+    const MultiRound R = M.round[t];
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      const int i = rg + k * M.row_lanes;
+      if (i < M.n) zs[i * lanes + cg] = R.exch_y ? y[k] : x[k];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      const int i = rg + k * M.row_lanes;
+      if (i < M.n) {
+        int p;
+        if (M.port == 2) {
+          p = i - R.shift; if (p < 0) p += M.n;
+        } else {
+          p = (i & 1) ? i - R.shift : i + R.shift;
+          if (p < 0) p += M.n;
+          if (p >= M.n) p -= M.n;
+        }
+        const V zp = zs[p * lanes + cg];
+        x[k] = combine(R.a, x[k], R.ap, zp);
+        y[k] = R.read_y ? combine(R.b, y[k], R.bp, zp) : R.bp * zp;
+      }
+    }
+    __syncthreads();
+  }
+  if (!on) return;
+#pragma unroll
+  for (int k = 0; k < RT; ++k) {
+    const int i = rg + k * M.row_lanes;
+    if (i < M.n) {
+      st_stream<V>(M.xout + (int64_t)i * M.ld + col, x[k]);
+      st_stream<V>(M.yout + (int64_t)i * M.ld + col, y[k]);
+    }
+  }
+}
+
+hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st) {
+  if (m.ngroups <= 0) return hipSuccess;
+  const int lanes = kBlock / m.row_lanes;
+  const int64_t blocks = (m.ngroups + lanes - 1) / lanes;
+  if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
+  const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
+  dim3 grid((unsigned)blocks), block(kBlock);
+  if (vec4) multi_round_kernel<4, kMultiRows><<<grid, block, lds, st>>>(m);
+  else multi_round_kernel<1, kMultiRows><<<grid, block, lds, st>>>(m);
+  return hipGetLastError();
+}
+
+}  // namespace ceca
