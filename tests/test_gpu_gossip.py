@@ -207,3 +207,33 @@ def test_fused_rounds_fallbacks(env):
         assert np.abs(gx - x0.astype(np.float64).mean(0)).max() <= 2e-6
     with pytest.raises(P.CecaError):
         P.ceca_gossip_rounds(S, T, n, d, 0, 2)
+
+
+@pytest.mark.parametrize("n", [130, 1026])
+@pytest.mark.parametrize("port", [1, 2])
+def test_finite_time_consensus_residue(env, n, port):
+    """The paper's consensus experiment (Sec. 5, finite-time exact consensus; n = 130 and n = 1026 are its
+    comparison sizes): the residue sum_i ||x_i - x*|| after every round, measured on the device with
+    consensus_error, follows the oracle and drops to rounding level exactly at round tau."""
+    torch, P = env
+    d = 256
+    x0 = WL.initial_state(n, d, seed=n)
+    tau = OS.num_rounds(n)
+    S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
+    ws = torch.empty(P.consensus_error_workspace_bytes(n, d), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(5, dtype=torch.float64, device="cuda")
+    x = y = x0.astype(np.float64)
+    residues = []
+    for r in range(tau):
+        P.ceca_gossip_round(S, T, n, d, r, port)
+        S, T = T, S
+        P.consensus_error(S[:n], n, d, out, workspace=ws)
+        got = out.cpu().numpy()
+        x, y = OC.gossip_round(x, y, r, port, store32=True)
+        want = OCONS.consensus_error(x)
+        residues.append(got[1])
+        if r < tau - 1:
+            assert np.isclose(got[1], want["residue"], rtol=1e-5)
+            assert got[1] > 1e-3 * n                      # not at consensus before the last round
+    assert residues[-1] <= 1e-6 * n * np.sqrt(d) * 0.2      # ~1e-7 per entry
+    assert all(b < a for a, b in zip(residues, residues[1:]))
