@@ -155,7 +155,8 @@ int32_t ceca_last_hip_error(void);
 
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe against running calls):
  *   CECA_OPT_SEGMENT  agents a 2-port chain walks before it starts a new one (0 = library default)
- *   CECA_OPT_ROWS     state rows whose loads one thread keeps in flight: 1, 2, 4 or 8 (0 = library default)
+ *   CECA_OPT_ROWS     state rows whose loads one thread keeps in flight: 1, 2, 4 or 8 (0 = library default);
+ *                     for ceca_gossip_rounds: rows of the tile per thread, 4, 8 or 16
  *   CECA_OPT_BAND     column tiles (of 1024 columns) per band of the launch order (0 = library default)
  *   CECA_OPT_WG_PER_CU  cap on workgroups resident per compute unit, 2..8 (0 = library default)
  *   CECA_OPT_ONEPASS  1 (default): minibatch gradients keep the sampled rows in registers and read A once when

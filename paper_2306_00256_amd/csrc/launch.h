@@ -48,7 +48,7 @@ struct MultiRound {
   float a, ap, b, bp;
 };
 
-constexpr int kMultiRows = 16;       // rows of (x, y) a thread of the multi-round kernel keeps in registers
+constexpr int kMultiRows = 16;       // most rows of (x, y) a thread of the multi-round kernel keeps in registers
 constexpr int kMultiMaxRounds = 64;
 
 struct MultiArgs {
@@ -59,7 +59,8 @@ struct MultiArgs {
   int64_t col0;
   int64_t ngroups;
   int32_t n, port, rounds;
-  int32_t row_lanes;   // power of two >= ceil(n / kMultiRows): threads of a workgroup that share a column group
+  int32_t rows_per_thread;  // 4, 8 or 16 rows of (x, y) in a thread's registers
+  int32_t row_lanes;   // power of two >= ceil(n / rows_per_thread): threads of a workgroup that share a column group
   MultiRound round[kMultiMaxRounds];
 };
 

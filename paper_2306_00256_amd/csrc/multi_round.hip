@@ -80,8 +80,17 @@ hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st) {
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
   dim3 grid((unsigned)blocks), block(kBlock);
-  if (vec4) multi_round_kernel<4, kMultiRows><<<grid, block, lds, st>>>(m);
-  else multi_round_kernel<1, kMultiRows><<<grid, block, lds, st>>>(m);
+#define CECA_MULTI(RT)                                                         \
+  do {                                                                         \
+    if (vec4) multi_round_kernel<4, RT><<<grid, block, lds, st>>>(m);          \
+    else multi_round_kernel<1, RT><<<grid, block, lds, st>>>(m);               \
+  } while (0)
+  switch (m.rows_per_thread) {
+    case 4: CECA_MULTI(4); break;
+    case 8: CECA_MULTI(8); break;
+    default: CECA_MULTI(16); break;
+  }
+#undef CECA_MULTI
   return hipGetLastError();
 }
 

@@ -190,6 +190,23 @@ def test_fused_rounds_equal_separate_rounds(env, n, port):
     assert bool((S[:, d:] == 12345.0).all())
 
 
+def test_fused_rounds_tile_shapes_bit_identical(env):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d = 37, 1100
+    x0 = WL.initial_state(n, d, seed=3)
+    outs = []
+    try:
+        for rows in (0, 4, 8, 16):
+            P.ceca_set_option(Bn.OPT_ROWS, rows)
+            S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
+            P.ceca_gossip_rounds(S, T, n, d, 7, 2)
+            outs.append(T.cpu().numpy())
+    finally:
+        P.ceca_set_option(Bn.OPT_ROWS, 0)
+    assert all(np.array_equal(o, outs[0]) for o in outs[1:])
+
+
 def test_fused_rounds_fallbacks(env):
     torch, P = env
     # one agent: copies; more agents than one workgroup can hold: one launch per round
