@@ -122,6 +122,15 @@ def run_gossip(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
+    # all tau rounds fused into one pass (exact averaging): 12 bytes per agent-parameter in total
+    for _ in range(2):
+        P.ceca_gossip_rounds(S, T, n, d, tau, port, ld=ld)
+    reps = max(1, steps // tau)
+    with Timer(torch) as tf:
+        for _ in range(reps):
+            P.ceca_gossip_rounds(S, T, n, d, tau, port, ld=ld)
+    tm.fused = {"fused_rounds": tau, "fused_ms": tf.event_ms / reps,
+                "fused_GBs_on_12B": n * d * 12.0 / (tf.event_ms / reps * 1e-3) / 1e9}
     return tm, 1, chain_bytes("gossip", port, [k % tau for k in range(warmup, warmup + steps)])
 
 
@@ -199,6 +208,7 @@ def measure(torch, P, Bn, name, steps, warmup):
     ev_ms = tm.event_ms / steps
     units = sp.n * sp.d
     extra = {"graph_replay_ms_per_step": tm.graph_ms_per_step} if hasattr(tm, "graph_ms_per_step") else {}
+    extra.update(getattr(tm, "fused", {}))
     return {
         **extra,
         "workload": name, "n": sp.n, "d": sp.d, "port": sp.port, "loss": sp.loss, "steps": steps,
