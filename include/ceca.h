@@ -148,6 +148,16 @@ int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double
                         float* xbar_or_null, void* workspace, int64_t workspace_bytes,
                         void* hip_stream);
 
+/* Consensus observables of both halves of a state S = [x; y] (device, 2n rows of ld floats), each half
+ * about its own mean, and the squared norm of the stacked deviation phi that the consensus lemma
+ * bounds (App. B.3, definition of phi):
+ *   out[0..4]  = the five values of consensus_error for the x rows,
+ *   out[5..9]  = the same for the y rows,
+ *   out[10]    = ||phi||_F^2 = out[0] + out[5].
+ * out: device, 11 doubles.  workspace: as consensus_error (same size; the two halves use it in turn). */
+int32_t ceca_state_consensus(const float* S, int32_t n, int64_t d, int64_t ld, double* out,
+                             void* workspace, int64_t workspace_bytes, void* hip_stream);
+
 /* Message for the calling thread's most recent error ("" if none); valid until its next failing call. */
 const char* ceca_last_error(void);
 /* hipError_t value behind the calling thread's most recent CECA_EHIP (0 if none). */

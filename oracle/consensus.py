@@ -23,3 +23,12 @@ def consensus_error(x: np.ndarray):
         "mean_norm": float(np.sqrt((xbar ** 2).sum())),
         "mean": xbar,
     }
+
+
+def state_consensus(x: np.ndarray, y: np.ndarray):
+    """Consensus observables of the stacked state: those of x, those of y (each about its own mean),
+    and ||phi||_F^2 = ||x - 1 x_bar^T||_F^2 + ||y - 1 y_bar^T||_F^2, the quantity the consensus lemma
+    bounds (App. B.3, definition of phi before the consensus lemma)."""
+    cx = consensus_error(x)
+    cy = consensus_error(y)
+    return {"x": cx, "y": cy, "phi2": cx["frob2"] + cy["frob2"]}

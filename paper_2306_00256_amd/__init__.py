@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     ceca_schedule,
     ceca_set_option,
     ceca_tau,
+    ceca_state_consensus,
     consensus_error,
     consensus_error_workspace_bytes,
     dsgd_ceca_step,

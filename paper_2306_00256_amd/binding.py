@@ -14,7 +14,7 @@ OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS = 1, 2, 3, 4, 5
 
 EXPORTS = (
     "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step",
-    "consensus_error_workspace_bytes", "consensus_error", "ceca_last_error", "ceca_last_hip_error",
+    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_last_error", "ceca_last_hip_error",
     "ceca_set_option",
 )
 
@@ -74,6 +74,9 @@ def lib():
         L.consensus_error.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int64, C.c_void_p]
         L.consensus_error.restype = C.c_int32
+        L.ceca_state_consensus.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                           C.c_int64, C.c_void_p]
+        L.ceca_state_consensus.restype = C.c_int32
         L.ceca_last_error.restype = C.c_char_p
         L.ceca_last_hip_error.restype = C.c_int32
         L.ceca_set_option.argtypes = [C.c_int32, C.c_int32]
@@ -146,6 +149,13 @@ def consensus_error(X, n: int, d: int, out, xbar=None, workspace=None, ld: Optio
     ld = int(X.stride(0)) if ld is None else ld
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().consensus_error(_ptr(X), n, d, ld, _ptr(out), _ptr(xbar), _ptr(workspace), wbytes, _stream(stream)))
+
+
+def ceca_state_consensus(S, n: int, d: int, out, workspace=None, ld: Optional[int] = None, stream=None) -> None:
+    """out: device float64 tensor of 11 (x part, y part, ||phi||_F^2); see include/ceca.h."""
+    ld = int(S.stride(0)) if ld is None else ld
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().ceca_state_consensus(_ptr(S), n, d, ld, _ptr(out), _ptr(workspace), wbytes, _stream(stream)))
 
 
 def ceca_set_option(option: int, value: int) -> None:

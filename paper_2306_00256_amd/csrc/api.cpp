@@ -454,4 +454,17 @@ int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double
   return CECA_OK;
 }
 
+int32_t ceca_state_consensus(const float* S, int32_t n, int64_t d, int64_t ld, double* out, void* workspace,
+                             int64_t workspace_bytes, void* hip_stream) {
+  if (!S || !out) return fail(CECA_EINVAL, "null pointer");
+  if (n < 1 || d < 1 || ld < d) return fail(CECA_EINVAL, "need n >= 1 and 1 <= d <= ld");
+  int32_t rc = consensus_error(S, n, d, ld, out, nullptr, workspace, workspace_bytes, hip_stream);
+  if (rc != CECA_OK) return rc;
+  rc = consensus_error(S + (int64_t)n * ld, n, d, ld, out + 5, nullptr, workspace, workspace_bytes, hip_stream);
+  if (rc != CECA_OK) return rc;
+  const hipError_t e = ceca::launch_phi(out, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "phi kernel launch");
+  return CECA_OK;
+}
+
 }  // extern "C"

@@ -145,6 +145,16 @@ __global__ __launch_bounds__(kBlock) void finish_kernel(const ConsensusArgs C) {
   }
 }
 
+// out[10] = out[0] + out[5]: the two halves' Frobenius terms of ||phi||_F^2
+__global__ void phi_kernel(double* out) {
+  if (threadIdx.x == 0) out[10] = out[0] + out[5];
+}
+
+hipError_t launch_phi(double* out, hipStream_t st) {
+  phi_kernel<<<dim3(1), dim3(64), 0, st>>>(out);
+  return hipGetLastError();
+}
+
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st) {
   const int vec = vec4 ? 4 : 1;
   const int64_t groups = (c.d + vec - 1) / vec;

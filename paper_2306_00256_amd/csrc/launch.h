@@ -109,6 +109,8 @@ hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);
+// out[10] = out[0] + out[5] (11 doubles on the device)
+hipError_t launch_phi(double* out, hipStream_t st);
 
 constexpr int kBlock = 256;          // threads per workgroup: 4 wavefronts of 64
 constexpr int kChunkGroups = 1;      // column groups per thread in the margins kernel

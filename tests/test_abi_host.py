@@ -84,5 +84,8 @@ def test_host_side_errors(api):
     assert L.ceca_gossip_round(p, p, 4, 8, 8, 2, 1, None) == Bn.CECA_EINVAL          # r >= tau
     assert b"outside" in L.ceca_last_error()
     assert api.consensus_error_workspace_bytes(31, 25_557_032) > 0
+    assert L.ceca_state_consensus(None, 4, 8, 8, p, p, 1 << 20, None) == Bn.CECA_EINVAL
+    assert L.ceca_state_consensus(p, 4, 8, 4, p, p, 1 << 20, None) == Bn.CECA_EINVAL   # ld < d
+    assert L.ceca_state_consensus(p, 4, 8, 8, p, p, 8, None) == Bn.CECA_EWORKSPACE     # workspace too small
     with pytest.raises(api.CecaError):
         api.ceca_set_option(99, 1)

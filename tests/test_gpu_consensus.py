@@ -100,3 +100,39 @@ def test_state_consensus_distance_of_x_and_y(env):
     gy, _ = _consensus(torch, P, T[n:], n, d, want_mean=False)
     assert gx[2] <= 1e-6 * gx[3] and gy[2] <= 1e-6 * gy[3]
     assert gx[0] + gy[0] <= 1e-11 * n * gx[3] ** 2
+
+
+@pytest.mark.parametrize("n,d,pad", [(1, 7, 0), (5, 1000, 0), (6, 1037, 3), (31, 40_001, 7), (258, 10, 0), (1023, 4096, 0)])
+def test_state_consensus_entry_point(env, n, d, pad):
+    """ceca_state_consensus on a state some gossip rounds into a run: x part, y part and ||phi||_F^2
+    against the fp64 oracle on the same stored state (aligned and ragged layouts, one agent)."""
+    torch, P = env
+    ld = d + pad
+    x0 = WL.initial_state(n, d, seed=n + 1)
+    y0 = WL.initial_state(n, d, seed=n + 2)
+    S = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
+    S[:n, :d] = torch.from_numpy(x0).cuda()
+    S[n:, :d] = torch.from_numpy(y0).cuda()
+    T = torch.zeros_like(S)
+    port = 2 if n % 2 else 1
+    if n > 1:
+        P.ceca_gossip_round(S, T, n, d, 0, port, ld=ld)
+        P.ceca_gossip_round(T, S, n, d, 1, port, ld=ld)
+    ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    out = torch.full((11,), -1.0, dtype=torch.float64, device="cuda")
+    P.ceca_state_consensus(S, n, d, out, workspace=ws, ld=ld)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    host = S.cpu().numpy()
+    want = OCONS.state_consensus(host[:n, :d], host[n:, :d])
+    for off, key in ((0, "x"), (5, "y")):
+        w = want[key]
+        scale = max(w["mean_norm"] ** 2 * n, w["frob2"], 1e-30)
+        assert abs(got[off + 0] - w["frob2"]) <= 1e-10 * scale
+        assert abs(got[off + 1] - w["residue"]) <= 1e-9 * max(w["residue"], np.sqrt(scale))
+        assert abs(got[off + 2] - w["max_dev"]) <= 1e-9 * max(w["max_dev"], np.sqrt(scale))
+        assert abs(got[off + 3] - w["mean_norm"]) <= 1e-10 * max(w["mean_norm"], 1e-30)
+        assert got[off + 4] == n
+    assert got[10] == got[0] + got[5]
+    assert abs(got[10] - want["phi2"]) <= 1e-10 * max(want["phi2"], n * want["x"]["mean_norm"] ** 2)

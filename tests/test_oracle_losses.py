@@ -137,6 +137,32 @@ def test_consensus_metrics_closed_form():
     assert np.isclose(m["mean_norm"], 5.0)
 
 
+def test_state_consensus_closed_forms():
+    """||phi||_F^2 (App. B.3): worked 3-agent example; n * total column variance (library routine);
+    and the gossip-only trajectory, where after tau rounds the x part is zero and y_i is the mean of
+    the other agents' inputs, so ||phi||^2 = ||u - 1 u_bar^T||_F^2 / (n-1)^2 (matrix-consensus lemma),
+    and one round later phi = 0 (Lemma 4.2)."""
+    x = np.array([[1.0, 2.0], [3.0, 6.0], [5.0, 4.0]])
+    y = np.array([[0.0, 0.0], [2.0, 0.0], [4.0, 3.0]])       # mean (2, 1); deviations (-2,-1), (0,-1), (2,2)
+    m = consensus.state_consensus(x, y)
+    assert np.isclose(m["x"]["frob2"], 16.0) and np.isclose(m["y"]["frob2"], 5 + 1 + 8)
+    assert np.isclose(m["phi2"], 30.0)
+    assert np.allclose(m["y"]["mean"], [2.0, 1.0])
+    rng = np.random.default_rng(11)
+    for n, port in [(5, 2), (6, 1), (31, 2), (100, 1)]:
+        u = rng.standard_normal((n, 7)) + 3.0
+        w = rng.standard_normal((n, 7))
+        m = consensus.state_consensus(u, w)
+        assert np.isclose(m["phi2"], n * (np.var(u, axis=0).sum() + np.var(w, axis=0).sum()), rtol=1e-12)
+        tau = S.num_rounds(n)
+        xs, ys = C.run(u, port, 0.0, None, tau, store32=False)
+        m = consensus.state_consensus(xs, ys)
+        assert m["x"]["frob2"] < 1e-24
+        assert np.isclose(m["phi2"], consensus.consensus_error(u)["frob2"] / (n - 1) ** 2, rtol=1e-10)
+        xs, ys = C.gossip_round(xs, ys, 0, port)
+        assert consensus.state_consensus(xs, ys)["phi2"] < 1e-24
+
+
 def test_mirror_mode_reaches_fp32_consensus():
     """The gate used on the device: after tau rounds max_i ||x_i - x_bar|| <= 1e-6 ||x_bar|| with fp32 storage."""
     for n, port in [(5, 2), (6, 1), (31, 2), (100, 1), (100, 2)]:
