@@ -24,4 +24,8 @@ Pin status (see tests/test_oracle_*.py):
       pinned only statistically (mean, variance, independence) -- *parity unpinned*
       as to the specific stream
   consensus metrics .............................. pinned by closed forms on hand-made inputs
+  comparison topologies (ring, static / one-peer exponential gossip) ... defined by the works
+      the paper cites, not by the paper: pinned by stochasticity, three codings agreeing
+      (per agent, dense, circular convolution), one-hot direction checks, the power-of-two
+      exact-averaging property and its equality with CECA; *parity unpinned by the paper*
 """
