@@ -5,7 +5,7 @@ A step is one pass of the whole hot path over one batch of synthetic input: one 
 (gradient + CECA round fused) for the training workloads, one ceca_gossip_round call for the pure
 gossip workloads.  Inputs are generated on the device before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--others] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--others] [--mix-only] [--no-cpu]
 """
 from __future__ import annotations
 
@@ -199,6 +199,32 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
     return tm, launches, minibatch_bytes(B)
 
 
+def run_mix(torch, P, Bn, n, d, steps, warmup):
+    """Comparison-topology gossip (ring, static / one-peer exponential) at the sizes of the paper's consensus
+    comparison: tau rounds fused into one ceca_mix_rounds call; 8 algorithmic bytes per agent-parameter
+    for the whole call (x read once, written once)."""
+    tau = _tau(n)
+    ld = _ld(d)
+    X = torch.empty((n, ld), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, ld), n, out=X)
+    Y = torch.empty_like(X)
+    kinds = {"ring": [P.ceca_topology_round(Bn.TOPO_RING, n)],
+             "static_exp": [P.ceca_topology_round(Bn.TOPO_STATIC_EXP, n)],
+             "one_peer_exp": [P.ceca_topology_round(Bn.TOPO_ONE_PEER_EXP, n, k) for k in range(tau)]}
+    out = {"workload": f"mix{n}", "n": n, "d": d, "rounds_fused": tau, "algorithmic_bytes_per_agent_param": 8}
+    for kind, specs in kinds.items():
+        for _ in range(warmup):
+            P.ceca_mix_rounds(X, Y, n, d, specs, tau, ld=ld)
+        tm = Timer(torch)
+        with tm:
+            for _ in range(steps):
+                P.ceca_mix_rounds(X, Y, n, d, specs, tau, ld=ld)
+        ms = tm.event_ms / steps
+        out[kind] = {"ms_per_call": ms, "GBs": 8.0 * n * d / (ms * 1e-3) / 1e9,
+                     "agent_param_rounds_per_s": tau * n * d / (ms * 1e-3)}
+    return out
+
+
 def measure(torch, P, Bn, name, steps, warmup):
     sp = WL.SPECS[name]
     fn = {"quad_center": run_quad, "none": run_gossip}.get(sp.loss, run_minibatch)
@@ -300,6 +326,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="quad31_2p", choices=sorted(WL.SPECS))
     ap.add_argument("--others", action="store_true", help="also time the remaining workloads (reported under 'others')")
+    ap.add_argument("--mix-only", action="store_true",
+                    help="time only the comparison-topology gossip rounds (n = 130 and n = 1026) and exit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run one plain 1 GiB device copy (calibrates rocprofv3 byte counters)")
@@ -319,6 +347,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+
+    if args.mix_only:
+        print(json.dumps({"mix": [run_mix(torch, P, Bn, 130, 1 << 20, args.steps, args.warmup),
+                                  run_mix(torch, P, Bn, 1026, 1 << 17, args.steps, args.warmup)]}), flush=True)
+        return
 
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -361,6 +394,8 @@ def main():
             sp_o = WL.SPECS[name]
             k = 50 if sp_o.loss in ("quad_center",) else (70 if sp_o.loss == "none" else 200)
             out["others"].append(measure(torch, P, Bn, name, k, 5))
+        out["others"].append(run_mix(torch, P, Bn, 130, 1 << 20, 20, 3))
+        out["others"].append(run_mix(torch, P, Bn, 1026, 1 << 17, 20, 3))
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(sp)
     print(json.dumps(out), flush=True)

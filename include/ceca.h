@@ -158,6 +158,39 @@ int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double
 int32_t ceca_state_consensus(const float* S, int32_t n, int64_t d, int64_t ld, double* out,
                              void* workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* ---- Shift-invariant gossip averaging (the comparison topologies of Table 1 and of the consensus
+ * comparison in Sec. 5; their definitions are those of the works cited there) ----
+ * One round:  x_i+ = w_self x_i + sum_{j < m} w[j] x_{(i - shift[j]) mod n}   on x alone (n rows).
+ * Evaluated as t = w[0] z_0, t = fma(w[j], z_j, t) for j = 1.., x+ = fma(w_self, x, t), so a round with
+ * m = 1 has the bits of a CECA round with the same weights. */
+#define CECA_MIX_MAX 16
+typedef struct {
+  int32_t m;                      /* 0 .. CECA_MIX_MAX peers */
+  float   w_self;
+  int32_t shift[CECA_MIX_MAX];    /* each in [0, n) */
+  float   w[CECA_MIX_MAX];
+} ceca_mix_t;
+
+enum {
+  CECA_TOPO_RING = 0,             /* shifts 1 and n-1, weights 1/3 (n = 2: 1/2, 1/2; n = 1: identity)       */
+  CECA_TOPO_STATIC_EXP = 1,       /* shifts 2^0 .. 2^(tau-1), every weight 1/(tau+1)                        */
+  CECA_TOPO_ONE_PEER_EXP = 2      /* round k: shift 2^(k mod tau), weights 1/2, 1/2 (CECA when n = 2^tau)   */
+};
+
+/* Host: round k of a topology.  w[j] = (float) of the exact weight, w_self = (float)(1 - sum_j w[j])
+ * so that the rounded weights still sum to one.  Static topologies ignore k.  Returns CECA_EINVAL
+ * for n < 1, k < 0 or an unknown kind. */
+int32_t ceca_topology_round(int32_t kind, int32_t n, int32_t k, ceca_mix_t* out);
+
+/* `rounds` mixing rounds in one pass over X (device, n rows of ld floats): round t applies
+ * specs[(k0 + t) mod period] (specs: host, `period` entries, at most 64 peers over the period).
+ * A workgroup keeps a column tile of every agent in registers and passes rows through LDS, so any number
+ * of rounds moves 8 bytes per agent-parameter.  X_out may be X_in or disjoint from it.  Limits: n <= 4096.
+ * Asynchronous on the stream; specs is read before the call returns. */
+int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, int64_t ld,
+                        const ceca_mix_t* specs, int32_t period, int32_t k0, int32_t rounds,
+                        void* hip_stream);
+
 /* Message for the calling thread's most recent error ("" if none); valid until its next failing call. */
 const char* ceca_last_error(void);
 /* hipError_t value behind the calling thread's most recent CECA_EHIP (0 if none). */
@@ -167,6 +200,7 @@ int32_t ceca_last_hip_error(void);
  *   CECA_OPT_SEGMENT  agents a 2-port chain walks before it starts a new one (0 = library default)
  *   CECA_OPT_ROWS     state rows whose loads one thread keeps in flight: 1, 2, 4 or 8 (0 = library default);
  *                     for ceca_gossip_rounds: rows of the tile per thread, 4, 8 or 16
+ *                     for ceca_mix_rounds: most rows of the tile per thread, a multiple of 4 up to 32
  *   CECA_OPT_BAND     column tiles (of 1024 columns) per band of the launch order (0 = library default)
  *   CECA_OPT_WG_PER_CU  cap on workgroups resident per compute unit, 2..8 (0 = library default)
  *   CECA_OPT_ONEPASS  1 (default): minibatch gradients keep the sampled rows in registers and read A once when

@@ -7,12 +7,15 @@ fails if the library has not been built (python -m paper_2306_00256_amd.build).
 from .binding import (  # noqa: F401
     CecaError,
     Loss,
+    Mix,
     Round,
     ceca_gossip_round,
     ceca_gossip_rounds,
+    ceca_mix_rounds,
     ceca_schedule,
     ceca_set_option,
     ceca_tau,
+    ceca_topology_round,
     ceca_state_consensus,
     consensus_error,
     consensus_error_workspace_bytes,

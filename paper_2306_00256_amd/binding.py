@@ -3,7 +3,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import List, Optional, Tuple
+from typing import List, Optional, Sequence, Tuple
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libceca.so")
@@ -11,10 +11,12 @@ _LIB_PATH = os.path.join(_HERE, "libceca.so")
 CECA_OK, CECA_EINVAL, CECA_EODD1P, CECA_EWORKSPACE, CECA_EHIP = 0, -1, -2, -3, -4
 LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER = 0, 1, 2
 OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS = 1, 2, 3, 4, 5
+TOPO_RING, TOPO_STATIC_EXP, TOPO_ONE_PEER_EXP = 0, 1, 2
+MIX_MAX = 16
 
 EXPORTS = (
     "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step",
-    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_last_error", "ceca_last_hip_error",
+    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_last_error", "ceca_last_hip_error",
     "ceca_set_option",
 )
 
@@ -37,6 +39,11 @@ class Loss(C.Structure):
     _fields_ = [("kind", C.c_int32), ("N", C.c_int32), ("B", C.c_int32), ("seed", C.c_uint32), ("k", C.c_uint32),
                 ("noise_std", C.c_float), ("grad_scale", C.c_float), ("A", C.c_void_p), ("lda", C.c_int64), ("t", C.c_void_p),
                 ("c", C.c_void_p), ("ldc", C.c_int64)]
+
+
+class Mix(C.Structure):
+    """ceca_mix_t"""
+    _fields_ = [("m", C.c_int32), ("w_self", C.c_float), ("shift", C.c_int32 * MIX_MAX), ("w", C.c_float * MIX_MAX)]
 
 
 _lib = None
@@ -77,6 +84,11 @@ def lib():
         L.ceca_state_consensus.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                            C.c_int64, C.c_void_p]
         L.ceca_state_consensus.restype = C.c_int32
+        L.ceca_topology_round.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(Mix)]
+        L.ceca_topology_round.restype = C.c_int32
+        L.ceca_mix_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Mix), C.c_int32,
+                                      C.c_int32, C.c_int32, C.c_void_p]
+        L.ceca_mix_rounds.restype = C.c_int32
         L.ceca_last_error.restype = C.c_char_p
         L.ceca_last_hip_error.restype = C.c_int32
         L.ceca_set_option.argtypes = [C.c_int32, C.c_int32]
@@ -126,6 +138,20 @@ def ceca_gossip_rounds(S_in, S_out, n: int, d: int, rounds: int, port: int, ld: 
     """`rounds` gradient-free rounds starting at round 0, fused into one pass."""
     ld = int(S_in.stride(0)) if ld is None else ld
     _check(lib().ceca_gossip_rounds(_ptr(S_in), _ptr(S_out), n, d, ld, rounds, port, _stream(stream)))
+
+
+def ceca_topology_round(kind: int, n: int, k: int = 0) -> Mix:
+    m = Mix()
+    _check(lib().ceca_topology_round(kind, n, k, C.byref(m)))
+    return m
+
+
+def ceca_mix_rounds(X_in, X_out, n: int, d: int, specs: Sequence[Mix], rounds: int, k0: int = 0,
+                    ld: Optional[int] = None, stream=None) -> None:
+    """`rounds` shift-invariant mixing rounds on x alone; round t applies specs[(k0 + t) % len(specs)]."""
+    ld = int(X_in.stride(0)) if ld is None else ld
+    arr = (Mix * len(specs))(*specs)
+    _check(lib().ceca_mix_rounds(_ptr(X_in), _ptr(X_out), n, d, ld, arr, len(specs), k0, rounds, _stream(stream)))
 
 
 def dsgd_ceca_workspace_bytes(n: int, d: int, loss: Loss) -> int:

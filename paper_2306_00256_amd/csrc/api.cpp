@@ -231,8 +231,8 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       g_opt_segment.store(value);
       return CECA_OK;
     case CECA_OPT_ROWS:
-      if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16)
-        return fail(CECA_EINVAL, "rows must be 0, 1, 2, 4, 8 or 16");
+      if (value != 0 && value != 1 && value != 2 && !(value >= 4 && value <= 32 && value % 4 == 0))
+        return fail(CECA_EINVAL, "rows must be 0, 1, 2 or a multiple of 4 up to 32");
       g_opt_rows.store(value);
       return CECA_OK;
     case CECA_OPT_WG_PER_CU:
@@ -295,10 +295,11 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
   const int32_t tau = ceca::tau_of(n);
   // rows per thread: 8 leaves room for twice as many workgroups per CU (measured 1.5x faster at n = 100)
   // as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
-  int32_t rpt = g_opt_rows.load();
-  if (rpt != 4 && rpt != 8 && rpt != 16) rpt = (n <= 256) ? 8 : ceca::kMultiRows;
+  int32_t cap = g_opt_rows.load();
+  if (cap < 4 || cap > ceca::kMultiRows) cap = (n <= 256) ? 8 : ceca::kMultiRows;
   int32_t row_lanes = 1;
-  while (row_lanes * rpt < n) row_lanes *= 2;
+  while (row_lanes * cap < n) row_lanes *= 2;
+  const int32_t rpt = (n + row_lanes - 1) / row_lanes;   // exactly the rows n needs with that many row lanes
   if (n == 1 || rounds > ceca::kMultiMaxRounds || row_lanes > ceca::kBlock) {
     // too many agents for one workgroup's registers (or nothing to fuse): one launch per round, the
     // first from S_in to S_out, the rest in place on S_out (whole cycles / pairs read before they write)
@@ -419,6 +420,74 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   a.aux = g.v;
   a.ldaux = g.ldv;
   return run_chain(a, ceca::MODE_FROMV, d, state_vec, rd, port, st);
+}
+
+int32_t ceca_topology_round(int32_t kind, int32_t n, int32_t k, ceca_mix_t* out) {
+  if (!out) return fail(CECA_EINVAL, "null pointer");
+  if (n < 1 || k < 0) return fail(CECA_EINVAL, "need n >= 1 and k >= 0");
+  if (!ceca::fill_topology(kind, n, k, out)) return fail(CECA_EINVAL, "topology kind %d with n = %d: unknown kind, or more than %d peers", kind, n, CECA_MIX_MAX);
+  return CECA_OK;
+}
+
+int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, int64_t ld, const ceca_mix_t* specs,
+                        int32_t period, int32_t k0, int32_t rounds, void* hip_stream) {
+  if (!X_in || !X_out || !specs) return fail(CECA_EINVAL, "null pointer");
+  if (n < 1 || n > 4096) return fail(CECA_EINVAL, "n = %d: mixing rounds take 1 to 4096 agents", n);
+  if (d < 1 || ld < d) return fail(CECA_EINVAL, "need 1 <= d <= ld (d = %lld, ld = %lld)", (long long)d, (long long)ld);
+  if (period < 1 || period > ceca::kMixMaxPeriod) return fail(CECA_EINVAL, "period = %d outside [1, %d]", period, ceca::kMixMaxPeriod);
+  if (k0 < 0 || rounds < 1) return fail(CECA_EINVAL, "need k0 >= 0 and rounds >= 1");
+  const int64_t bytes = (int64_t)n * ld * (int64_t)sizeof(float);
+  if (overlaps(X_in, bytes, X_out, bytes) && (const void*)X_in != (const void*)X_out)
+    return fail(CECA_EINVAL, "X_out partially overlaps X_in");
+  ceca::MixArgs m{};
+  int32_t total = 0;
+  for (int32_t q = 0; q < period; ++q) {
+    const ceca_mix_t& sp = specs[q];
+    if (sp.m < 0 || sp.m > CECA_MIX_MAX) return fail(CECA_EINVAL, "round %d: m = %d outside [0, %d]", q, sp.m, CECA_MIX_MAX);
+    if (total + sp.m > ceca::kMixMaxPeers) return fail(CECA_EINVAL, "more than %d peers over the period", ceca::kMixMaxPeers);
+    m.start[q] = total;
+    m.w_self[q] = sp.w_self;
+    for (int32_t j = 0; j < sp.m; ++j) {
+      if (sp.shift[j] < 0 || sp.shift[j] >= n) return fail(CECA_EINVAL, "round %d: shift %d outside [0, n)", q, sp.shift[j]);
+      m.shift[total] = sp.shift[j];
+      m.w[total] = sp.w[j];
+      ++total;
+    }
+  }
+  m.start[period] = total;
+  m.xin = X_in;  m.xout = X_out;  m.ld = ld;
+  m.n = n;  m.rounds = rounds;  m.period = period;  m.k0 = k0 % period;
+  // Tile shape: a thread keeps up to `cap` rows; the fewest row lanes (a power of two) that cover n
+  // rows give the widest row segments, and the row count is then trimmed to what n needs.
+  int32_t cap = g_opt_rows.load();
+  if (cap < 4 || cap > 32) {
+    // measured on MI355X (n = 31, 130, 258, 1026): one or two peers per round want wide row segments,
+    // many peers per round (LDS-read bound) want more resident workgroups
+    int32_t most = 0;
+    for (int32_t q = 0; q < period; ++q) most = std::max(most, specs[q].m);
+    const bool heavy = most >= 4;
+    cap = n <= 32 ? 12 : (n <= 192 ? (heavy ? 8 : 16) : (n <= 512 ? 16 : (heavy ? 16 : 24)));
+  }
+  int32_t row_lanes = 1;
+  while (row_lanes * cap < n) row_lanes *= 2;
+  if (row_lanes > ceca::kBlock) { row_lanes = ceca::kBlock; }
+  const int32_t rpt = (n + row_lanes - 1) / row_lanes;
+  m.rows_per_thread = rpt;
+  m.row_lanes = row_lanes;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool can_vec = aligned16(X_in) && aligned16(X_out) && ld % 4 == 0;
+  const int64_t d4 = can_vec ? d / 4 : 0;
+  if (d4 > 0) {
+    m.col0 = 0;  m.ngroups = d4;
+    const hipError_t e = ceca::launch_mix_rounds(m, true, st);
+    if (e != hipSuccess) return hip_fail(e, "mixing kernel launch");
+  }
+  if (d - 4 * d4 > 0) {
+    m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+    const hipError_t e = ceca::launch_mix_rounds(m, false, st);
+    if (e != hipSuccess) return hip_fail(e, "mixing kernel launch (scalar columns)");
+  }
+  return CECA_OK;
 }
 
 int64_t consensus_error_workspace_bytes(int32_t n, int64_t d) {

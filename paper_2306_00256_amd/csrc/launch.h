@@ -59,8 +59,8 @@ struct MultiArgs {
   int64_t col0;
   int64_t ngroups;
   int32_t n, port, rounds;
-  int32_t rows_per_thread;  // 4, 8 or 16 rows of (x, y) in a thread's registers
-  int32_t row_lanes;   // power of two >= ceil(n / rows_per_thread): threads of a workgroup that share a column group
+  int32_t rows_per_thread;  // 1 to 16 rows of (x, y) in a thread's registers
+  int32_t row_lanes;   // power of two, row_lanes * rows_per_thread >= n: threads of a workgroup that share a column group
   MultiRound round[kMultiMaxRounds];
 };
 
@@ -101,11 +101,32 @@ struct ConsensusArgs {
   float* xbar;             // optional
 };
 
+constexpr int kMixMaxPeriod = 16;    // distinct rounds of a mixing sequence
+constexpr int kMixMaxPeers = 64;     // peers summed over those rounds
+
+// Shift-invariant mixing rounds on x alone: round t applies entries
+// [start[(k0 + t) % period], start[(k0 + t) % period + 1]) of (shift, w) and w_self of that round.
+struct MixArgs {
+  const float* xin;
+  float* xout;
+  int64_t ld;
+  int64_t col0;
+  int64_t ngroups;
+  int32_t n, rounds, period, k0;
+  int32_t rows_per_thread;  // rows of x in a thread's registers: 1 to 32
+  int32_t row_lanes;        // power of two, row_lanes * rows_per_thread >= n
+  int32_t start[kMixMaxPeriod + 1];
+  float w_self[kMixMaxPeriod];
+  int32_t shift[kMixMaxPeers];
+  float w[kMixMaxPeers];
+};
+
 // rows: state rows whose loads a thread keeps in flight together (1, 2, 4 or 8)
 hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
 // one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
+hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);

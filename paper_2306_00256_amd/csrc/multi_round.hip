@@ -43,22 +43,26 @@ __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) 
       if (i < M.n) zs[i * lanes + cg] = R.exch_y ? y[k] : x[k];
     }
     __syncthreads();
+    // no branch around the LDS reads: threads past the last agent shadow it (their rows are never
+    // published or stored), so a thread's RT reads issue back to back
+    V zp[RT];
 #pragma unroll
     for (int k = 0; k < RT; ++k) {
-      const int i = rg + k * M.row_lanes;
-      if (i < M.n) {
-        int p;
-        if (M.port == 2) {
-          p = i - R.shift; if (p < 0) p += M.n;
-        } else {
-          p = (i & 1) ? i - R.shift : i + R.shift;
-          if (p < 0) p += M.n;
-          if (p >= M.n) p -= M.n;
-        }
-        const V zp = zs[p * lanes + cg];
-        x[k] = combine(R.a, x[k], R.ap, zp);
-        y[k] = R.read_y ? combine(R.b, y[k], R.bp, zp) : R.bp * zp;
+      const int i = min(rg + k * M.row_lanes, M.n - 1);
+      int p;
+      if (M.port == 2) {
+        p = i - R.shift; if (p < 0) p += M.n;
+      } else {
+        p = (i & 1) ? i - R.shift : i + R.shift;
+        if (p < 0) p += M.n;
+        if (p >= M.n) p -= M.n;
       }
+      zp[k] = zs[p * lanes + cg];
+    }
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      x[k] = combine(R.a, x[k], R.ap, zp[k]);
+      y[k] = R.read_y ? combine(R.b, y[k], R.bp, zp[k]) : R.bp * zp[k];
     }
     __syncthreads();
   }
@@ -80,17 +84,21 @@ hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st) {
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
   dim3 grid((unsigned)blocks), block(kBlock);
-#define CECA_MULTI(RT)                                                         \
-  do {                                                                         \
-    if (vec4) multi_round_kernel<4, RT><<<grid, block, lds, st>>>(m);          \
-    else multi_round_kernel<1, RT><<<grid, block, lds, st>>>(m);               \
-  } while (0)
-  switch (m.rows_per_thread) {
-    case 4: CECA_MULTI(4); break;
-    case 8: CECA_MULTI(8); break;
-    default: CECA_MULTI(16); break;
-  }
-#undef CECA_MULTI
+  // 16-byte groups: exactly the rows n needs (1..16 per thread); the few scalar tail columns round up
+#define CECA_MULTI4(RT) case RT: multi_round_kernel<4, RT><<<grid, block, lds, st>>>(m); break
+#define CECA_MULTI1(RT) multi_round_kernel<1, RT><<<grid, block, lds, st>>>(m)
+  if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows) return hipErrorInvalidValue;
+  if (vec4) {
+    switch (m.rows_per_thread) {
+      CECA_MULTI4(1); CECA_MULTI4(2); CECA_MULTI4(3); CECA_MULTI4(4); CECA_MULTI4(5); CECA_MULTI4(6);
+      CECA_MULTI4(7); CECA_MULTI4(8); CECA_MULTI4(9); CECA_MULTI4(10); CECA_MULTI4(11); CECA_MULTI4(12);
+      CECA_MULTI4(13); CECA_MULTI4(14); CECA_MULTI4(15); CECA_MULTI4(16);
+    }
+  } else if (m.rows_per_thread <= 4) CECA_MULTI1(4);
+  else if (m.rows_per_thread <= 8) CECA_MULTI1(8);
+  else CECA_MULTI1(16);
+#undef CECA_MULTI4
+#undef CECA_MULTI1
   return hipGetLastError();
 }
 

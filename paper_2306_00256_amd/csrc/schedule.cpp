@@ -37,4 +37,35 @@ void fill_round(int32_t n, int32_t r, int32_t port, ceca_round_t* out) {
   out->b_peer = (float)((double)(out->b_den - out->b_num) / (double)out->b_den);
 }
 
+bool fill_topology(int32_t kind, int32_t n, int32_t k, ceca_mix_t* out) {
+  *out = ceca_mix_t{};
+  if (n < 1 || k < 0) return false;
+  const int32_t tau = tau_of(n);
+  double w = 0.0;
+  switch (kind) {
+    case CECA_TOPO_RING:
+      if (n == 2) { out->m = 1; out->shift[0] = 1; w = 0.5; }
+      else if (n > 2) { out->m = 2; out->shift[0] = 1; out->shift[1] = n - 1; w = 1.0 / 3.0; }
+      break;
+    case CECA_TOPO_STATIC_EXP:
+      if (tau > CECA_MIX_MAX) return false;
+      out->m = tau;
+      w = 1.0 / (double)(tau + 1);
+      for (int32_t j = 0; j < tau; ++j) out->shift[j] = (int32_t)(1u << j);
+      break;
+    case CECA_TOPO_ONE_PEER_EXP:
+      if (tau > 0) { out->m = 1; out->shift[0] = (int32_t)(1u << (k % tau)); w = 0.5; }
+      break;
+    default:
+      return false;
+  }
+  double rest = 1.0;
+  for (int32_t j = 0; j < out->m; ++j) {
+    out->w[j] = (float)w;
+    rest -= (double)out->w[j];
+  }
+  out->w_self = (float)rest;
+  return true;
+}
+
 }  // namespace ceca

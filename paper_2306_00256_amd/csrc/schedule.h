@@ -28,4 +28,8 @@ inline int32_t peer_of(const ceca_round_t& rd, int32_t i) {
   return (int32_t)j;
 }
 
+// Round k of a comparison topology (ring, static / one-peer exponential gossip).  Expects n >= 1,
+// k >= 0 and a known kind; returns false otherwise.
+bool fill_topology(int32_t kind, int32_t n, int32_t k, ceca_mix_t* out);
+
 }  // namespace ceca

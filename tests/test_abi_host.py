@@ -37,6 +37,7 @@ def test_struct_sizes_match_header(api):
     from paper_2306_00256_amd import binding
     assert ctypes.sizeof(binding.Round) == 12 * 4 + 4 * 4
     assert ctypes.sizeof(binding.Loss) == 32 + 5 * 8
+    assert ctypes.sizeof(binding.Mix) == 8 + 2 * 4 * binding.MIX_MAX
 
 
 @pytest.mark.parametrize("port", [1, 2])
