@@ -142,3 +142,25 @@ def test_consensus_comparison(env, n):
         want = OCONS.consensus_error(OT.run(x0, ora, tau))
         assert got[2] > 1e-3 * got[3], kind                    # far from consensus
         assert abs(got[1] - want["residue"]) <= 1e-4 * want["residue"], kind
+
+
+@pytest.mark.parametrize("n,d", [(130, 1 << 20), (1026, 1 << 17)])
+@pytest.mark.parametrize("kind", KINDS)
+def test_bench_sizes_on_sampled_columns(env, kind, n, d):
+    """The sizes and the call bench.py times (tau rounds fused, 256-byte row pitch, device-drawn data):
+    2048 sampled columns (head, tail and random ones) against the oracle, and the column means, which
+    every doubly stochastic round preserves, over the whole width."""
+    torch, P = env
+    dev, ora = _specs(P, kind, n)
+    tau = OS.num_rounds(n)
+    X = torch.empty((n, d), dtype=torch.float32, device="cuda")
+    WL.device_normal((n, d), seed=n, out=X)
+    Y = torch.empty_like(X)
+    cols = WL.sample_columns(d, 2048, seed=n, tail=8)
+    tc = torch.from_numpy(cols).cuda()
+    x0 = X[:, tc].cpu().numpy().astype(np.float64)
+    mean0 = X.double().mean(0)
+    P.ceca_mix_rounds(X, Y, n, d, dev, tau)
+    want = OT.run(x0, ora, tau)
+    assert max(rel_err(Y[:, tc].cpu().numpy(), want)) <= 1e-4
+    assert (Y.double().mean(0) - mean0).abs().max().item() <= 2e-6
