@@ -134,6 +134,18 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
                        int32_t r, int32_t port, void* workspace, int64_t workspace_bytes,
                        void* hip_stream);
 
+/* `steps` consecutive DSGD-CECA iterations with the quadratic-centre loss in one pass over the state.
+ * Iteration t (t = 0 .. steps-1) uses round (r0 + t) mod tau and the noise counter loss->k + t, at the
+ * one step size lr; the result has the same bits as `steps` calls of dsgd_ceca_step.  Only
+ * CECA_LOSS_QUAD_CENTER is taken (CECA_EINVAL otherwise): its gradient is elementwise, so columns stay
+ * independent across whole iterations and a workgroup can carry a column tile of x, y and c through all
+ * of them in registers -- 20 bytes per agent-parameter for the whole call instead of per iteration.
+ * S_out may be S_in or disjoint from it.  Up to 4096 agents and 64 iterations run as one kernel; larger
+ * cases fall back to one dsgd_ceca_step per iteration (in place on S_out after the first). */
+int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
+                        const ceca_loss_t* loss, float lr, int32_t r0, int32_t steps, int32_t port,
+                        void* hip_stream);
+
 /* Bytes of device workspace consensus_error needs; < 0 on error. */
 int64_t consensus_error_workspace_bytes(int32_t n, int64_t d);
 

@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     consensus_error,
     consensus_error_workspace_bytes,
     dsgd_ceca_step,
+    dsgd_ceca_steps,
     dsgd_ceca_workspace_bytes,
     lib,
     library_path,

@@ -422,6 +422,71 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   return run_chain(a, ceca::MODE_FROMV, d, state_vec, rd, port, st);
 }
 
+int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, const ceca_loss_t* loss,
+                        float lr, int32_t r0, int32_t steps, int32_t port, void* hip_stream) {
+  ceca_round_t rd;
+  int32_t rc = check_state_call(S_in, S_out, n, d, ld, r0, port, &rd);
+  if (rc != CECA_OK) return rc;
+  rc = check_loss(loss, d, false, nullptr);
+  if (rc != CECA_OK) return rc;
+  if (loss->kind != CECA_LOSS_QUAD_CENTER)
+    return fail(CECA_EINVAL, "fused iterations need an elementwise loss (CECA_LOSS_QUAD_CENTER)");
+  if (steps < 1) return fail(CECA_EINVAL, "steps = %d: need at least one", steps);
+  const int64_t sbytes = 2 * (int64_t)n * ld * 4, cbytes = (int64_t)n * loss->ldc * 4;
+  if (overlaps(loss->c, cbytes, S_out, sbytes)) return fail(CECA_EINVAL, "centres overlap S_out");
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int32_t tau = ceca::tau_of(n);
+  // The tile holds x, y and c, and with noise the kernel is bound by the generator's arithmetic: few rows
+  // per thread (small register footprint, many resident wavefronts) measured best on MI355X; many
+  // agents need more rows per thread to keep a row of the tile at least 32-64 bytes wide.
+  int32_t cap = g_opt_rows.load();
+  if (cap < 1 || cap > ceca::kMultiRows) cap = n <= 128 ? 4 : (n <= 512 ? 8 : (steps <= 16 ? 16 : 8));
+  int32_t row_lanes = 1;
+  while (row_lanes * cap < n) row_lanes *= 2;
+  if (row_lanes > ceca::kBlock) { row_lanes = ceca::kBlock; }
+  const int32_t rpt = (n + row_lanes - 1) / row_lanes;
+  if (n == 1 || steps > ceca::kMultiMaxRounds || rpt > ceca::kMultiRows) {
+    ceca_loss_t one = *loss;
+    for (int32_t t = 0; t < steps; ++t) {
+      one.k = loss->k + (uint32_t)t;
+      const int32_t r1 = dsgd_ceca_step(t == 0 ? S_in : S_out, S_out, n, d, ld, &one, nullptr, lr,
+                                        n == 1 ? 0 : (r0 + t) % tau, port, nullptr, 0, st);
+      if (r1 != CECA_OK) return r1;
+    }
+    return CECA_OK;
+  }
+  ceca::StepsArgs a{};
+  ceca::MultiArgs& m = a.m;
+  m.xin = S_in;
+  m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
+  m.ld = ld;
+  m.n = n;  m.port = port;  m.rounds = steps;
+  m.row_lanes = row_lanes;
+  m.rows_per_thread = rpt;
+  for (int32_t t = 0; t < steps; ++t) {
+    ceca::fill_round(n, (r0 + t) % tau, port, &rd);
+    ceca::MultiRound& R = m.round[t];
+    R.shift = rd.shift;  R.exch_y = rd.exchange_y;  R.read_y = rd.b_num != 0;
+    R.a = rd.a;  R.ap = rd.a_peer;  R.b = rd.b;  R.bp = rd.b_peer;
+  }
+  a.yin = S_in + (int64_t)n * ld;
+  a.c = loss->c;  a.ldc = loss->ldc;
+  a.lr = lr;  a.noise_std = loss->noise_std;  a.seed = loss->seed;  a.k0 = loss->k;
+  const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->c) && loss->ldc % 4 == 0;
+  const int64_t d4 = can_vec ? d / 4 : 0;
+  if (d4 > 0) {
+    m.col0 = 0;  m.ngroups = d4;
+    const hipError_t e = ceca::launch_multi_step(a, true, st);
+    if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch");
+  }
+  if (d - 4 * d4 > 0) {
+    m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+    const hipError_t e = ceca::launch_multi_step(a, false, st);
+    if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch (scalar columns)");
+  }
+  return CECA_OK;
+}
+
 int32_t ceca_topology_round(int32_t kind, int32_t n, int32_t k, ceca_mix_t* out) {
   if (!out) return fail(CECA_EINVAL, "null pointer");
   if (n < 1 || k < 0) return fail(CECA_EINVAL, "need n >= 1 and k >= 0");

@@ -101,6 +101,17 @@ struct ConsensusArgs {
   float* xbar;             // optional
 };
 
+// Fused iterations with the quadratic-centre loss: the rounds of MultiArgs plus what the gradient needs.
+// Iteration t uses round m.round[t] and the noise counter k0 + t.
+struct StepsArgs {
+  MultiArgs m;
+  const float* yin;     // row 0 of y in S_in
+  const float* c;       // centres
+  int64_t ldc;
+  float lr, noise_std;
+  uint32_t seed, k0;
+};
+
 constexpr int kMixMaxPeriod = 16;    // distinct rounds of a mixing sequence
 constexpr int kMixMaxPeers = 64;     // peers summed over those rounds
 
@@ -127,6 +138,7 @@ hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipSt
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
+hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);

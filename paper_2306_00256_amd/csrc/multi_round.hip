@@ -77,6 +77,118 @@ __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) 
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Several DSGD-CECA iterations with the quadratic-centre loss in one pass.  That loss is elementwise
+// (e_i = z_i - c_i + noise), so columns stay independent through whole iterations, not just through
+// the communication round: the workgroup keeps a column tile of every agent's x, y and c in registers,
+// takes the local step in place, exchanges the messages through LDS and combines (Algorithm 1,
+// Eqs. (8), (9)), `rounds` times.  20 bytes per agent-parameter for any number of iterations.  The
+// arithmetic per iteration is that of the single-step kernel, operation for operation.
+// ---------------------------------------------------------------------------------------------
+template <int VEC, int RT>
+__global__ __launch_bounds__(kBlock) void multi_step_kernel(const StepsArgs S) {
+#pragma clang fp contract(off)
+  using V = typename VecOf<VEC>::T;
+  const MultiArgs& M = S.m;
+  extern __shared__ float lds_z[];                 // [n][lanes] groups of VEC floats
+  const int lanes = kBlock / M.row_lanes;
+  const int cg = threadIdx.x % lanes;
+  const int rg = threadIdx.x / lanes;
+  const int64_t g = (int64_t)blockIdx.x * lanes + cg;
+  const bool on = g < M.ngroups;
+  const int64_t col = M.col0 + (on ? g : 0) * VEC; // lanes past the last column shadow column group 0
+
+  V x[RT], y[RT], c[RT];
+  const bool first_reads_y = M.round[0].read_y != 0;
+#pragma unroll
+  for (int k = 0; k < RT; ++k) {
+    const int i = min(rg + k * M.row_lanes, M.n - 1);   // rows past the last agent shadow it
+    x[k] = ld_stream<V>(M.xin + (int64_t)i * M.ld + col);
+    c[k] = ld_stream<V>(S.c + (int64_t)i * S.ldc + col);
+  }
+  if (first_reads_y) {                             // a first round with b = 0 never uses y(0)
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      const int i = min(rg + k * M.row_lanes, M.n - 1);
+      y[k] = ld_stream<V>(S.yin + (int64_t)i * M.ld + col);
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < RT; ++k) y[k] = V(0.0f);
+  }
+  V* zs = reinterpret_cast<V*>(lds_z);
+  for (int t = 0; t < M.rounds; ++t) {
+    const MultiRound R = M.round[t];
+    V ge[RT];
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      const int i = min(rg + k * M.row_lanes, M.n - 1);
+      const V z = R.exch_y ? y[k] : x[k];
+      V e = z - c[k];
+      if (S.noise_std != 0.0f) e += S.noise_std * noise_group<V>(col, noise_keys(S.seed, S.k0 + (uint32_t)t, (uint32_t)i));
+      ge[k] = S.lr * e;
+      if (rg + k * M.row_lanes < M.n) zs[i * lanes + cg] = z - ge[k];      // the message v_i
+    }
+    __syncthreads();
+    V zp[RT];
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      const int i = min(rg + k * M.row_lanes, M.n - 1);
+      int p;
+      if (M.port == 2) {
+        p = i - R.shift; if (p < 0) p += M.n;
+      } else {
+        p = (i & 1) ? i - R.shift : i + R.shift;
+        if (p < 0) p += M.n;
+        if (p >= M.n) p -= M.n;
+      }
+      zp[k] = zs[p * lanes + cg];
+    }
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      const V xs = x[k] - ge[k];
+      const V ys = y[k] - ge[k];
+      x[k] = combine(R.a, xs, R.ap, zp[k]);
+      y[k] = R.read_y ? combine(R.b, ys, R.bp, zp[k]) : R.bp * zp[k];
+    }
+    __syncthreads();
+  }
+  if (!on) return;
+#pragma unroll
+  for (int k = 0; k < RT; ++k) {
+    const int i = rg + k * M.row_lanes;
+    if (i < M.n) {
+      st_stream<V>(M.xout + (int64_t)i * M.ld + col, x[k]);
+      st_stream<V>(M.yout + (int64_t)i * M.ld + col, y[k]);
+    }
+  }
+}
+
+hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st) {
+  const MultiArgs& m = s.m;
+  if (m.ngroups <= 0) return hipSuccess;
+  const int lanes = kBlock / m.row_lanes;
+  const int64_t blocks = (m.ngroups + lanes - 1) / lanes;
+  if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
+  const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
+  dim3 grid((unsigned)blocks), block(kBlock);
+#define CECA_STEPS4(RT) case RT: multi_step_kernel<4, RT><<<grid, block, lds, st>>>(s); break
+#define CECA_STEPS1(RT) multi_step_kernel<1, RT><<<grid, block, lds, st>>>(s)
+  if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows) return hipErrorInvalidValue;
+  if (vec4) {
+    switch (m.rows_per_thread) {
+      CECA_STEPS4(1); CECA_STEPS4(2); CECA_STEPS4(3); CECA_STEPS4(4); CECA_STEPS4(5); CECA_STEPS4(6);
+      CECA_STEPS4(7); CECA_STEPS4(8); CECA_STEPS4(9); CECA_STEPS4(10); CECA_STEPS4(11); CECA_STEPS4(12);
+      CECA_STEPS4(13); CECA_STEPS4(14); CECA_STEPS4(15); CECA_STEPS4(16);
+    }
+  } else if (m.rows_per_thread <= 4) CECA_STEPS1(4);
+  else if (m.rows_per_thread <= 8) CECA_STEPS1(8);
+  else CECA_STEPS1(16);
+#undef CECA_STEPS4
+#undef CECA_STEPS1
+  return hipGetLastError();
+}
+
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st) {
   if (m.ngroups <= 0) return hipSuccess;
   const int lanes = kBlock / m.row_lanes;
