@@ -84,6 +84,13 @@ def test_host_side_errors(api):
     assert L.ceca_gossip_round(p, p, 4, 8, 4, 0, 1, None) == Bn.CECA_EINVAL          # ld < d
     assert L.ceca_gossip_round(p, p, 4, 8, 8, 2, 1, None) == Bn.CECA_EINVAL          # r >= tau
     assert b"outside" in L.ceca_last_error()
+    q = Bn.Loss(); q.kind = Bn.LOSS_QUAD_CENTER; q.c = p; q.ldc = 8
+    assert L.dsgd_ceca_steps(p, p, 4, 8, 8, ctypes.byref(q), 0.1, 0, 0, 1, None) == Bn.CECA_EINVAL     # no iterations
+    assert L.dsgd_ceca_steps(p, p, 4, 8, 8, ctypes.byref(q), 0.1, 2, 3, 1, None) == Bn.CECA_EINVAL     # r0 >= tau
+    assert L.dsgd_ceca_steps(p, p, 3, 8, 8, ctypes.byref(q), 0.1, 0, 3, 1, None) == Bn.CECA_EODD1P
+    assert L.dsgd_ceca_steps(p, p, 4, 8, 8, None, 0.1, 0, 3, 1, None) == Bn.CECA_EINVAL
+    q.ldc = 4
+    assert L.dsgd_ceca_steps(p, p, 4, 8, 8, ctypes.byref(q), 0.1, 0, 3, 1, None) == Bn.CECA_EINVAL     # ldc < d
     assert api.consensus_error_workspace_bytes(31, 25_557_032) > 0
     assert L.ceca_state_consensus(None, 4, 8, 8, p, p, 1 << 20, None) == Bn.CECA_EINVAL
     assert L.ceca_state_consensus(p, 4, 8, 4, p, p, 1 << 20, None) == Bn.CECA_EINVAL   # ld < d
