@@ -1,0 +1,77 @@
+"""GPU parity at the size limits of the fused kernels: the largest agent counts one workgroup's
+registers take (4096) and the first ones beyond, where the calls fall back to one launch per round."""
+import numpy as np
+import pytest
+
+import workloads as WL
+from oracle import ceca as OC
+from oracle import losses as OL
+from oracle import schedule as OS
+from oracle import topologies as OT
+from gpu_util import make_state, rel_err, split_state
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    import paper_2306_00256_amd as P
+    assert torch.cuda.is_available()
+    P.lib()
+    return torch, P
+
+
+@pytest.mark.parametrize("n,port", [(4095, 2), (4096, 1), (4096, 2), (4097, 2), (4098, 1), (5000, 2)])
+def test_fused_rounds_around_the_agent_limit(env, n, port):
+    torch, P = env
+    d = 37
+    tau = OS.num_rounds(n)
+    x0 = WL.initial_state(n, d, seed=n)
+    S = make_state(torch, x0, y0=np.full_like(x0, np.nan))
+    T = make_state(torch, np.zeros_like(x0))
+    P.ceca_gossip_rounds(S, T, n, d, tau + 1, port)
+    gx, gy = split_state(T, n, d)
+    x, y = OC.run(x0, port, 0.0, None, tau + 1, store32=True)
+    assert max(rel_err(gx, x)) <= 1e-5 and max(rel_err(gy, y)) <= 1e-5
+    mean = x0.astype(np.float64).mean(axis=0)
+    assert np.abs(gx - mean).max() <= 1e-6 and np.abs(gy - mean).max() <= 1e-6     # Lemma 4.2: both at the mean
+    # same bits as single rounds
+    A = make_state(torch, x0)
+    B = make_state(torch, np.zeros_like(x0))
+    for r in range(tau + 1):
+        P.ceca_gossip_round(A, B, n, d, r % tau, port)
+        A, B = B, A
+    ax, ay = split_state(A, n, d)
+    assert np.array_equal(ax, gx) and np.array_equal(ay, gy)
+
+
+@pytest.mark.parametrize("n,port", [(4096, 1), (4097, 2)])
+def test_fused_iterations_around_the_agent_limit(env, n, port):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    d, seed, lr, std, steps = 21, 9, 0.1, 0.01, 5
+    c = WL.quad_centers(n, d, seed)
+    cdev = torch.from_numpy(c).cuda()
+    x0 = WL.initial_state(n, d, seed)
+    A = make_state(torch, x0)
+    B = make_state(torch, np.zeros_like(x0))
+    P.dsgd_ceca_steps(A, B, n, d, Bn.make_quad_center_loss(cdev, std, seed, 2), lr, 2, steps, port)
+    gx, gy = split_state(B, n, d)
+    x, y = OC.run(x0, port, lr, OL.make_quad_center_grad(c, std, seed), steps, store32=True, k0=2)
+    assert max(rel_err(gx, x)) <= 1e-4 and max(rel_err(gy, y)) <= 1e-4
+
+
+def test_mixing_rounds_at_the_agent_limit(env):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d = 4096, 29
+    x0 = WL.initial_state(n, d, seed=4)
+    X = torch.from_numpy(x0).cuda()
+    for kind, want in [(Bn.TOPO_STATIC_EXP, [OT.static_exponential(n)]), (Bn.TOPO_RING, [OT.ring(n)])]:
+        Y = torch.empty_like(X)
+        P.ceca_mix_rounds(X, Y, n, d, [P.ceca_topology_round(kind, n)], 3)
+        assert max(rel_err(Y.cpu().numpy(), OT.run(x0, want, 3))) <= 1e-5
+    with pytest.raises(P.CecaError) as e:
+        P.ceca_mix_rounds(X, X, 4097, d, [P.ceca_topology_round(Bn.TOPO_RING, 4097)], 1)
+    assert e.value.code == Bn.CECA_EINVAL
