@@ -40,31 +40,36 @@ __device__ __forceinline__ double wave_max(double v) {
   for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
   return v;
 }
-// Sums N per-lane values across the 64 lanes of a wavefront at once.  Each butterfly step halves the
-// number of values a lane carries (partners swap the halves they do not keep), so N values cost
-// N - 1 + (6 - log2 N) lane exchanges instead of 6 N.  On return lane l < N holds the complete sum
-// of value number `which`.
-template <int N>
-__device__ __forceinline__ float wave_sum_many(float (&m)[N], int lane, int& which) {
-  static_assert(N >= 1 && N <= 64 && (N & (N - 1)) == 0, "N must be a power of two");
-  which = 0;
-  int bit = 0;
-#pragma unroll
-  for (int len = N; len > 1; len >>= 1, ++bit) {
-    const bool up = (lane >> bit) & 1;
-    const int half = len / 2;
-#pragma unroll
-    for (int k = 0; k < half; ++k) {
-      const float send = up ? m[k] : m[k + half];
-      const float keep = up ? m[k + half] : m[k];
-      m[k] = keep + __shfl_xor(send, 1 << bit, 64);
-    }
-    which += up ? half : 0;
-  }
-  float v = m[0];
-#pragma unroll
-  for (int b = bit; b < 6; ++b) v += __shfl_xor(v, 1 << b, 64);
+// Sum over the 64 lanes of a wavefront with data-parallel-primitive adds (no LDS traffic): pairs and
+// quads by quad permutes, rows of 16 by the two row mirrors, then the last lane of row 0 into row 1
+// and of row 2 into row 3, then lane 31 into rows 2 and 3.  Lane 63 ends up with the complete sum.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false);
+  return v + __builtin_bit_cast(float, moved);     // rows outside ROW_MASK receive +0
+}
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+  v = dpp_add<0xB1, 0xf>(v);    // quad_perm [1, 0, 3, 2]
+  v = dpp_add<0x4E, 0xf>(v);    // quad_perm [2, 3, 0, 1]
+  v = dpp_add<0x141, 0xf>(v);   // row_half_mirror
+  v = dpp_add<0x140, 0xf>(v);   // row_mirror
+  v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
   return v;
+}
+// Sums N per-lane values across the wavefront.  On return lane l < N holds the complete sum of value
+// number `which` = l.  Every index is a compile-time constant, so the values stay in registers.
+template <int N>
+__device__ __forceinline__ float wave_sum_many(const float (&m)[N], int lane, int& which) {
+  static_assert(N >= 1 && N <= 64, "one lane per value");
+  float mine = 0.0f;
+#pragma unroll
+  for (int k = 0; k < N; ++k) {
+    const float total = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_to_lane63(m[k])), 63));
+    mine = (lane == k) ? total : mine;
+  }
+  which = lane;
+  return mine;
 }
 
 __device__ __forceinline__ float dot_v(vf4 a, vf4 b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }

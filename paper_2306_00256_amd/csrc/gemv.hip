@@ -10,8 +10,8 @@ namespace ceca {
 // Minibatch row numbers are the same for every lane: keep them in scalar registers so that row
 // addresses are scalar and all row loads can be issued back to back.
 __device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
-// A sampled row number, forced into [0, N): a bad index must not become a wild read.
-__device__ __forceinline__ int32_t sample_row(int32_t v, int32_t N) { return min(max(uniform_i32(v), 0), N - 1); }
+// Sampled row numbers are forced into [0, N) wherever they are used: a bad index must not become a
+// wild read.
 
 // partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col].
 // A workgroup takes one column chunk of kRowGroup sampled rows of one agent (grid: chunks x agents x row groups),
@@ -33,10 +33,13 @@ __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
   const V z = on ? zv : V(0.0f);
   const int32_t* idx = G.batch_idx + (int64_t)agent * G.B;
   const float* Abase = G.A + (int64_t)agent * G.N * G.lda + col;
+  // one vector load for the group's sample numbers (lane jj holds sample j0 + jj; samples past B repeat
+  // the last), made scalar lane by lane: scalar loads would each wait for the one before
+  const int32_t myidx = idx[min(j0 + min(lane, kRowGroup - 1), G.B - 1)];
   V a[kRowGroup];
 #pragma unroll
   for (int jj = 0; jj < kRowGroup; ++jj) {
-    const int32_t rj = sample_row(idx[min(j0 + jj, G.B - 1)], G.N);   // rows past B repeat the last one
+    const int32_t rj = min(max(__builtin_amdgcn_readlane(myidx, jj), 0), G.N - 1);
     a[jj] = ld_stream<V>(Abase + (int64_t)rj * G.lda);
   }
   float acc[kRowGroup];
@@ -119,9 +122,14 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
   }
   const int32_t* idx = P.batch_idx + (int64_t)agent * P.B;
   const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
+  // one vector load brings the whole batch into a wavefront (lane j holds sample j; samples past B repeat
+  // the last), then the row numbers become scalars lane by lane: B scalar loads would each wait for
+  // the one before, because scalar loads return out of order
+  static_assert(BMAX <= 64, "one lane per sampled row");
+  const int32_t myidx = idx[min(lane, P.B - 1)];
   int32_t rowid[BMAX];
 #pragma unroll
-  for (int j = 0; j < BMAX; ++j) rowid[j] = sample_row(idx[min(j, P.B - 1)], P.N);   // rows past B repeat the last
+  for (int j = 0; j < BMAX; ++j) rowid[j] = min(max(__builtin_amdgcn_readlane(myidx, j), 0), P.N - 1);
   vf4 a[BMAX][G];
 #pragma unroll
   for (int j = 0; j < BMAX; ++j) {
@@ -129,6 +137,13 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 #pragma unroll
     for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
   }
+  // the target of "my" sampled row (threads 0 .. BMAX-1 turn margins into coefficients later) is
+  // requested here, behind the rows, not between the two barriers where every wavefront would wait
+  // for it; the row number comes from the scalar row ids, so nothing has to arrive first
+  int32_t rmine = rowid[0];
+#pragma unroll
+  for (int j = 1; j < BMAX; ++j) rmine = ((int)threadIdx.x == j) ? rowid[j] : rmine;
+  const float tmine = P.t[(int64_t)agent * P.N + rmine];
   float m[BMAX];
 #pragma unroll
   for (int j = 0; j < BMAX; ++j) {
@@ -145,8 +160,7 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
     float m = 0.0f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) m += red[w][j];
-    const float t = P.t[(int64_t)agent * P.N + min(max(idx[min(j, P.B - 1)], 0), P.N - 1)];
-    coef[j] = (j < P.B) ? loss_coef(P.kind, m, t, P.scale) : 0.0f;
+    coef[j] = (j < P.B) ? loss_coef(P.kind, m, tmine, P.scale) : 0.0f;
   }
   __syncthreads();
 #pragma unroll
