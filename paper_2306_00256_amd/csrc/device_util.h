@@ -40,36 +40,51 @@ __device__ __forceinline__ double wave_max(double v) {
   for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
   return v;
 }
-// Sum over the 64 lanes of a wavefront with data-parallel-primitive adds (no LDS traffic): pairs and
-// quads by quad permutes, rows of 16 by the two row mirrors, then the last lane of row 0 into row 1
-// and of row 2 into row 3, then lane 31 into rows 2 and 3.  Lane 63 ends up with the complete sum.
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_add(float v) {
-  const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false);
-  return v + __builtin_bit_cast(float, moved);     // rows outside ROW_MASK receive +0
+// v + (v of lane ^ XOR).  Distances 1 and 2 are quad permutes on the data-parallel-primitive path (no
+// LDS traffic); 4, 8 and 16 are swizzles inside each half of the wavefront; 32 is a lane exchange.
+template <int XOR>
+__device__ __forceinline__ float xor_add(float v) {
+  const int bits = __builtin_bit_cast(int, v);
+  int moved;
+  if constexpr (XOR == 1) moved = __builtin_amdgcn_update_dpp(0, bits, 0xB1, 0xf, 0xf, false);        // quad_perm [1, 0, 3, 2]
+  else if constexpr (XOR == 2) moved = __builtin_amdgcn_update_dpp(0, bits, 0x4E, 0xf, 0xf, false);   // quad_perm [2, 3, 0, 1]
+  else if constexpr (XOR == 32) moved = __shfl_xor(bits, 32, 64);
+  else moved = __builtin_amdgcn_ds_swizzle(bits, (XOR << 10) | 0x1f);                                  // xor mask, all lanes kept
+  return v + __builtin_bit_cast(float, moved);
 }
-__device__ __forceinline__ float wave_sum_to_lane63(float v) {
-  v = dpp_add<0xB1, 0xf>(v);    // quad_perm [1, 0, 3, 2]
-  v = dpp_add<0x4E, 0xf>(v);    // quad_perm [2, 3, 0, 1]
-  v = dpp_add<0x141, 0xf>(v);   // row_half_mirror
-  v = dpp_add<0x140, 0xf>(v);   // row_mirror
-  v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
-  v = dpp_add<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
-  return v;
-}
-// Sums N per-lane values across the wavefront.  On return lane l < N holds the complete sum of value
-// number `which` = l.  Every index is a compile-time constant, so the values stay in registers.
-template <int N>
-__device__ __forceinline__ float wave_sum_many(const float (&m)[N], int lane, int& which) {
-  static_assert(N >= 1 && N <= 64, "one lane per value");
-  float mine = 0.0f;
+// One level of the halving butterfly below: every lane adds its partner's copy of each of the 2H values
+// it still carries, then keeps the H values that belong to its side (`up`); with one value left (H = 0)
+// both partners keep the pair sum.
+template <int XOR, int H>
+__device__ __forceinline__ void halve(float (&m)[16], bool up) {
+  if constexpr (H >= 1) {
+    float s[2 * H];
 #pragma unroll
-  for (int k = 0; k < N; ++k) {
-    const float total = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_to_lane63(m[k])), 63));
-    mine = (lane == k) ? total : mine;
+    for (int k = 0; k < 2 * H; ++k) s[k] = xor_add<XOR>(m[k]);
+#pragma unroll
+    for (int k = 0; k < H; ++k) m[k] = up ? s[k + H] : s[k];
+  } else {
+    m[0] = xor_add<XOR>(m[0]);
   }
-  which = lane;
-  return mine;
+}
+// Sums N <= 16 per-lane values (N a power of two) across the 64 lanes of a wavefront.  The level with
+// partner distance 2^t halves the number of values a lane carries while there is more than one (the
+// partner sits on the other side of lane bit t and carries the same values), so N values cost about
+// 2N adds instead of 6N.  On return lane l < N holds the complete sum of value number `which`.
+// All array indices are compile-time constants: the values stay in registers.
+template <int N>
+__device__ __forceinline__ float wave_sum_many(const float (&in)[N], int lane, int& which) {
+  static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16, "N must be a power of two up to 16");
+  float m[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) m[k] = in[k < N ? k : 0];
+  const bool u0 = lane & 1, u1 = lane & 2, u2 = lane & 4, u3 = lane & 8;
+  halve<1, N / 2>(m, u0);
+  halve<2, N / 4>(m, u1);
+  halve<4, N / 8>(m, u2);
+  halve<8, N / 16>(m, u3);
+  which = (N >= 2 && u0 ? N / 2 : 0) + (N >= 4 && u1 ? N / 4 : 0) + (N >= 8 && u2 ? N / 8 : 0) + (N >= 16 && u3 ? 1 : 0);
+  return xor_add<32>(xor_add<16>(m[0]));
 }
 
 __device__ __forceinline__ float dot_v(vf4 a, vf4 b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }

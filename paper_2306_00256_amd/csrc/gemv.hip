@@ -105,7 +105,6 @@ template <int THREADS, int BMAX, int G>
 __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P) {
   constexpr int WAVES = THREADS / 64;
   __shared__ float red[WAVES][BMAX];
-  __shared__ float coef[BMAX];
   const int agent = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // lanes past the last column read column 0 instead and carry z = 0: no branch surrounds a load
@@ -137,13 +136,16 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 #pragma unroll
     for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
   }
-  // the target of "my" sampled row (threads 0 .. BMAX-1 turn margins into coefficients later) is
-  // requested here, behind the rows, not between the two barriers where every wavefront would wait
-  // for it; the row number comes from the scalar row ids, so nothing has to arrive first
+  // the target of "my" sampled row (lanes 0 .. BMAX-1 of every wavefront turn margins into coefficients
+  // later) is requested here, behind the rows, so that nothing waits for it after the barrier; the row
+  // number comes from the scalar row ids, so nothing has to arrive first
   int32_t rmine = rowid[0];
 #pragma unroll
-  for (int j = 1; j < BMAX; ++j) rmine = ((int)threadIdx.x == j) ? rowid[j] : rmine;
+  for (int j = 1; j < BMAX; ++j) rmine = (lane == j) ? rowid[j] : rmine;
   const float tmine = P.t[(int64_t)agent * P.N + rmine];
+  // every load above is issued before any arithmetic below: the scheduler must not trade loads in
+  // flight for registers here (it split the rows into two dependent batches when left alone)
+  __builtin_amdgcn_sched_barrier(0);
   float m[BMAX];
 #pragma unroll
   for (int j = 0; j < BMAX; ++j) {
@@ -151,18 +153,30 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 #pragma unroll
     for (int u = 0; u < G; ++u) m[j] += dot_v(a[j][u], z[u]);
   }
-  int jrow;
-  const float msum = wave_sum_many<BMAX>(m, lane, jrow);
-  if (lane < BMAX) red[wave][jrow] = msum;
-  __syncthreads();
-  if ((int)threadIdx.x < BMAX) {
-    const int j = threadIdx.x;
-    float m = 0.0f;
+  constexpr int CH = BMAX < 16 ? BMAX : 16;        // margins are summed across the wavefront 16 at a time
 #pragma unroll
-    for (int w = 0; w < WAVES; ++w) m += red[w][j];
-    coef[j] = (j < P.B) ? loss_coef(P.kind, m, tmine, P.scale) : 0.0f;
+  for (int c0 = 0; c0 < BMAX; c0 += CH) {
+    float part[CH];
+#pragma unroll
+    for (int k = 0; k < CH; ++k) part[k] = m[c0 + k];
+    int jrow;
+    const float msum = wave_sum_many<CH>(part, lane, jrow);
+    if (lane < CH) red[wave][c0 + jrow] = msum;
   }
   __syncthreads();
+  // every wavefront turns the margins into coefficients for itself (lane j: sample j, same summation
+  // order everywhere), so no second barrier and no LDS round trip for the coefficients
+  float cmine = 0.0f;
+  {
+    const int j = min(lane, BMAX - 1);
+    float mj = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) mj += red[w][j];
+    cmine = (lane < P.B) ? loss_coef(P.kind, mj, tmine, P.scale) : 0.0f;
+  }
+  float coef[BMAX];                                 // wavefront-uniform: scalar registers
+#pragma unroll
+  for (int j = 0; j < BMAX; ++j) coef[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cmine), j));
 #pragma unroll
   for (int u = 0; u < G; ++u) {
     vf4 e = vf4(0.0f);
