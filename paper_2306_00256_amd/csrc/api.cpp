@@ -64,7 +64,7 @@ int32_t check_state_call(const float* S_in, float* S_out, int32_t n, int64_t d, 
 }
 
 // Chain shape for the round: which cycles the walk has and how they are cut into stretches.
-void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place, bool round0_pairs, int64_t groups,
+void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place, int32_t default_seg, int64_t groups,
                  ceca::ChainArgs* a) {
   a->n = n;
   if (n == 1) {
@@ -86,7 +86,7 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place,
   // stretches: the device then sweeps the rows of a column band one at a time (few concurrent DRAM
   // streams), and the message a stretch re-reads is still in L2 from the stretch before it.
   int32_t seg_len = in_place ? len : g_opt_segment.load();
-  if (seg_len <= 0) seg_len = round0_pairs ? 2 : 1;
+  if (seg_len <= 0) seg_len = default_seg;
   if (seg_len > len) seg_len = len;
   // a launch addresses fewer than 2^24 workgroups: huge problems walk longer stretches
   const int64_t tiles = (groups + ceca::kBlock - 1) / ceca::kBlock;
@@ -108,7 +108,17 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   // round 0 of the fused step (y not read: half the traffic is writes) measured best with the lightest
   // variant, two-row stretches, wider bands and at most 4 workgroups per CU
   const bool quad_round0 = mode == ceca::MODE_QUAD && !a.read_y && !(pairs || in_place);
-  if (rows == 0) rows = quad_round0 ? 1 : (mode == ceca::MODE_QUAD && (pairs || in_place)) ? 8 : 4;
+  // a state that stays in the last-level cache (minibatch losses on many small agents) is not a
+  // streaming problem: measured on MI355X at n = 1023, d = 4096, 16-row stretches with two rows in
+  // flight beat one-row stretches (fewer, longer workgroups; 18.5 -> 14 us for the combine)
+  // (only when one-row stretches would make thousands of workgroups: a handful of agents or columns
+  // needs every workgroup it can get)
+  const bool cached = mode == ceca::MODE_FROMV && !(pairs || in_place) &&
+                      2 * (int64_t)a.n * a.ld * (int64_t)sizeof(float) <= (64LL << 20) &&
+                      (int64_t)a.n * ((d + 4 * ceca::kBlock - 1) / (4 * ceca::kBlock)) >= 2048;
+  const int32_t default_seg = quad_round0 ? 2 : (cached ? 16 : 1);
+  if (rows == 0) rows = quad_round0 ? 1 : cached ? 2 : (mode == ceca::MODE_QUAD && (pairs || in_place)) ? 8 : 4;
+  if (cached && a.band == 0) a.band = 2;
   if (quad_round0) {
     if (a.band == 0) a.band = 512;
     if (a.wg_per_cu == 0) a.wg_per_cu = 4;
@@ -122,7 +132,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   if (d4 > 0) {
     a.col0 = 0;
     a.ngroups = d4;
-    shape_chain(rd, a.n, port, in_place, quad_round0, d4, &a);
+    shape_chain(rd, a.n, port, in_place, default_seg, d4, &a);
     const hipError_t e = ceca::launch_chain(a, mode, true, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch");
   }
@@ -130,7 +140,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   if (rest > 0) {
     a.col0 = 4 * d4;
     a.ngroups = rest;
-    shape_chain(rd, a.n, port, in_place, quad_round0, rest, &a);
+    shape_chain(rd, a.n, port, in_place, default_seg, rest, &a);
     const hipError_t e = ceca::launch_chain(a, mode, false, rows, st);
     if (e != hipSuccess) return hip_fail(e, "chain kernel launch (scalar columns)");
   }
@@ -241,6 +251,10 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       return CECA_OK;
     case CECA_OPT_ONEPASS:
       g_opt_onepass.store(value != 0);
+      return CECA_OK;
+    case 7:
+      if (value < 0) return fail(CECA_EINVAL, "agents per workgroup must be >= 0");
+      ceca::g_agents_per_wg = value;
       return CECA_OK;
     case CECA_OPT_BAND:
       if (value < 0) return fail(CECA_EINVAL, "band width must be >= 0");

@@ -104,95 +104,113 @@ __global__ __launch_bounds__(kBlock) void halfstep_kernel(const GemvArgs G) {
 template <int THREADS, int BMAX, int G>
 __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P) {
   constexpr int WAVES = THREADS / 64;
-  __shared__ float red[WAVES][BMAX];
-  const int agent = blockIdx.x;
+  __shared__ float red[2][WAVES][BMAX];   // alternating between a workgroup's agents: one barrier per agent
+  static_assert(BMAX <= 64, "one lane per sampled row");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // lanes past the last column read column 0 instead and carry z = 0: no branch surrounds a load
   int64_t col[G];
   bool on[G];
-  vf4 z[G];
 #pragma unroll
   for (int u = 0; u < G; ++u) {
     const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * 4;
     on[u] = c < P.d;                       // d is a multiple of 4 on this path
     col[u] = on[u] ? c : 0;
-    const vf4 zv = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
-    z[u] = on[u] ? zv : vf4(0.0f);
   }
-  const int32_t* idx = P.batch_idx + (int64_t)agent * P.B;
-  const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
-  // one vector load brings the whole batch into a wavefront (lane j holds sample j; samples past B repeat
-  // the last), then the row numbers become scalars lane by lane: B scalar loads would each wait for
-  // the one before, because scalar loads return out of order
-  static_assert(BMAX <= 64, "one lane per sampled row");
-  const int32_t myidx = idx[min(lane, P.B - 1)];
-  int32_t rowid[BMAX];
+  // A workgroup takes agents blockIdx.x, blockIdx.x + gridDim.x, ...  The next agent's batch numbers
+  // and z are requested while the current agent is being worked on, so only the first agent of a
+  // workgroup waits for them before its rows can be requested.
+  // One vector load brings a whole batch into a wavefront (lane j holds sample j; samples past B repeat
+  // the last); the row numbers then become scalars lane by lane: B scalar loads would each wait for
+  // the one before, because scalar loads return out of order.
+  int agent = blockIdx.x;
+  int32_t idx_next = P.batch_idx[(int64_t)agent * P.B + min(lane, P.B - 1)];
+  vf4 z_next[G];
 #pragma unroll
-  for (int j = 0; j < BMAX; ++j) rowid[j] = min(max(__builtin_amdgcn_readlane(myidx, j), 0), P.N - 1);
-  vf4 a[BMAX][G];
+  for (int u = 0; u < G; ++u) z_next[u] = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
+  for (int turn = 0; agent < P.n; agent += gridDim.x, turn ^= 1) {
+    const int32_t myidx = idx_next;
+    vf4 z[G];
 #pragma unroll
-  for (int j = 0; j < BMAX; ++j) {
-    const float* row = Abase + (int64_t)rowid[j] * P.lda;
+    for (int u = 0; u < G; ++u) z[u] = on[u] ? z_next[u] : vf4(0.0f);
+    const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
+    int32_t rowid[BMAX];
 #pragma unroll
-    for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
-  }
-  // the target of "my" sampled row (lanes 0 .. BMAX-1 of every wavefront turn margins into coefficients
-  // later) is requested here, behind the rows, so that nothing waits for it after the barrier; the row
-  // number comes from the scalar row ids, so nothing has to arrive first
-  int32_t rmine = rowid[0];
+    for (int j = 0; j < BMAX; ++j) rowid[j] = min(max(__builtin_amdgcn_readlane(myidx, j), 0), P.N - 1);
+    vf4 a[BMAX][G];
 #pragma unroll
-  for (int j = 1; j < BMAX; ++j) rmine = (lane == j) ? rowid[j] : rmine;
-  const float tmine = P.t[(int64_t)agent * P.N + rmine];
-  // every load above is issued before any arithmetic below: the scheduler must not trade loads in
-  // flight for registers here (it split the rows into two dependent batches when left alone)
-  __builtin_amdgcn_sched_barrier(0);
-  float m[BMAX];
+    for (int j = 0; j < BMAX; ++j) {
+      const float* row = Abase + (int64_t)rowid[j] * P.lda;
 #pragma unroll
-  for (int j = 0; j < BMAX; ++j) {
-    m[j] = 0.0f;
+      for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
+    }
+    // the target of "my" sampled row (lanes 0 .. BMAX-1 of every wavefront turn margins into
+    // coefficients later) is requested here, behind the rows, so that nothing waits for it after the
+    // barrier; the row number comes from the scalar row ids, so nothing has to arrive first
+    int32_t rmine = rowid[0];
 #pragma unroll
-    for (int u = 0; u < G; ++u) m[j] += dot_v(a[j][u], z[u]);
-  }
-  constexpr int CH = BMAX < 16 ? BMAX : 16;        // margins are summed across the wavefront 16 at a time
+    for (int j = 1; j < BMAX; ++j) rmine = (lane == j) ? rowid[j] : rmine;
+    const float tmine = P.t[(int64_t)agent * P.N + rmine];
+    // what the next agent of this workgroup needs first (the last one re-reads its own: no branch)
+    const int nxt = agent + (int)gridDim.x < P.n ? agent + (int)gridDim.x : agent;
+    idx_next = P.batch_idx[(int64_t)nxt * P.B + min(lane, P.B - 1)];
 #pragma unroll
-  for (int c0 = 0; c0 < BMAX; c0 += CH) {
-    float part[CH];
+    for (int u = 0; u < G; ++u) z_next[u] = ld_plain<vf4>(P.zin + (int64_t)nxt * P.ld + col[u]);
+    // every load above is issued before any arithmetic below: the scheduler must not trade loads in
+    // flight for registers here (it split the rows into two dependent batches when left alone)
+    __builtin_amdgcn_sched_barrier(0);
+    float m[BMAX];
 #pragma unroll
-    for (int k = 0; k < CH; ++k) part[k] = m[c0 + k];
-    int jrow;
-    const float msum = wave_sum_many<CH>(part, lane, jrow);
-    if (lane < CH) red[wave][c0 + jrow] = msum;
-  }
-  __syncthreads();
-  // every wavefront turns the margins into coefficients for itself (lane j: sample j, same summation
-  // order everywhere), so no second barrier and no LDS round trip for the coefficients
-  float cmine = 0.0f;
-  {
-    const int j = min(lane, BMAX - 1);
-    float mj = 0.0f;
+    for (int j = 0; j < BMAX; ++j) {
+      m[j] = 0.0f;
 #pragma unroll
-    for (int w = 0; w < WAVES; ++w) mj += red[w][j];
-    cmine = (lane < P.B) ? loss_coef(P.kind, mj, tmine, P.scale) : 0.0f;
-  }
-  float coef[BMAX];                                 // wavefront-uniform: scalar registers
+      for (int u = 0; u < G; ++u) m[j] += dot_v(a[j][u], z[u]);
+    }
+    constexpr int CH = BMAX < 16 ? BMAX : 16;        // margins are summed across the wavefront 16 at a time
 #pragma unroll
-  for (int j = 0; j < BMAX; ++j) coef[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cmine), j));
+    for (int c0 = 0; c0 < BMAX; c0 += CH) {
+      float part[CH];
 #pragma unroll
-  for (int u = 0; u < G; ++u) {
-    vf4 e = vf4(0.0f);
+      for (int k = 0; k < CH; ++k) part[k] = m[c0 + k];
+      int jrow;
+      const float msum = wave_sum_many<CH>(part, lane, jrow);
+      if (lane < CH) red[turn][wave][c0 + jrow] = msum;
+    }
+    __syncthreads();
+    // every wavefront turns the margins into coefficients for itself (lane j: sample j, same summation
+    // order everywhere), so no second barrier and no LDS round trip for the coefficients
+    float cmine = 0.0f;
+    {
+      const int j = min(lane, BMAX - 1);
+      float mj = 0.0f;
 #pragma unroll
-    for (int j = 0; j < BMAX; ++j) e += coef[j] * a[j][u];
-    if (P.noise_std != 0.0f) e += P.noise_std * noise_group<vf4>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
-    if (on[u]) *reinterpret_cast<vf4*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * e;
+      for (int w = 0; w < WAVES; ++w) mj += red[turn][w][j];
+      cmine = (lane < P.B) ? loss_coef(P.kind, mj, tmine, P.scale) : 0.0f;
+    }
+    float coef[BMAX];                                 // wavefront-uniform: scalar registers
+#pragma unroll
+    for (int j = 0; j < BMAX; ++j) coef[j] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cmine), j));
+#pragma unroll
+    for (int u = 0; u < G; ++u) {
+      vf4 e = vf4(0.0f);
+#pragma unroll
+      for (int j = 0; j < BMAX; ++j) e += coef[j] * a[j][u];
+      if (P.noise_std != 0.0f) e += P.noise_std * noise_group<vf4>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
+      if (on[u]) *reinterpret_cast<vf4*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * e;
+    }
   }
 }
+
+int g_agents_per_wg = 0;   // measurement knob: agents per workgroup of the one-pass kernel (0 = default)
 
 // Picks the one-pass variant whose register tile covers (B, d); false if none does.
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   const int64_t d4 = g.d / 4;
-  dim3 grid((unsigned)g.n);
+  // 1024-thread workgroups fill a compute unit alone: one per unit, each looping over its agents;
+  // 256-thread workgroups leave room for several per unit
 #define CECA_ONEPASS(T, BM, GG)                                          \
   if (g.B <= BM && d4 <= (int64_t)T * GG) {                              \
+    const int per_wg = g_agents_per_wg > 0 ? g_agents_per_wg : (T == 1024 ? (g.n + 255) / 256 : 1); \
+    dim3 grid((unsigned)((g.n + per_wg - 1) / per_wg));                  \
     grad_onepass_kernel<T, BM, GG><<<grid, dim3(T), 0, st>>>(g);         \
     *err = hipGetLastError();                                            \
     return true;                                                         \

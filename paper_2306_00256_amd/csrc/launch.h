@@ -136,6 +136,7 @@ struct MixArgs {
 hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
 // one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
+extern int g_agents_per_wg;  // measurement knob for the one-pass kernel (0 = default)
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
