@@ -200,16 +200,100 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
   }
 }
 
-int g_agents_per_wg = 0;   // measurement knob: agents per workgroup of the one-pass kernel (0 = default)
+// The same computation with the batch taken CH rows at a time: only CH rows of A are in registers at
+// once, so two 1024-thread workgroups fit a compute unit and one computes while the other waits for
+// its rows.  e accumulates over the samples in the same order as in the kernel above.
+// (One column group per thread fits 64 registers, i.e. two workgroups per unit; wider rows take up to
+// 128 registers and one workgroup per unit, but still any batch size.)
+template <int THREADS, int CH, int G>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(G == 1 ? THREADS / 128 : THREADS / 256, THREADS / 128)))
+void grad_chunked_kernel(const GemvArgs P) {
+  constexpr int WAVES = THREADS / 64;
+  __shared__ float red[2][WAVES][CH];     // alternating between chunks: one barrier per chunk
+  static_assert(CH <= 16, "one wavefront sum per chunk");
+  const int agent = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int64_t col[G];
+  bool on[G];
+  vf4 z[G], e[G];
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * 4;
+    on[u] = c < P.d;
+    col[u] = on[u] ? c : 0;
+    const vf4 zv = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
+    z[u] = on[u] ? zv : vf4(0.0f);
+    e[u] = vf4(0.0f);
+  }
+  const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
+  // lane j holds sample j of the whole batch (B <= 64; samples past B repeat the last)
+  const int32_t myidx = min(max(P.batch_idx[(int64_t)agent * P.B + min(lane, P.B - 1)], 0), P.N - 1);
+  const float tmine = P.t[(int64_t)agent * P.N + myidx];
+  int turn = 0;
+  for (int c0 = 0; c0 < P.B; c0 += CH, turn ^= 1) {
+    vf4 a[CH][G];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const int32_t rj = __builtin_amdgcn_readlane(myidx, min(c0 + j, 63));
+      const float* row = Abase + (int64_t)rj * P.lda;
+#pragma unroll
+      for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float m[CH];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      m[j] = 0.0f;
+#pragma unroll
+      for (int u = 0; u < G; ++u) m[j] += dot_v(a[j][u], z[u]);
+    }
+    int jrow;
+    const float msum = wave_sum_many<CH>(m, lane, jrow);
+    if (lane < CH) red[turn][wave][jrow] = msum;
+    __syncthreads();
+    // lane c0 + j of every wavefront turns margin j of this chunk into its coefficient
+    const int jm = min(max(lane - c0, 0), CH - 1);
+    float mj = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) mj += red[turn][w][jm];
+    const float cmine = (lane >= c0 && lane < P.B) ? loss_coef(P.kind, mj, tmine, P.scale) : 0.0f;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const float cj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cmine), min(c0 + j, 63)));
+#pragma unroll
+      for (int u = 0; u < G; ++u) e[u] += cj * a[j][u];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    vf4 ee = e[u];
+    if (P.noise_std != 0.0f) ee += P.noise_std * noise_group<vf4>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
+    if (on[u]) *reinterpret_cast<vf4*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * ee;
+  }
+}
+
+int g_agents_per_wg = 0;   // measurement knob: agents per workgroup of the looping one-pass kernel (0 = default);
+                           // 1000 = never take the chunked kernel
 
 // Picks the one-pass variant whose register tile covers (B, d); false if none does.
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   const int64_t d4 = g.d / 4;
+  // many agents, long rows: the chunked kernel (any B up to 64, d up to 16384), two workgroups per
+  // compute unit; a handful of agents cannot fill the device that way and stays with the kernels below
+  if (g.n >= 128 && d4 > 256 && d4 <= 4096 && g_agents_per_wg != 1000) {
+    dim3 grid((unsigned)g.n), block(1024);
+    if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1><<<grid, block, 0, st>>>(g);
+    else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2><<<grid, block, 0, st>>>(g);
+    else if (d4 <= 3072) grad_chunked_kernel<1024, 2, 3><<<grid, block, 0, st>>>(g);
+    else grad_chunked_kernel<1024, 2, 4><<<grid, block, 0, st>>>(g);
+    *err = hipGetLastError();
+    return true;
+  }
   // 1024-thread workgroups fill a compute unit alone: one per unit, each looping over its agents;
   // 256-thread workgroups leave room for several per unit
 #define CECA_ONEPASS(T, BM, GG)                                          \
   if (g.B <= BM && d4 <= (int64_t)T * GG) {                              \
-    const int per_wg = g_agents_per_wg > 0 ? g_agents_per_wg : (T == 1024 ? (g.n + 255) / 256 : 1); \
+    const int per_wg = (g_agents_per_wg > 0 && g_agents_per_wg < 1000) ? g_agents_per_wg : (T == 1024 ? (g.n + 255) / 256 : 1); \
     dim3 grid((unsigned)((g.n + per_wg - 1) / per_wg));                  \
     grad_onepass_kernel<T, BM, GG><<<grid, dim3(T), 0, st>>>(g);         \
     *err = hipGetLastError();                                            \

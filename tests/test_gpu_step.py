@@ -213,8 +213,17 @@ def test_minibatch_step_variants(env, kind, n, port, d, B, off, ld, onepass):
         P.ceca_set_option(Bn.OPT_ONEPASS, 1)
 
 
-def _minibatch_variant(torch, P, kind, n, port, d, B, off, ld):
-    N, iters = 40, 7
+@pytest.mark.parametrize("kind", ["lsq", "logistic"])
+@pytest.mark.parametrize("n,port,d,B", [(130, 2, 2052, 5), (128, 1, 4096, 16), (129, 2, 8192, 33), (130, 1, 12000, 3),
+                                        (128, 2, 16384, 9), (131, 2, 4096, 64)])
+def test_many_agent_chunked_gradient(env, kind, n, port, d, B):
+    """Many agents with long rows take the gradient kernel that walks the batch a few rows at a time
+    (any B up to 64, 1 to 4 column groups per thread): per-step parity from the oracle's state."""
+    torch, P = env
+    _minibatch_variant(torch, P, kind, n, port, d, B, 0, None, N=12, iters=4)
+
+
+def _minibatch_variant(torch, P, kind, n, port, d, B, off, ld, N=40, iters=7):
     if kind == "lsq":
         A, t, _ = WL.lsq_data(n, N, d, seed=n)
     else:
