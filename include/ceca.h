@@ -217,8 +217,11 @@ int32_t ceca_last_hip_error(void);
  *   CECA_OPT_WG_PER_CU  cap on workgroups resident per compute unit, 2..8 (0 = library default)
  *   CECA_OPT_ONEPASS  1 (default): minibatch gradients keep the sampled rows in registers and read A once when
  *                     (B, d) fits; 0: always the two-pass margins / half-step kernels
+ *   CECA_OPT_AGENTS_PER_WG  agents one workgroup of the looping one-pass gradient kernel takes in turn
+ *                     (0 = library default); 1000: never use the chunked gradient kernel
  * Returns CECA_EINVAL for an unknown option or value. */
-enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5 };
+enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5,
+       CECA_OPT_AGENTS_PER_WG = 7 };
 int32_t ceca_set_option(int32_t option, int32_t value);
 
 #ifdef __cplusplus

@@ -252,7 +252,7 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
     case CECA_OPT_ONEPASS:
       g_opt_onepass.store(value != 0);
       return CECA_OK;
-    case 7:
+    case CECA_OPT_AGENTS_PER_WG:
       if (value < 0) return fail(CECA_EINVAL, "agents per workgroup must be >= 0");
       ceca::g_agents_per_wg = value;
       return CECA_OK;

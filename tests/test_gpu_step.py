@@ -223,6 +223,31 @@ def test_many_agent_chunked_gradient(env, kind, n, port, d, B):
     _minibatch_variant(torch, P, kind, n, port, d, B, 0, None, N=12, iters=4)
 
 
+def test_gradient_kernels_agree_bit_for_bit(env):
+    """The chunked kernel, the looping one-pass kernel (any number of agents per workgroup) and the
+    single-agent one-pass kernel accumulate in the same order: identical states after several steps."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, N, B, port = 130, 4096, 12, 16, 2
+    A, t, _ = WL.logistic_data_sparse(n, N, d, seed=3, density=0.5)
+    idx = WL.batch_indices(n, N, B, 5, seed=3)
+    Ad, td, idxd, loss = _minibatch_problem(torch, Bn, "logistic", A, t, idx)
+    ws = _workspace(torch, P, n, d, loss)
+    x0 = 0.05 * WL.initial_state(n, d, seed=4)
+    outs = []
+    try:
+        for knob in (0, 1000, 1, 3):
+            P.ceca_set_option(Bn.OPT_AGENTS_PER_WG, knob)
+            S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
+            for k in range(5):
+                P.dsgd_ceca_step(S, T, n, d, loss, idxd[k], 0.01, k % OS.num_rounds(n), port, workspace=ws)
+                S, T = T, S
+            outs.append(S.clone())
+    finally:
+        P.ceca_set_option(Bn.OPT_AGENTS_PER_WG, 0)
+    assert all(torch.equal(outs[0], o) for o in outs[1:])
+
+
 def _minibatch_variant(torch, P, kind, n, port, d, B, off, ld, N=40, iters=7):
     if kind == "lsq":
         A, t, _ = WL.lsq_data(n, N, d, seed=n)
