@@ -203,8 +203,20 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
         for _ in range(reps):
             graph.replay()
     tm.graph_ms_per_step = tg.event_ms / (reps * window)
+    # the same iterations through dsgd_ceca_run (one call for a window of iterations; with many agents one
+    # kernel per iteration): needs one step size and a batch table that covers the window
+    K = min(steps, nidx)
+    if not sp.lr_decay_every and K >= 2:
+        wsr = torch.empty(P.dsgd_ceca_run_workspace_bytes(n, d, loss0) + 256, dtype=torch.uint8, device="cuda")
+        wsr = wsr[(-wsr.data_ptr()) % 256:]
+        P.dsgd_ceca_run(S, T, n, d, loss0, idx[:K], sp.lr, 0, K, port, workspace=wsr, ld=ld)
+        with Timer(torch) as tr:
+            P.dsgd_ceca_run(S, T, n, d, loss0, idx[:K], sp.lr, 0, K, port, workspace=wsr, ld=ld)
+        tm.run_ms_per_step = tr.event_ms / K
+        tm.run_iterations_per_call = K
     # one-pass gradient + combine when the sampled rows fit the register tile, else margins + half step + combine
-    launches = 2 if d % 4 == 0 and ((B <= 16 and d <= 4096) or (B <= 8 and d <= 8192) or (B <= 4 and d <= 16384)) else 3
+    launches = 2 if d % 4 == 0 and ((n >= 128 and 1024 < d <= 16384) or (B <= 32 and d <= 1024) or (B <= 16 and d <= 4096)
+                                   or (B <= 8 and d <= 8192) or (B <= 4 and d <= 16384)) else 3
     return tm, launches, minibatch_bytes(B)
 
 
@@ -243,6 +255,8 @@ def measure(torch, P, Bn, name, steps, warmup):
     ev_ms = tm.event_ms / steps
     units = sp.n * sp.d
     extra = {"graph_replay_ms_per_step": tm.graph_ms_per_step} if hasattr(tm, "graph_ms_per_step") else {}
+    if hasattr(tm, "run_ms_per_step"):
+        extra.update({"run_call_ms_per_step": tm.run_ms_per_step, "run_iterations_per_call": tm.run_iterations_per_call})
     extra.update(getattr(tm, "fused", {}))
     return {
         **extra,

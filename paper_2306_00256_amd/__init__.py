@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     ceca_state_consensus,
     consensus_error,
     consensus_error_workspace_bytes,
+    dsgd_ceca_run,
+    dsgd_ceca_run_workspace_bytes,
     dsgd_ceca_step,
     dsgd_ceca_steps,
     dsgd_ceca_workspace_bytes,

@@ -15,7 +15,7 @@ TOPO_RING, TOPO_STATIC_EXP, TOPO_ONE_PEER_EXP = 0, 1, 2
 MIX_MAX = 16
 
 EXPORTS = (
-    "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps",
+    "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps", "dsgd_ceca_run_workspace_bytes", "dsgd_ceca_run",
     "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_last_error", "ceca_last_hip_error",
     "ceca_set_option",
 )
@@ -79,6 +79,11 @@ def lib():
         L.dsgd_ceca_steps.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Loss), C.c_float,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         L.dsgd_ceca_steps.restype = C.c_int32
+        L.dsgd_ceca_run_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.POINTER(Loss)]
+        L.dsgd_ceca_run_workspace_bytes.restype = C.c_int64
+        L.dsgd_ceca_run.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Loss), C.c_void_p,
+                                    C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+        L.dsgd_ceca_run.restype = C.c_int32
         L.consensus_error_workspace_bytes.argtypes = [C.c_int32, C.c_int64]
         L.consensus_error_workspace_bytes.restype = C.c_int64
         L.consensus_error.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
@@ -175,6 +180,19 @@ def dsgd_ceca_steps(S_in, S_out, n: int, d: int, loss: Loss, lr: float, r0: int,
     noise counters loss.k, loss.k + 1, ...)."""
     ld = int(S_in.stride(0)) if ld is None else ld
     _check(lib().dsgd_ceca_steps(_ptr(S_in), _ptr(S_out), n, d, ld, C.byref(loss), lr, r0, steps, port, _stream(stream)))
+
+
+def dsgd_ceca_run_workspace_bytes(n: int, d: int, loss: Loss) -> int:
+    return _check(lib().dsgd_ceca_run_workspace_bytes(n, d, C.byref(loss)))
+
+
+def dsgd_ceca_run(S_in, S_out, n: int, d: int, loss: Loss, batch_idx, lr: float, r0: int, iters: int, port: int,
+                  workspace=None, ld: Optional[int] = None, stream=None) -> None:
+    """`iters` iterations with a minibatch loss in one call (batch_idx: iters x n x B int32 on the device)."""
+    ld = int(S_in.stride(0)) if ld is None else ld
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().dsgd_ceca_run(_ptr(S_in), _ptr(S_out), n, d, ld, C.byref(loss), _ptr(batch_idx), lr, r0, iters, port,
+                               _ptr(workspace), wbytes, _stream(stream)))
 
 
 def consensus_error_workspace_bytes(n: int, d: int) -> int:

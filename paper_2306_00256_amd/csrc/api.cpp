@@ -101,7 +101,9 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   int rows = g_opt_rows.load();
   a.band = (uint32_t)g_opt_band.load();
   a.wg_per_cu = g_opt_wgs.load();
-  const bool in_place = a.xin == a.xout;
+  // combining from stored messages reads no other agent's state rows, so it can overwrite the state
+  // row by row with any stretch length; the other modes may only run whole cycles in place
+  const bool in_place = a.xin == a.xout && mode != ceca::MODE_FROMV;
   const bool pairs = port == 1 || a.n == 1;
   // rows in flight per thread: closed pairs and in-place cycles of the fused step like the fattest
   // variant (it also runs fewer workgroups per CU); one-row stretches want more, lighter workgroups
@@ -434,6 +436,108 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   a.aux = g.v;
   a.ldaux = g.ldv;
   return run_chain(a, ceca::MODE_FROMV, d, state_vec, rd, port, st);
+}
+
+int64_t dsgd_ceca_run_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss) {
+  if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
+  const int32_t rc = check_loss(loss, d, false, nullptr);
+  if (rc != CECA_OK) return rc;
+  if (loss->kind == CECA_LOSS_QUAD_CENTER) return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (use dsgd_ceca_steps)");
+  const GemvPlan p = gemv_plan(n, d, loss->B);
+  return 2 * p.v_bytes + p.partial_bytes;     // two message buffers (iterations alternate) + partial margins
+}
+
+int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, const ceca_loss_t* loss,
+                      const int32_t* batch_idx, float lr, int32_t r0, int32_t iters, int32_t port, void* workspace,
+                      int64_t workspace_bytes, void* hip_stream) {
+  ceca_round_t rd;
+  int32_t rc = check_state_call(S_in, S_out, n, d, ld, r0, port, &rd);
+  if (rc != CECA_OK) return rc;
+  rc = check_loss(loss, d, true, batch_idx);
+  if (rc != CECA_OK) return rc;
+  if (loss->kind == CECA_LOSS_QUAD_CENTER) return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (use dsgd_ceca_steps)");
+  if (iters < 1) return fail(CECA_EINVAL, "iters = %d: need at least one", iters);
+  const GemvPlan p = gemv_plan(n, d, loss->B);
+  const int64_t need = 2 * p.v_bytes + p.partial_bytes;
+  if (!workspace || workspace_bytes < need)
+    return fail(CECA_EWORKSPACE, "workspace of %lld bytes needed, %lld given", (long long)need,
+                (long long)(workspace ? workspace_bytes : 0));
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(CECA_EWORKSPACE, "workspace must be 256-byte aligned");
+  const int64_t sbytes = 2 * (int64_t)n * ld * 4;
+  if (overlaps(workspace, need, S_out, sbytes) || overlaps(workspace, need, S_in, sbytes))
+    return fail(CECA_EINVAL, "workspace overlaps the state");
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int32_t tau = ceca::tau_of(n);
+  char* w = reinterpret_cast<char*>(workspace);
+  const int64_t nb = (int64_t)n * loss->B;
+  const bool vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
+  const bool fused = vec && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg != 1000 &&
+                     ceca::grad_fused_covers(n, d);
+  ceca_loss_t one = *loss;
+  if (!fused) {
+    // one dsgd_ceca_step per iteration: the first from S_in to S_out, the rest in place on S_out
+    for (int32_t t = 0; t < iters; ++t) {
+      one.k = loss->k + (uint32_t)t;
+      rc = dsgd_ceca_step(t == 0 ? S_in : S_out, S_out, n, d, ld, &one, batch_idx + (int64_t)t * nb, lr,
+                          n == 1 ? 0 : (r0 + t) % tau, port, w + p.v_bytes, p.v_bytes + p.partial_bytes, st);
+      if (rc != CECA_OK) return rc;
+    }
+    return CECA_OK;
+  }
+  float* V[2] = {reinterpret_cast<float*>(w), reinterpret_cast<float*>(w + p.v_bytes)};
+  ceca::GemvArgs g{};
+  g.ld = ld;
+  g.A = loss->A;  g.lda = loss->lda;  g.t = loss->t;
+  g.ldv = p.ldv;
+  g.partial = reinterpret_cast<float*>(w + 2 * p.v_bytes);
+  g.d = d;
+  g.n = n;  g.N = loss->N;  g.B = loss->B;  g.kind = loss->kind;
+  g.lr = lr;
+  g.scale = loss->grad_scale > 0.0f ? loss->grad_scale : 1.0f / (float)loss->B;
+  g.noise_std = loss->noise_std;
+  g.seed = loss->seed;
+  g.chunk_cols = ceca::kBlock * ceca::kChunkGroups * 4;
+  g.nchunks = (int32_t)((d + g.chunk_cols - 1) / g.chunk_cols);
+  const float* xin = S_in;
+  const float* yin = S_in + (int64_t)n * ld;
+  float* xout = S_out;
+  float* yout = S_out + (int64_t)n * ld;
+  hipError_t e = hipSuccess;
+  ceca_round_t prev{};
+  for (int32_t t = 0; t < iters; ++t) {
+    ceca::fill_round(n, (r0 + t) % tau, port, &rd);
+    g.batch_idx = batch_idx + (int64_t)t * nb;
+    g.k = loss->k + (uint32_t)t;
+    g.v = V[t & 1];
+    if (t == 0) {
+      g.zin = rd.exchange_y ? yin : xin;
+      if (!ceca::launch_grad_onepass(g, st, &e)) return fail(CECA_EINVAL, "internal: gradient kernel does not cover this shape");
+    } else {
+      // the state before iteration t-1's combine: S_in for t = 1, then S_out (updated row by row in place)
+      g.px = (t == 1) ? xin : xout;
+      g.py = (t == 1) ? yin : yout;
+      g.ox = xout;  g.oy = yout;
+      g.pv = V[(t - 1) & 1];
+      g.p_shift = prev.shift;  g.p_port = port;
+      g.p_exch_y = prev.exchange_y;  g.p_read_y = prev.b_num != 0;
+      g.pa = prev.a;  g.pap = prev.a_peer;  g.pb = prev.b;  g.pbp = prev.b_peer;
+      g.new_exch_y = rd.exchange_y;
+      if (!ceca::launch_grad_fused(g, st, &e)) return fail(CECA_EINVAL, "internal: fused gradient kernel does not cover this shape");
+    }
+    if (e != hipSuccess) return hip_fail(e, "gradient kernel launch");
+    prev = rd;
+  }
+  // the last iteration's combine: from the state before it (S_out, or S_in when there was one iteration)
+  ceca::ChainArgs a{};
+  a.xin = xout;  a.yin = yout;
+  a.xout = xout; a.yout = yout;
+  a.ld = ld;
+  a.n = n;
+  a.lr = lr;
+  set_weights(prev, n, /*gossip_only=*/false, &a);
+  a.aux = V[(iters - 1) & 1];
+  a.ldaux = p.ldv;
+  return run_chain(a, ceca::MODE_FROMV, d, true, prev, port, st);
 }
 
 int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, const ceca_loss_t* loss,

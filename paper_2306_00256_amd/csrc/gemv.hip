@@ -205,7 +205,11 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 // its rows.  e accumulates over the samples in the same order as in the kernel above.
 // (One column group per thread fits 64 registers, i.e. two workgroups per unit; wider rows take up to
 // 128 registers and one workgroup per unit, but still any batch size.)
-template <int THREADS, int CH, int G>
+// FUSE: the workgroup first finishes the iteration before for its agent -- x+, y+ from x, y, its own
+// message and its peer's (Eqs. (8), (9), with the arithmetic of the combine kernel, operation for
+// operation) -- stores them, and takes the gradient at the new z.  One launch per iteration instead
+// of two, and the state rows (cache resident at these sizes) are touched once.
+template <int THREADS, int CH, int G, bool FUSE>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(G == 1 ? THREADS / 128 : THREADS / 256, THREADS / 128)))
 void grad_chunked_kernel(const GemvArgs P) {
   constexpr int WAVES = THREADS / 64;
@@ -221,17 +225,14 @@ void grad_chunked_kernel(const GemvArgs P) {
     const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * 4;
     on[u] = c < P.d;
     col[u] = on[u] ? c : 0;
-    const vf4 zv = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
-    z[u] = on[u] ? zv : vf4(0.0f);
-    e[u] = vf4(0.0f);
   }
   const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
   // lane j holds sample j of the whole batch (B <= 64; samples past B repeat the last)
   const int32_t myidx = min(max(P.batch_idx[(int64_t)agent * P.B + min(lane, P.B - 1)], 0), P.N - 1);
   const float tmine = P.t[(int64_t)agent * P.N + myidx];
-  int turn = 0;
-  for (int c0 = 0; c0 < P.B; c0 += CH, turn ^= 1) {
-    vf4 a[CH][G];
+  vf4 a[CH][G];
+  // rows c0 .. c0 + CH - 1 of the batch into the register tile
+  auto request_rows = [&](int c0) {
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
       const int32_t rj = __builtin_amdgcn_readlane(myidx, min(c0 + j, 63));
@@ -239,7 +240,47 @@ void grad_chunked_kernel(const GemvArgs P) {
 #pragma unroll
       for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
     }
-    __builtin_amdgcn_sched_barrier(0);
+  };
+  // without the prologue the first rows are requested before z; with it they follow it: the prologue
+  // needs 24 registers of its own, and loads return in order anyway
+  if (!FUSE) request_rows(0);
+#pragma unroll
+  for (int u = 0; u < G; ++u) {
+    vf4 zv;
+    if (FUSE) {
+#pragma clang fp contract(off)
+      int p;
+      if (P.p_port == 2) {
+        p = agent - P.p_shift; if (p < 0) p += P.n;
+      } else {
+        p = (agent & 1) ? agent - P.p_shift : agent + P.p_shift;
+        if (p < 0) p += P.n;
+        if (p >= P.n) p -= P.n;
+      }
+      const int64_t off = (int64_t)agent * P.ld + col[u];
+      const vf4 x = ld_plain<vf4>(P.px + off);
+      const vf4 y = P.p_read_y || P.p_exch_y ? ld_plain<vf4>(P.py + off) : vf4(0.0f);
+      const vf4 v = ld_plain<vf4>(P.pv + (int64_t)agent * P.ldv + col[u]);
+      const vf4 msg = ld_plain<vf4>(P.pv + (int64_t)p * P.ldv + col[u]);
+      const vf4 dz = v - (P.p_exch_y ? y : x);        // -lr e of the iteration before
+      const vf4 xs = P.p_exch_y ? x + dz : v;
+      const vf4 ys = P.p_exch_y ? v : y + dz;
+      const vf4 xn = combine(P.pa, xs, P.pap, msg);
+      const vf4 yn = P.p_read_y ? combine(P.pb, ys, P.pbp, msg) : P.pbp * msg;
+      if (on[u]) {
+        *reinterpret_cast<vf4*>(P.ox + off) = xn;
+        *reinterpret_cast<vf4*>(P.oy + off) = yn;
+      }
+      zv = P.new_exch_y ? yn : xn;
+    } else {
+      zv = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
+    }
+    z[u] = on[u] ? zv : vf4(0.0f);
+    e[u] = vf4(0.0f);
+  }
+  if (FUSE) request_rows(0);
+  int turn = 0;
+  for (int c0 = 0; c0 < P.B; c0 += CH, turn ^= 1) {
     float m[CH];
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
@@ -263,6 +304,7 @@ void grad_chunked_kernel(const GemvArgs P) {
 #pragma unroll
       for (int u = 0; u < G; ++u) e[u] += cj * a[j][u];
     }
+    if (c0 + CH < P.B) request_rows(c0 + CH);       // same for every thread
   }
 #pragma unroll
   for (int u = 0; u < G; ++u) {
@@ -275,17 +317,35 @@ void grad_chunked_kernel(const GemvArgs P) {
 int g_agents_per_wg = 0;   // measurement knob: agents per workgroup of the looping one-pass kernel (0 = default);
                            // 1000 = never take the chunked kernel
 
+// Shapes the chunked kernel takes (d a multiple of 4, vector layouts: checked by the caller).
+bool grad_fused_covers(int32_t n, int64_t d) {
+  const int64_t d4 = d / 4;
+  return n >= 128 && d4 > 256 && d4 <= 4096;
+}
+
+bool launch_grad_fused(const GemvArgs& g, hipStream_t st, hipError_t* err) {
+  if (!grad_fused_covers(g.n, g.d)) return false;
+  const int64_t d4 = g.d / 4;
+  dim3 grid((unsigned)g.n), block(1024);
+  if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1, true><<<grid, block, 0, st>>>(g);
+  else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2, true><<<grid, block, 0, st>>>(g);
+  else if (d4 <= 3072) grad_chunked_kernel<1024, 2, 3, true><<<grid, block, 0, st>>>(g);
+  else grad_chunked_kernel<1024, 2, 4, true><<<grid, block, 0, st>>>(g);
+  *err = hipGetLastError();
+  return true;
+}
+
 // Picks the one-pass variant whose register tile covers (B, d); false if none does.
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   const int64_t d4 = g.d / 4;
   // many agents, long rows: the chunked kernel (any B up to 64, d up to 16384), two workgroups per
   // compute unit; a handful of agents cannot fill the device that way and stays with the kernels below
-  if (g.n >= 128 && d4 > 256 && d4 <= 4096 && g_agents_per_wg != 1000) {
+  if (grad_fused_covers(g.n, g.d) && g_agents_per_wg != 1000) {
     dim3 grid((unsigned)g.n), block(1024);
-    if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1><<<grid, block, 0, st>>>(g);
-    else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2><<<grid, block, 0, st>>>(g);
-    else if (d4 <= 3072) grad_chunked_kernel<1024, 2, 3><<<grid, block, 0, st>>>(g);
-    else grad_chunked_kernel<1024, 2, 4><<<grid, block, 0, st>>>(g);
+    if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1, false><<<grid, block, 0, st>>>(g);
+    else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2, false><<<grid, block, 0, st>>>(g);
+    else if (d4 <= 3072) grad_chunked_kernel<1024, 2, 3, false><<<grid, block, 0, st>>>(g);
+    else grad_chunked_kernel<1024, 2, 4, false><<<grid, block, 0, st>>>(g);
     *err = hipGetLastError();
     return true;
   }

@@ -82,6 +82,16 @@ struct GemvArgs {
   float scale;            // factor on sum_j coef_j a_ij: 1/B, or the caller's grad_scale
   float noise_std;        // additive Gaussian gradient noise (0 = none), keyed by (seed, k)
   uint32_t seed, k;
+  // Fused form only (launch_grad_fused): the combine of the iteration before runs as a prologue.
+  // z is then the x or y row (new_exch_y) of the state this prologue produces.
+  const float* px;        // row 0 of x, y before that combine
+  const float* py;
+  float* ox;              // row 0 of x, y after it (may be px, py: a workgroup touches only its agent's rows)
+  float* oy;
+  const float* pv;        // messages of the iteration before, [n][ldv]
+  int32_t p_shift, p_port, p_exch_y, p_read_y;
+  float pa, pap, pb, pbp; // its weights
+  int32_t new_exch_y;
 };
 
 struct ConsensusArgs {
@@ -136,6 +146,9 @@ struct MixArgs {
 hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
 // one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
+// gradient kernel with the previous iteration's combine as its prologue; false when the shape is not covered
+bool launch_grad_fused(const GemvArgs& g, hipStream_t st, hipError_t* err);
+bool grad_fused_covers(int32_t n, int64_t d);
 extern int g_agents_per_wg;  // measurement knob for the one-pass kernel (0 = default)
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
