@@ -78,6 +78,18 @@ class Timer:
         self.event_ms = self.e0.elapsed_time(self.e1)
 
 
+def consensus_report(torch, P, X, n, d, ld):
+    """Consensus observables of the x rows, measured by the library (outside any timed region)."""
+    ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    out = torch.zeros(5, dtype=torch.float64, device="cuda")
+    P.consensus_error(X, n, d, out, workspace=ws, ld=ld)
+    torch.cuda.synchronize()
+    frob2, resid, mx, nrm, _ = out.tolist()
+    return {"max_dev_over_mean_norm": mx / nrm if nrm else None, "mean_distance_to_average": resid / n,
+            "mean_norm": nrm}
+
+
 def run_quad(torch, P, Bn, sp, steps, warmup):
     n, d, port = sp.n, sp.d, sp.port
     ld = _ld(d)
@@ -131,6 +143,16 @@ def run_gossip(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
+    # consensus error after each of the tau rounds from a fresh X(0) (not timed)
+    WL.device_normal((n, ld), seed=sp.seed, out=S[:n])
+    S[n:] = S[:n]
+    per_round = []
+    for r in range(tau):
+        P.ceca_gossip_round(S, T, n, d, r, port, ld=ld)
+        if port == 2:
+            S, T = T, S
+        per_round.append(consensus_report(torch, P, S[:n], n, d, ld)["max_dev_over_mean_norm"])
+    tm.consensus = {"max_dev_over_mean_norm_after_round": per_round}
     # all tau rounds fused into one pass (exact averaging): 12 bytes per agent-parameter in total
     for _ in range(2):
         P.ceca_gossip_rounds(S, T, n, d, tau, port, ld=ld)
@@ -138,7 +160,7 @@ def run_gossip(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tf:
         for _ in range(reps):
             P.ceca_gossip_rounds(S, T, n, d, tau, port, ld=ld)
-    tm.fused = {"fused_rounds": tau, "fused_ms": tf.event_ms / reps,
+    tm.fused = {"fused_rounds": tau, "fused_ms": tf.event_ms / reps, **tm.consensus,
                 "fused_GBs_on_12B": n * d * 12.0 / (tf.event_ms / reps * 1e-3) / 1e9}
     return tm, 1, chain_bytes("gossip", port, [k % tau for k in range(warmup, warmup + steps)])
 
@@ -184,6 +206,7 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
+    tm.final = consensus_report(torch, P, S[:n], n, d, ld)      # after warmup + steps iterations from x(0) = 0
     # launch-bound loops: the same iterations captured once as a HIP graph and replayed
     window = 2 * tau * max(1, 16 // tau)          # even number of steps: two-port buffers end where they began
     side = torch.cuda.Stream()
@@ -258,6 +281,8 @@ def measure(torch, P, Bn, name, steps, warmup):
     if hasattr(tm, "run_ms_per_step"):
         extra.update({"run_call_ms_per_step": tm.run_ms_per_step, "run_iterations_per_call": tm.run_iterations_per_call})
     extra.update(getattr(tm, "fused", {}))
+    if hasattr(tm, "final"):
+        extra["consensus_after_timed_steps"] = tm.final
     return {
         **extra,
         "workload": name, "n": sp.n, "d": sp.d, "port": sp.port, "loss": sp.loss, "steps": steps,
@@ -409,6 +434,12 @@ def main():
             "gather_model_GBs": main_res["gather_model_GBs"],
         },
     }
+    details = {k: main_res[k] for k in ("graph_replay_ms_per_step", "run_call_ms_per_step", "run_iterations_per_call",
+                                        "fused_rounds", "fused_ms", "fused_GBs_on_12B",
+                                        "max_dev_over_mean_norm_after_round", "consensus_after_timed_steps")
+               if k in main_res}
+    if details:
+        out["details"] = details
     if "fused_iterations_per_call" in main_res:
         # not the headline: `value` is the one-launch-per-iteration path that the metric names
         out["fused_iterations"] = {k: main_res[k] for k in ("fused_iterations_per_call", "fused_ms_per_iteration",
