@@ -71,3 +71,60 @@ def test_graph_replays_equal_eager(env, name):
         scratch = torch.randn(1024, device="cuda").sum().item()      # unrelated eager work between replays
         assert np.isfinite(scratch)
         assert np.array_equal(S2.cpu().numpy(), eager[rep]), rep
+
+
+def test_graph_of_the_multi_iteration_calls(env):
+    """dsgd_ceca_run (fused gradient + combine kernels), dsgd_ceca_steps, ceca_gossip_rounds,
+    ceca_mix_rounds and ceca_state_consensus captured in one graph: every replay equals the eager run."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, N, B, iters, port = 130, 2048, 8, 6, 5, 2
+    A, t, _ = WL.logistic_data_sparse(n, N, d, seed=2, density=0.5)
+    idx = torch.from_numpy(WL.batch_indices(n, N, B, iters, seed=2)).cuda()
+    Ad, td = torch.from_numpy(A).cuda(), torch.from_numpy(t).cuda()
+    loss = Bn.make_minibatch_loss(Bn.LOSS_LOGISTIC, Ad, td, N, B, noise_std=0.01, seed=3)
+    wsr = torch.empty(P.dsgd_ceca_run_workspace_bytes(n, d, loss) + 256, dtype=torch.uint8, device="cuda")
+    wsr = wsr[(-wsr.data_ptr()) % 256:]
+    wsc = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+    wsc = wsc[(-wsc.data_ptr()) % 256:]
+    c = torch.from_numpy(WL.quad_centers(n, d, 4)).cuda()
+    qloss = Bn.make_quad_center_loss(c, 0.01, 5, 0)
+    ring = [P.ceca_topology_round(Bn.TOPO_RING, n)]
+    x0 = 0.1 * WL.initial_state(n, d, 6)
+    tau = OS.num_rounds(n)
+
+    def window(S, out):
+        P.dsgd_ceca_run(S, S, n, d, loss, idx, 0.01, 0, iters, port, workspace=wsr)
+        P.dsgd_ceca_steps(S, S, n, d, qloss, 0.05, iters % tau, 3, port)
+        P.ceca_mix_rounds(S[:n], S[:n], n, d, ring, 2)
+        P.ceca_gossip_rounds(S, S, n, d, 2, port)
+        P.ceca_state_consensus(S, n, d, out, workspace=wsc)
+
+    replays = 3
+    S = make_state(torch, x0)
+    out = torch.zeros(11, dtype=torch.float64, device="cuda")
+    eager = []
+    for _ in range(replays):
+        window(S, out)
+        torch.cuda.synchronize()
+        eager.append((S.cpu().numpy().copy(), out.cpu().numpy().copy()))
+
+    S2 = make_state(torch, x0)
+    out2 = torch.zeros(11, dtype=torch.float64, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        window(S2, out2)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    S2.copy_(make_state(torch, x0))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        window(S2, out2)
+    S2.copy_(make_state(torch, x0))
+    for rep in range(replays):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.isfinite(torch.randn(1024, device="cuda").sum().item())      # unrelated eager work in between
+        assert np.array_equal(S2.cpu().numpy(), eager[rep][0]), rep
+        assert np.array_equal(out2.cpu().numpy(), eager[rep][1]), rep
