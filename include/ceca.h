@@ -236,9 +236,11 @@ int32_t ceca_last_hip_error(void);
  *                     (B, d) fits; 0: always the two-pass margins / half-step kernels
  *   CECA_OPT_AGENTS_PER_WG  agents one workgroup of the looping one-pass gradient kernel takes in turn
  *                     (0 = library default); 1000: never use the chunked gradient kernel
+ *   CECA_OPT_CONS_SINGLE_PASS  1 (default): consensus observables read x once when a workgroup's registers can
+ *                     hold a column tile of every agent; 0: always the two-pass kernels
  * Returns CECA_EINVAL for an unknown option or value. */
 enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5,
-       CECA_OPT_AGENTS_PER_WG = 7 };
+       CECA_OPT_AGENTS_PER_WG = 7, CECA_OPT_CONS_SINGLE_PASS = 8 };
 int32_t ceca_set_option(int32_t option, int32_t value);
 
 #ifdef __cplusplus

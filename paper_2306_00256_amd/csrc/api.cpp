@@ -20,6 +20,7 @@ std::atomic<int32_t> g_opt_rows{0};
 std::atomic<int32_t> g_opt_band{0};
 std::atomic<int32_t> g_opt_wgs{0};
 std::atomic<int32_t> g_opt_onepass{1};
+std::atomic<int32_t> g_opt_cons_tile{1};
 
 int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -202,6 +203,10 @@ struct ConsPlan {
   int64_t ntiles;
   int32_t agent_groups, agents_per_group, dev_agents;
   int64_t off_norm, off_devpart, off_dev2, total;
+  // single-pass form: rows per thread (0 = not available for this n), row lanes, tiles for 16-byte / scalar groups
+  int32_t rows_per_thread, row_lanes;
+  int64_t tile_ntiles_vec, tile_ntiles_scalar;
+  int64_t tile_off_devpart, tile_off_dev2;     // (normpart sits at offset 0)
 };
 
 ConsPlan cons_plan(int32_t n, int64_t d) {
@@ -226,6 +231,29 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
   p.off_devpart = off;  off += round_up((int64_t)n * p.ntiles * 8, 256);
   p.off_dev2 = off;     off += round_up((int64_t)n * 8, 256);
   p.total = off;
+  // single pass: every agent's column tile in one workgroup (x-only tiling of the fused-round kernels)
+  p.rows_per_thread = 0;
+  p.row_lanes = 0;
+  int32_t cap = g_opt_rows.load();
+  if (cap < 4 || cap > 32) cap = n <= 32 ? 16 : 32;     // wide tiles measured best on MI355X (n = 31, 100, 1023)
+  int32_t row_lanes = 1;
+  while (row_lanes * cap < n) row_lanes *= 2;
+  while (row_lanes <= ceca::kBlock && ((int64_t)n + 1) * (ceca::kBlock / row_lanes) * 8 > 65536) row_lanes *= 2;
+  // rows of the tile narrower than 128 bytes read poorly: with that many agents the single pass is kept
+  // only for small problems, where the two-pass form is bound by its five launches
+  const bool wide_enough = ceca::kBlock / (row_lanes < ceca::kBlock ? row_lanes : ceca::kBlock) >= 8 ||
+                           (int64_t)n * d * 4 <= (64LL << 20);
+  if (row_lanes <= ceca::kBlock && (n + row_lanes - 1) / row_lanes <= 32 && wide_enough) {
+    p.row_lanes = row_lanes;
+    p.rows_per_thread = (n + row_lanes - 1) / row_lanes;
+    const int64_t lanes = ceca::kBlock / row_lanes;
+    p.tile_ntiles_vec = ((d + 3) / 4 + lanes - 1) / lanes;
+    p.tile_ntiles_scalar = (d + lanes - 1) / lanes;
+    int64_t o = round_up(p.tile_ntiles_scalar * 8, 256);
+    p.tile_off_devpart = o;  o += round_up((int64_t)n * p.tile_ntiles_scalar * 8, 256);
+    p.tile_off_dev2 = o;     o += round_up((int64_t)n * 8, 256);
+    if (o > p.total) p.total = o;
+  }
   return p;
 }
 
@@ -253,6 +281,9 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       return CECA_OK;
     case CECA_OPT_ONEPASS:
       g_opt_onepass.store(value != 0);
+      return CECA_OK;
+    case CECA_OPT_CONS_SINGLE_PASS:
+      g_opt_cons_tile.store(value != 0);
       return CECA_OK;
     case CECA_OPT_AGENTS_PER_WG:
       if (value < 0) return fail(CECA_EINVAL, "agents per workgroup must be >= 0");
@@ -701,6 +732,16 @@ int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double
   c.out = out;
   c.xbar = xbar_or_null;
   const bool vec = aligned16(X) && ld % 4 == 0 && d % 4 == 0;
+  if (p.rows_per_thread > 0 && g_opt_cons_tile.load() != 0) {
+    // single pass over x; the workspace then holds only the partials
+    c.rows_per_thread = p.rows_per_thread;
+    c.row_lanes = p.row_lanes;
+    c.ntiles = vec ? p.tile_ntiles_vec : p.tile_ntiles_scalar;
+    c.colsum = nullptr;
+    c.normpart = reinterpret_cast<double*>(w);
+    c.devpart = reinterpret_cast<double*>(w + p.tile_off_devpart);
+    c.dev2 = reinterpret_cast<double*>(w + p.tile_off_dev2);
+  }
   const hipError_t e = ceca::launch_consensus(c, vec, (hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_fail(e, "consensus kernels launch");
   return CECA_OK;

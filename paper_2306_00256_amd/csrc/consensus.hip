@@ -107,6 +107,67 @@ __global__ __launch_bounds__(kBlock) void dev_kernel(const ConsensusArgs C) {
   }
 }
 
+// Single pass: a workgroup holds a column tile of every agent (RT rows per thread, the tiling of the
+// fused-round kernels), so x is read once: column sums across the workgroup through LDS (fp64, fixed
+// order), the mean in registers, then every row's squared distance to it and the tile's share of
+// ||xbar||^2.  Writes devpart[agent][tile], normpart[tile] and, if asked, xbar.
+template <int VEC, int RT>
+__global__ __launch_bounds__(kBlock) void cons_tile_kernel(const ConsensusArgs C) {
+  using V = typename VecOf<VEC>::T;
+  extern __shared__ double lds_d[];                // phase 1: [row_lanes][lanes * VEC]; phase 2: [n + 1][lanes]
+  const int lanes = kBlock / C.row_lanes;
+  const int cg = threadIdx.x % lanes;
+  const int rg = threadIdx.x / lanes;
+  const int64_t tile = blockIdx.x;
+  const int64_t g = tile * lanes + cg;
+  const int64_t ngroups = (C.d + VEC - 1) / VEC;   // d is a multiple of VEC on the vector path
+  const bool on = g < ngroups;
+  const int64_t col = (on ? g : 0) * VEC;          // lanes past the last column shadow column group 0
+  V x[RT];
+#pragma unroll
+  for (int k = 0; k < RT; ++k) {
+    const int i = min(rg + k * C.row_lanes, C.n - 1);    // rows past the last agent shadow it (weight 0 below)
+    x[k] = ld_stream<V>(C.X + (int64_t)i * C.ld + col);
+  }
+  double s[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int k = 0; k < RT; ++k)
+    if (rg + k * C.row_lanes < C.n) acc4(s, x[k]);
+#pragma unroll
+  for (int q = 0; q < VEC; ++q) lds_d[(rg * lanes + cg) * VEC + q] = s[q];
+  __syncthreads();
+  double m[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int r = 0; r < C.row_lanes; ++r) {
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) m[q] += lds_d[(r * lanes + cg) * VEC + q];
+  }
+#pragma unroll
+  for (int q = 0; q < VEC; ++q) m[q] /= (double)C.n;
+  __syncthreads();                                  // phase 1 values are consumed: the buffer changes shape
+#pragma unroll
+  for (int k = 0; k < RT; ++k) {
+    const int i = rg + k * C.row_lanes;
+    if (i < C.n) lds_d[i * lanes + cg] = on ? sqdev(x[k], m) : 0.0;
+  }
+  if (rg == 0) {
+    double sq = 0.0;
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) sq += m[q] * m[q];
+    lds_d[C.n * lanes + cg] = on ? sq : 0.0;
+    if (on && C.xbar) {
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) C.xbar[col + q] = (float)m[q];
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i <= C.n; i += kBlock) {
+    double t = 0.0;
+    for (int c = 0; c < lanes; ++c) t += lds_d[i * lanes + c];
+    if (i < C.n) C.devpart[(int64_t)i * C.ntiles + tile] = t;
+    else C.normpart[tile] = t;
+  }
+}
+
 // dev2[agent] = sum over tiles of devpart[agent][tile]
 __global__ __launch_bounds__(kBlock) void devsum_kernel(const ConsensusArgs C) {
   __shared__ double red[kBlock / 64];
@@ -155,7 +216,34 @@ hipError_t launch_phi(double* out, hipStream_t st) {
   return hipGetLastError();
 }
 
+static hipError_t launch_cons_tile(const ConsensusArgs& c, bool vec4, hipStream_t st) {
+  const int lanes = kBlock / c.row_lanes;
+  const size_t lds = sizeof(double) * (size_t)((c.n + 1) * lanes > kBlock * (vec4 ? 4 : 1) ? (c.n + 1) * lanes : kBlock * (vec4 ? 4 : 1));
+  if (c.ntiles < 1 || c.ntiles >= (1LL << 24) || lds > 65536 || c.rows_per_thread < 1 || c.rows_per_thread > 32)
+    return hipErrorInvalidConfiguration;
+  dim3 grid((unsigned)c.ntiles), block(kBlock);
+#define CECA_CONS4(RT) case RT: cons_tile_kernel<4, RT><<<grid, block, lds, st>>>(c); break
+#define CECA_CONS1(RT) cons_tile_kernel<1, RT><<<grid, block, lds, st>>>(c)
+  if (vec4) {
+    switch (c.rows_per_thread) {
+      CECA_CONS4(1); CECA_CONS4(2); CECA_CONS4(3); CECA_CONS4(4); CECA_CONS4(5); CECA_CONS4(6); CECA_CONS4(7); CECA_CONS4(8);
+      CECA_CONS4(9); CECA_CONS4(10); CECA_CONS4(11); CECA_CONS4(12); CECA_CONS4(13); CECA_CONS4(14); CECA_CONS4(15); CECA_CONS4(16);
+      CECA_CONS4(17); CECA_CONS4(18); CECA_CONS4(19); CECA_CONS4(20); CECA_CONS4(21); CECA_CONS4(22); CECA_CONS4(23); CECA_CONS4(24);
+      CECA_CONS4(25); CECA_CONS4(26); CECA_CONS4(27); CECA_CONS4(28); CECA_CONS4(29); CECA_CONS4(30); CECA_CONS4(31); CECA_CONS4(32);
+    }
+  } else if (c.rows_per_thread <= 4) CECA_CONS1(4);
+  else if (c.rows_per_thread <= 8) CECA_CONS1(8);
+  else if (c.rows_per_thread <= 16) CECA_CONS1(16);
+  else CECA_CONS1(32);
+#undef CECA_CONS4
+#undef CECA_CONS1
+  devsum_kernel<<<dim3((unsigned)c.n), block, 0, st>>>(c);
+  finish_kernel<<<dim3(1), block, 0, st>>>(c);
+  return hipGetLastError();
+}
+
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st) {
+  if (c.rows_per_thread > 0) return launch_cons_tile(c, vec4, st);
   const int vec = vec4 ? 4 : 1;
   const int64_t groups = (c.d + vec - 1) / vec;
   const int64_t gx = (groups + kBlock - 1) / kBlock;

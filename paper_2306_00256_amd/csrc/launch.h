@@ -109,6 +109,9 @@ struct ConsensusArgs {
   double* dev2;            // [n]
   double* out;             // 5 results
   float* xbar;             // optional
+  // single-pass form (every agent's column tile in one workgroup's registers); 0 rows = two-pass form
+  int32_t rows_per_thread; // 1..32 rows of x per thread
+  int32_t row_lanes;       // power of two, row_lanes * rows_per_thread >= n
 };
 
 // Fused iterations with the quadratic-centre loss: the rounds of MultiArgs plus what the gradient needs.

@@ -136,3 +136,41 @@ def test_state_consensus_entry_point(env, n, d, pad):
         assert got[off + 4] == n
     assert got[10] == got[0] + got[5]
     assert abs(got[10] - want["phi2"]) <= 1e-10 * max(want["phi2"], n * want["x"]["mean_norm"] ** 2)
+
+
+@pytest.mark.parametrize("n,d,pad,off", [(1, 5, 0, 0), (2, 1, 0, 0), (5, 1000, 0, 0), (6, 1027, 2, 0), (31, 4096, 0, 0),
+                                         (100, 3000, 8, 0), (130, 515, 0, 1), (1023, 4096, 0, 0), (1026, 37, 3, 0),
+                                         (3, 70001, 3, 0), (4000, 12, 0, 0), (4096, 9, 0, 0), (5000, 8, 0, 0)])
+def test_single_pass_and_two_pass_forms(env, n, d, pad, off):
+    """Both forms of the consensus kernels (x read once with every agent's column tile in one workgroup;
+    column sums first, deviations second) against the fp64 oracle, on aligned, padded and unaligned layouts."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    ld = d + pad
+    x = WL.initial_state(n, d, seed=n + d) * 2.0 + 0.7
+    buf = torch.zeros(n * ld + off + 8, dtype=torch.float32, device="cuda")
+    X = buf[off: off + n * ld].view(n, ld)
+    X[:, :d] = torch.from_numpy(x).cuda()
+    X[:, d:] = 1e30                                         # padding must never be read
+    want = OCONS.consensus_error(x)
+    ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    got = {}
+    try:
+        for mode in (1, 0):
+            P.ceca_set_option(Bn.OPT_CONS_SINGLE_PASS, mode)
+            out = torch.full((5,), -1.0, dtype=torch.float64, device="cuda")
+            xbar = torch.zeros(d, dtype=torch.float32, device="cuda")
+            P.consensus_error(X, n, d, out, xbar=xbar, workspace=ws, ld=ld)
+            torch.cuda.synchronize()
+            g = out.cpu().numpy()
+            got[mode] = g
+            scale = max(want["frob2"], 1e-300)
+            assert abs(g[0] - want["frob2"]) <= 1e-10 * scale, mode
+            assert abs(g[1] - want["residue"]) <= 1e-9 * max(want["residue"], 1e-300), mode
+            assert abs(g[2] - want["max_dev"]) <= 1e-9 * max(want["max_dev"], 1e-300), mode
+            assert abs(g[3] - want["mean_norm"]) <= 1e-10 * want["mean_norm"], mode
+            assert g[4] == n
+            assert np.abs(xbar.cpu().numpy() - want["mean"]).max() <= 1e-6 * max(np.abs(want["mean"]).max(), 1.0), mode
+    finally:
+        P.ceca_set_option(Bn.OPT_CONS_SINGLE_PASS, 1)
