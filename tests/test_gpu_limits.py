@@ -75,3 +75,53 @@ def test_mixing_rounds_at_the_agent_limit(env):
     with pytest.raises(P.CecaError) as e:
         P.ceca_mix_rounds(X, X, 4097, d, [P.ceca_topology_round(Bn.TOPO_RING, 4097)], 1)
     assert e.value.code == Bn.CECA_EINVAL
+
+
+@pytest.mark.parametrize("n,port", [(70001, 2), (70000, 1), (131072, 2)])
+def test_very_many_agents(env, n, port):
+    """More agents than any grid dimension but the first can index (65535): gossip rounds, fused rounds
+    (one launch per round at this size), the consensus observables and the state consensus call."""
+    torch, P = env
+    from oracle import consensus as OCONS
+    d = 6
+    tau = OS.num_rounds(n)
+    x0 = WL.initial_state(n, d, seed=n % 1000)
+    S = make_state(torch, x0)
+    T = make_state(torch, np.zeros_like(x0))
+    x = y = x0.astype(np.float64)
+    for r in range(3):
+        P.ceca_gossip_round(S, T, n, d, r, port)
+        S, T = T, S
+        x, y = OC.gossip_round(x, y, r, port, store32=True)
+    gx, gy = split_state(S, n, d)
+    assert max(rel_err(gx, x)) <= 1e-5 and max(rel_err(gy, y)) <= 1e-5
+    F = make_state(torch, x0)
+    P.ceca_gossip_rounds(F, F, n, d, tau, port)
+    fx, _ = split_state(F, n, d)
+    mean = x0.astype(np.float64).mean(axis=0)
+    assert np.abs(fx - mean).max() <= 5e-7          # inputs are N(0, 1): fp32 rounding of the early rounds
+    ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    out = torch.zeros(11, dtype=torch.float64, device="cuda")
+    P.ceca_state_consensus(S, n, d, out, workspace=ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = OCONS.state_consensus(gx, gy)
+    assert abs(got[0] - want["x"]["frob2"]) <= 1e-10 * want["x"]["frob2"]
+    assert abs(got[5] - want["y"]["frob2"]) <= 1e-10 * want["y"]["frob2"]
+    assert abs(got[10] - want["phi2"]) <= 1e-10 * want["phi2"]
+
+
+def test_minibatch_losses_refuse_more_than_65535_agents(env):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, N, B = 65536, 4, 2, 1
+    A = torch.zeros((n, N, d), dtype=torch.float32, device="cuda")
+    t = torch.zeros((n, N), dtype=torch.float32, device="cuda")
+    idx = torch.zeros((n, B), dtype=torch.int32, device="cuda")
+    S = torch.zeros((2 * n, d), dtype=torch.float32, device="cuda")
+    loss = Bn.make_minibatch_loss(Bn.LOSS_LSQ, A, t, N, B)
+    ws = torch.empty(max(P.dsgd_ceca_workspace_bytes(n, d, loss), 256), dtype=torch.uint8, device="cuda")
+    with pytest.raises(P.CecaError) as e:
+        P.dsgd_ceca_step(S, S, n, d, loss, idx, 0.1, 0, 2, workspace=ws)
+    assert e.value.code == Bn.CECA_EINVAL
