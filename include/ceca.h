@@ -152,10 +152,12 @@ int64_t dsgd_ceca_run_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* l
 /* `iters` consecutive DSGD-CECA iterations with a minibatch loss (LSQ or LOGISTIC) in one call.
  * Iteration t (t = 0 .. iters-1) uses round (r0 + t) mod tau, the noise counter loss->k + t, the batch
  * rows batch_idx + t * n * B (device, iters * n * B int32) and the one step size lr; the result has the
- * same bits as `iters` calls of dsgd_ceca_step.  With many agents and long rows (n >= 128,
- * 1024 < d <= 16384, 16-byte aligned layouts) each iteration after the first is ONE kernel: the
- * workgroup that takes agent i's gradient first finishes the iteration before for that agent
- * (Eqs. (8), (9)) from its own and its peer's message; otherwise the call loops over dsgd_ceca_step.
+ * same bits as `iters` calls of dsgd_ceca_step.  Where a workgroup can take an agent's whole rows
+ * (16-byte aligned layouts, d <= 16384, and either n >= 128 with d > 1024 or a batch that fits a
+ * register tile: B <= 32 at d <= 1024, 16 at 4096, 8 at 8192, 4 at 16384) each iteration after the
+ * first is ONE kernel: the workgroup that takes agent i's gradient first finishes the iteration before
+ * for that agent (Eqs. (8), (9)) from its own and its peer's message; otherwise the call loops over
+ * dsgd_ceca_step.
  * S_out may be S_in or disjoint from it; when disjoint, S_in is left unchanged.
  * workspace: device, 256-byte aligned, at least dsgd_ceca_run_workspace_bytes(); contents are scratch. */
 int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,

@@ -503,7 +503,7 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
   const int64_t nb = (int64_t)n * loss->B;
   const bool vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
   const bool fused = vec && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg != 1000 &&
-                     ceca::grad_fused_covers(n, d);
+                     ceca::grad_fused_covers(n, d, loss->B);
   ceca_loss_t one = *loss;
   if (!fused) {
     // one dsgd_ceca_step per iteration: the first from S_in to S_out, the rest in place on S_out

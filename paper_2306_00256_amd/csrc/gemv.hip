@@ -203,14 +203,14 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 // The same computation with the batch taken CH rows at a time: only CH rows of A are in registers at
 // once, so two 1024-thread workgroups fit a compute unit and one computes while the other waits for
 // its rows.  e accumulates over the samples in the same order as in the kernel above.
-// (One column group per thread fits 64 registers, i.e. two workgroups per unit; wider rows take up to
-// 128 registers and one workgroup per unit, but still any batch size.)
+// (One column group per thread fits 64 registers, i.e. two 1024-thread workgroups per unit; wider rows
+// take up to 128 registers and one such workgroup per unit, but still any batch size.)
 // FUSE: the workgroup first finishes the iteration before for its agent -- x+, y+ from x, y, its own
 // message and its peer's (Eqs. (8), (9), with the arithmetic of the combine kernel, operation for
 // operation) -- stores them, and takes the gradient at the new z.  One launch per iteration instead
 // of two, and the state rows (cache resident at these sizes) are touched once.
 template <int THREADS, int CH, int G, bool FUSE>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(G == 1 ? THREADS / 128 : THREADS / 256, THREADS / 128)))
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(G == 1 ? 8 : 4, 8)))
 void grad_chunked_kernel(const GemvArgs P) {
   constexpr int WAVES = THREADS / 64;
   __shared__ float red[2][WAVES][CH];     // alternating between chunks: one barrier per chunk
@@ -317,21 +317,41 @@ void grad_chunked_kernel(const GemvArgs P) {
 int g_agents_per_wg = 0;   // measurement knob: agents per workgroup of the looping one-pass kernel (0 = default);
                            // 1000 = never take the chunked kernel
 
-// Shapes the chunked kernel takes (d a multiple of 4, vector layouts: checked by the caller).
-bool grad_fused_covers(int32_t n, int64_t d) {
+// The chunked kernel for rows of d4 16-byte groups.  Workgroup size and column groups per thread are a
+// function of d4 alone and equal those of the one-pass variant for the same d4, so either kernel (and
+// the fused form) produces the same bits.
+template <bool FUSE>
+static hipError_t launch_chunked(const GemvArgs& g, hipStream_t st) {
+  const int64_t d4 = g.d / 4;
+  dim3 grid((unsigned)g.n);
+  if (d4 <= 256) grad_chunked_kernel<256, 8, 1, FUSE><<<grid, dim3(256), 0, st>>>(g);
+  else if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1, FUSE><<<grid, dim3(1024), 0, st>>>(g);
+  else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2, FUSE><<<grid, dim3(1024), 0, st>>>(g);
+  else grad_chunked_kernel<1024, 2, 4, FUSE><<<grid, dim3(1024), 0, st>>>(g);
+  return hipGetLastError();
+}
+
+// A one-pass variant with the whole batch in registers exists for (B, d4).
+static bool onepass_tile_exists(int32_t B, int64_t d4) {
+  return (B <= 32 && d4 <= 256) || (B <= 16 && d4 <= 1024) || (B <= 8 && d4 <= 2048) || (B <= 4 && d4 <= 4096);
+}
+
+// With many agents and long rows the chunked kernel is the default for a single step.
+static bool chunked_by_default(int32_t n, int64_t d4) { return n >= 128 && d4 > 256 && d4 <= 4096; }
+
+// Shapes whose iterations can run as one fused kernel each with the bits of single steps: those where a
+// single step already uses the chunked kernel, and those where it uses a one-pass variant (same bits).
+// Few agents with a batch too large for a register tile stay with the two-pass kernels: a handful of
+// workgroups walking megabytes of rows would be slower than three launches.
+// (d a multiple of 4, vector layouts: checked by the caller.)
+bool grad_fused_covers(int32_t n, int64_t d, int32_t B) {
   const int64_t d4 = d / 4;
-  return n >= 128 && d4 > 256 && d4 <= 4096;
+  return n >= 2 && d4 <= 4096 && (chunked_by_default(n, d4) || onepass_tile_exists(B, d4));
 }
 
 bool launch_grad_fused(const GemvArgs& g, hipStream_t st, hipError_t* err) {
-  if (!grad_fused_covers(g.n, g.d)) return false;
-  const int64_t d4 = g.d / 4;
-  dim3 grid((unsigned)g.n), block(1024);
-  if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1, true><<<grid, block, 0, st>>>(g);
-  else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2, true><<<grid, block, 0, st>>>(g);
-  else if (d4 <= 3072) grad_chunked_kernel<1024, 2, 3, true><<<grid, block, 0, st>>>(g);
-  else grad_chunked_kernel<1024, 2, 4, true><<<grid, block, 0, st>>>(g);
-  *err = hipGetLastError();
+  if (!grad_fused_covers(g.n, g.d, g.B)) return false;
+  *err = launch_chunked<true>(g, st);
   return true;
 }
 
@@ -340,13 +360,8 @@ bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   const int64_t d4 = g.d / 4;
   // many agents, long rows: the chunked kernel (any B up to 64, d up to 16384), two workgroups per
   // compute unit; a handful of agents cannot fill the device that way and stays with the kernels below
-  if (grad_fused_covers(g.n, g.d) && g_agents_per_wg != 1000) {
-    dim3 grid((unsigned)g.n), block(1024);
-    if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1, false><<<grid, block, 0, st>>>(g);
-    else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2, false><<<grid, block, 0, st>>>(g);
-    else if (d4 <= 3072) grad_chunked_kernel<1024, 2, 3, false><<<grid, block, 0, st>>>(g);
-    else grad_chunked_kernel<1024, 2, 4, false><<<grid, block, 0, st>>>(g);
-    *err = hipGetLastError();
+  if (chunked_by_default(g.n, d4) && g_agents_per_wg != 1000) {
+    *err = launch_chunked<false>(g, st);
     return true;
   }
   // 1024-thread workgroups fill a compute unit alone: one per unit, each looping over its agents;
