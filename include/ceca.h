@@ -119,6 +119,15 @@ int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d,
 int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                            int32_t rounds, int32_t port, void* hip_stream);
 
+/* Exact averaging (the problem CECA solves, Sec. 3.1): X_out row i = (1/n) sum_j X_in row j for every i,
+ * reached by tau = ceil(log2 n) CECA rounds carried through registers, with the arithmetic of
+ * ceca_gossip_rounds(rounds = tau) -- the x rows have the same bits -- but the auxiliary y is neither
+ * read nor written: 8 bytes per agent-parameter.  X_in, X_out: device, n rows of ld floats; X_out may be
+ * X_in or disjoint from it.  port = 1 needs even n.  Limits: n <= 4096 (CECA_EINVAL beyond; use
+ * ceca_gossip_rounds on a full state there). */
+int32_t ceca_average(const float* X_in, float* X_out, int32_t n, int64_t d, int64_t ld, int32_t port,
+                     void* hip_stream);
+
 /* Bytes of device workspace dsgd_ceca_step needs for this problem (0 for QUAD_CENTER); < 0 on error. */
 int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss);
 

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     Loss,
     Mix,
     Round,
+    ceca_average,
     ceca_gossip_round,
     ceca_gossip_rounds,
     ceca_mix_rounds,

@@ -15,7 +15,7 @@ TOPO_RING, TOPO_STATIC_EXP, TOPO_ONE_PEER_EXP = 0, 1, 2
 MIX_MAX = 16
 
 EXPORTS = (
-    "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps", "dsgd_ceca_run_workspace_bytes", "dsgd_ceca_run",
+    "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "ceca_average", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps", "dsgd_ceca_run_workspace_bytes", "dsgd_ceca_run",
     "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_last_error", "ceca_last_hip_error",
     "ceca_set_option",
 )
@@ -76,6 +76,8 @@ def lib():
                                      C.c_void_p, C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
                                      C.c_void_p]
         L.dsgd_ceca_step.restype = C.c_int32
+        L.ceca_average.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.c_void_p]
+        L.ceca_average.restype = C.c_int32
         L.dsgd_ceca_steps.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Loss), C.c_float,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         L.dsgd_ceca_steps.restype = C.c_int32
@@ -160,6 +162,12 @@ def ceca_mix_rounds(X_in, X_out, n: int, d: int, specs: Sequence[Mix], rounds: i
     ld = int(X_in.stride(0)) if ld is None else ld
     arr = (Mix * len(specs))(*specs)
     _check(lib().ceca_mix_rounds(_ptr(X_in), _ptr(X_out), n, d, ld, arr, len(specs), k0, rounds, _stream(stream)))
+
+
+def ceca_average(X_in, X_out, n: int, d: int, port: int, ld: Optional[int] = None, stream=None) -> None:
+    """Every row of X_out becomes the mean of the rows of X_in (tau CECA rounds in one pass, x only)."""
+    ld = int(X_in.stride(0)) if ld is None else ld
+    _check(lib().ceca_average(_ptr(X_in), _ptr(X_out), n, d, ld, port, _stream(stream)))
 
 
 def dsgd_ceca_workspace_bytes(n: int, d: int, loss: Loss) -> int:

@@ -384,6 +384,51 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
   return CECA_OK;
 }
 
+int32_t ceca_average(const float* X_in, float* X_out, int32_t n, int64_t d, int64_t ld, int32_t port, void* hip_stream) {
+  if (!X_in || !X_out) return fail(CECA_EINVAL, "null pointer");
+  if (n < 1 || n > 4096) return fail(CECA_EINVAL, "n = %d: exact averaging in one pass takes 1 to 4096 agents", n);
+  if (d < 1 || ld < d) return fail(CECA_EINVAL, "need 1 <= d <= ld (d = %lld, ld = %lld)", (long long)d, (long long)ld);
+  if (port != 1 && port != 2) return fail(CECA_EINVAL, "port = %d: must be 1 or 2", port);
+  if (port == 1 && n > 1 && (n & 1)) return fail(CECA_EODD1P, "one-port CECA needs an even number of agents (n = %d)", n);
+  const int64_t bytes = (int64_t)n * ld * (int64_t)sizeof(float);
+  if (overlaps(X_in, bytes, X_out, bytes) && (const void*)X_in != (const void*)X_out)
+    return fail(CECA_EINVAL, "X_out partially overlaps X_in");
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int32_t tau = ceca::tau_of(n);
+  int32_t cap = g_opt_rows.load();
+  if (cap < 4 || cap > ceca::kMultiRows) cap = (n <= 256) ? 8 : ceca::kMultiRows;
+  int32_t row_lanes = 1;
+  while (row_lanes * cap < n) row_lanes *= 2;
+  if (row_lanes > ceca::kBlock) row_lanes = ceca::kBlock;
+  ceca::MultiArgs m{};
+  m.xin = X_in;
+  m.xout = X_out;  m.yout = nullptr;
+  m.ld = ld;
+  m.n = n;  m.port = port;  m.rounds = tau;          // n = 1: no rounds, the kernel copies
+  m.row_lanes = row_lanes;
+  m.rows_per_thread = (n + row_lanes - 1) / row_lanes;
+  ceca_round_t rd;
+  for (int32_t t = 0; t < tau; ++t) {
+    ceca::fill_round(n, t, port, &rd);
+    ceca::MultiRound& R = m.round[t];
+    R.shift = rd.shift;  R.exch_y = rd.exchange_y;  R.read_y = rd.b_num != 0;
+    R.a = rd.a;  R.ap = rd.a_peer;  R.b = rd.b;  R.bp = rd.b_peer;
+  }
+  const bool can_vec = aligned16(X_in) && aligned16(X_out) && ld % 4 == 0;
+  const int64_t d4 = can_vec ? d / 4 : 0;
+  if (d4 > 0) {
+    m.col0 = 0;  m.ngroups = d4;
+    const hipError_t e = ceca::launch_multi_round(m, true, st);
+    if (e != hipSuccess) return hip_fail(e, "averaging kernel launch");
+  }
+  if (d - 4 * d4 > 0) {
+    m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+    const hipError_t e = ceca::launch_multi_round(m, false, st);
+    if (e != hipSuccess) return hip_fail(e, "averaging kernel launch (scalar columns)");
+  }
+  return CECA_OK;
+}
+
 int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss) {
   if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
   const int32_t rc = check_loss(loss, d, false, nullptr);

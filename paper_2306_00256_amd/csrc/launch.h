@@ -54,7 +54,7 @@ constexpr int kMultiMaxRounds = 64;
 struct MultiArgs {
   const float* xin;    // row 0 of x in S_in (y of S_in is not read: round 0 overwrites it)
   float* xout;
-  float* yout;
+  float* yout;         // NULL: y is not stored (exact averaging only needs x)
   int64_t ld;
   int64_t col0;
   int64_t ngroups;

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) 
     const int i = rg + k * M.row_lanes;
     if (i < M.n) {
       st_stream<V>(M.xout + (int64_t)i * M.ld + col, x[k]);
-      st_stream<V>(M.yout + (int64_t)i * M.ld + col, y[k]);
+      if (M.yout) st_stream<V>(M.yout + (int64_t)i * M.ld + col, y[k]);   // same for every thread
     }
   }
 }

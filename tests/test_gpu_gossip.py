@@ -254,3 +254,47 @@ def test_finite_time_consensus_residue(env, n, port):
             assert got[1] > 1e-3 * n                      # not at consensus before the last round
     assert residues[-1] <= 1e-6 * n * np.sqrt(d) * 0.2      # ~1e-7 per entry
     assert all(b < a for a, b in zip(residues, residues[1:]))
+
+
+@pytest.mark.parametrize("n,port", [(1, 2), (2, 1), (3, 2), (5, 2), (6, 1), (31, 2), (30, 1), (100, 1), (100, 2), (130, 1),
+                                    (1023, 2), (1026, 1), (4096, 2)])
+@pytest.mark.parametrize("d,pad,off", [(1037, 3, 0), (256, 0, 1)])
+def test_exact_averaging_call(env, n, port, d, pad, off):
+    """ceca_average: every output row is the plain column mean (the definition; 1e-6 relative to its
+    norm), the rows are the x rows of ceca_gossip_rounds(rounds = tau) bit for bit, in place or not."""
+    torch, P = env
+    if n > 1000:
+        d = 64 + (d % 5)
+    ld = d + pad
+    x0 = WL.initial_state(n, d, seed=11 * n + port)
+    buf = torch.full((n * ld + off + 8,), 12345.0, dtype=torch.float32, device="cuda")
+    X = buf[off: off + n * ld].view(n, ld)
+    X[:, :d] = torch.from_numpy(x0).cuda()
+    Y = torch.full_like(X, 12345.0)
+    P.ceca_average(X, Y, n, d, port, ld=ld)
+    got = Y[:, :d].cpu().numpy().astype(np.float64)
+    mean = x0.astype(np.float64).mean(axis=0)
+    assert np.sqrt(((got - mean) ** 2).sum(axis=1)).max() <= 1e-6 * max(np.sqrt((mean ** 2).sum()), 1e-30) + 1e-7
+    assert bool((Y[:, d:] == 12345.0).all())
+    tau = OS.num_rounds(n)
+    if n > 1:
+        S = make_state(torch, x0, y0=np.full_like(x0, np.nan))
+        T = make_state(torch, np.zeros_like(x0))
+        P.ceca_gossip_rounds(S, T, n, d, tau, port)
+        assert np.array_equal(split_state(T, n, d)[0], got)
+    P.ceca_average(X, X, n, d, port, ld=ld)
+    assert torch.equal(X[:, :d], Y[:, :d])
+
+
+def test_exact_averaging_errors(env):
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    X = torch.zeros((5, 8), dtype=torch.float32, device="cuda")
+    for n, port, code in [(5, 1, Bn.CECA_EODD1P), (4, 3, Bn.CECA_EINVAL), (0, 2, Bn.CECA_EINVAL)]:
+        with pytest.raises(P.CecaError) as e:
+            P.ceca_average(X, X, n, 8, port)
+        assert e.value.code == code
+    big = torch.zeros((4097, 4), dtype=torch.float32, device="cuda")
+    with pytest.raises(P.CecaError) as e:
+        P.ceca_average(big, big, 4097, 4, 2)
+    assert e.value.code == Bn.CECA_EINVAL
