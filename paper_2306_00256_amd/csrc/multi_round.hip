@@ -35,34 +35,55 @@ __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) 
     y[k] = V(0.0f);                                // round 0 has b = 0: y(0) is never used
   }
   V* zs = reinterpret_cast<V*>(lds_z);
+  // LDS slot of each of my rows (rows past the last agent shadow it and are never published)
+  int slot[RT];
+  bool mine[RT];
+#pragma unroll
+  for (int k = 0; k < RT; ++k) {
+    const int i = rg + k * M.row_lanes;
+    mine[k] = i < M.n;
+    slot[k] = min(i, M.n - 1) * lanes + cg;
+  }
+  const int wrap = M.n * lanes;
   for (int t = 0; t < M.rounds; ++t) {
     const MultiRound R = M.round[t];
+    // the round's flags are the same for every thread: branches, not per-element selects
+    if (R.exch_y) {
 #pragma unroll
-    for (int k = 0; k < RT; ++k) {
-      const int i = rg + k * M.row_lanes;
-      if (i < M.n) zs[i * lanes + cg] = R.exch_y ? y[k] : x[k];
+      for (int k = 0; k < RT; ++k) if (mine[k]) zs[slot[k]] = y[k];
+    } else {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) if (mine[k]) zs[slot[k]] = x[k];
     }
     __syncthreads();
-    // no branch around the LDS reads: threads past the last agent shadow it (their rows are never
-    // published or stored), so a thread's RT reads issue back to back
+    // no branch around the LDS reads, so a thread's RT reads issue back to back
     V zp[RT];
+    const int back = R.shift * lanes;
+    if (M.port == 2) {
 #pragma unroll
-    for (int k = 0; k < RT; ++k) {
-      const int i = min(rg + k * M.row_lanes, M.n - 1);
-      int p;
-      if (M.port == 2) {
-        p = i - R.shift; if (p < 0) p += M.n;
-      } else {
-        p = (i & 1) ? i - R.shift : i + R.shift;
-        if (p < 0) p += M.n;
-        if (p >= M.n) p -= M.n;
+      for (int k = 0; k < RT; ++k) {
+        int q = slot[k] - back;
+        if (q < 0) q += wrap;
+        zp[k] = zs[q];
       }
-      zp[k] = zs[p * lanes + cg];
+    } else {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) {
+        const int i = min(rg + k * M.row_lanes, M.n - 1);
+        int q = (i & 1) ? slot[k] - back : slot[k] + back;     // even rows look ahead, odd rows back (Eq. (7))
+        if (q < 0) q += wrap;
+        if (q >= wrap) q -= wrap;
+        zp[k] = zs[q];
+      }
     }
 #pragma unroll
-    for (int k = 0; k < RT; ++k) {
-      x[k] = combine(R.a, x[k], R.ap, zp[k]);
-      y[k] = R.read_y ? combine(R.b, y[k], R.bp, zp[k]) : R.bp * zp[k];
+    for (int k = 0; k < RT; ++k) x[k] = combine(R.a, x[k], R.ap, zp[k]);
+    if (R.read_y) {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) y[k] = combine(R.b, y[k], R.bp, zp[k]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) y[k] = R.bp * zp[k];
     }
     __syncthreads();
   }
@@ -120,14 +141,21 @@ __global__ __launch_bounds__(kBlock) void multi_step_kernel(const StepsArgs S) {
   for (int t = 0; t < M.rounds; ++t) {
     const MultiRound R = M.round[t];
     V ge[RT];
-#pragma unroll
-    for (int k = 0; k < RT; ++k) {
+    // local step of row k at z (its x or y): lr * e stays in registers, the message v_i goes to LDS
+    auto half_step = [&](int k, const V& z) {
       const int i = min(rg + k * M.row_lanes, M.n - 1);
-      const V z = R.exch_y ? y[k] : x[k];
       V e = z - c[k];
       if (S.noise_std != 0.0f) e += S.noise_std * noise_group<V>(col, noise_keys(S.seed, S.k0 + (uint32_t)t, (uint32_t)i));
       ge[k] = S.lr * e;
-      if (rg + k * M.row_lanes < M.n) zs[i * lanes + cg] = z - ge[k];      // the message v_i
+      if (rg + k * M.row_lanes < M.n) zs[i * lanes + cg] = z - ge[k];
+    };
+    // the round's flags are the same for every thread: branches, not per-element selects
+    if (R.exch_y) {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) half_step(k, y[k]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) half_step(k, x[k]);
     }
     __syncthreads();
     V zp[RT];
@@ -145,11 +173,13 @@ __global__ __launch_bounds__(kBlock) void multi_step_kernel(const StepsArgs S) {
       zp[k] = zs[p * lanes + cg];
     }
 #pragma unroll
-    for (int k = 0; k < RT; ++k) {
-      const V xs = x[k] - ge[k];
-      const V ys = y[k] - ge[k];
-      x[k] = combine(R.a, xs, R.ap, zp[k]);
-      y[k] = R.read_y ? combine(R.b, ys, R.bp, zp[k]) : R.bp * zp[k];
+    for (int k = 0; k < RT; ++k) x[k] = combine(R.a, x[k] - ge[k], R.ap, zp[k]);
+    if (R.read_y) {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) y[k] = combine(R.b, y[k] - ge[k], R.bp, zp[k]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) y[k] = R.bp * zp[k];
     }
     __syncthreads();
   }
