@@ -97,3 +97,29 @@ def test_host_side_errors(api):
     assert L.ceca_state_consensus(p, 4, 8, 8, p, p, 8, None) == Bn.CECA_EWORKSPACE     # workspace too small
     with pytest.raises(api.CecaError):
         api.ceca_set_option(99, 1)
+
+
+@pytest.mark.parametrize("port", [1, 2])
+def test_schedule_at_the_largest_agent_counts(api, port):
+    """n up to 2^31 - 1: every field of every round fits its int32 (2 n_r + 1 <= n in every round) and
+    equals the oracle's integers; the peer table is not requested at these sizes."""
+    import numpy as np
+    from paper_2306_00256_amd import binding as Bn
+    L = api.lib()
+    rng = np.random.default_rng(5)
+    ns = [2 ** 30 - 1, 2 ** 30, 2 ** 30 + 1, 2 ** 31 - 1, 2 ** 31 - 2] + [int(x) for x in rng.integers(2 ** 16, 2 ** 31 - 1, size=40)]
+    for n in ns:
+        if port == 1 and n % 2:
+            n -= 1
+        tau = S.num_rounds(n)
+        assert api.ceca_tau(n) == tau
+        dl, nr = S.delta_bits(n), S.window_sizes(n)
+        assert nr[tau] == n - 1
+        for r in range(tau):
+            rd = Bn.Round()
+            assert L.ceca_schedule(n, r, port, ctypes.byref(rd), None) == 0
+            assert (rd.n, rd.tau, rd.r, rd.delta, rd.n_r) == (n, tau, r, dl[r], nr[r])
+            assert rd.shift == (nr[r] + dl[r] if port == 2 else 2 * nr[r] + 1) and 0 < rd.shift <= n
+            a, b = S.weights(n, r)
+            assert a == S.Fraction(rd.a_num, rd.a_den) and b == S.Fraction(rd.b_num, rd.b_den)
+            assert rd.a == np.float32(float(a)) and rd.b_peer == np.float32(float(1 - b))
