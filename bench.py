@@ -228,14 +228,23 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
     tm.graph_ms_per_step = tg.event_ms / (reps * window)
     # the same iterations through dsgd_ceca_run (one call for a window of iterations; with many agents one
     # kernel per iteration): needs one step size and a batch table that covers the window
-    K = min(steps, nidx)
-    if not sp.lr_decay_every and K >= 2:
+    # (a decaying step size is constant over windows of lr_decay_every iterations: one call per window)
+    K = sp.lr_decay_every if sp.lr_decay_every else min(steps, nidx)
+    idx_run = idx[:K] if nidx >= K else idx[:1].repeat(K, 1, 1).contiguous()     # a full batch serves every iteration
+    if K >= 2:
         wsr = torch.empty(P.dsgd_ceca_run_workspace_bytes(n, d, loss0) + 256, dtype=torch.uint8, device="cuda")
         wsr = wsr[(-wsr.data_ptr()) % 256:]
-        P.dsgd_ceca_run(S, T, n, d, loss0, idx[:K], sp.lr, 0, K, port, workspace=wsr, ld=ld)
+        calls = max(1, steps // K)
+
+        def run_windows():
+            for w in range(calls):
+                P.dsgd_ceca_run(S, T, n, d, make_loss(w * K) if sp.noise_std else loss0, idx_run, WL.step_size(sp, w * K),
+                                (w * K) % tau, K, port, workspace=wsr, ld=ld)
+
+        run_windows()
         with Timer(torch) as tr:
-            P.dsgd_ceca_run(S, T, n, d, loss0, idx[:K], sp.lr, 0, K, port, workspace=wsr, ld=ld)
-        tm.run_ms_per_step = tr.event_ms / K
+            run_windows()
+        tm.run_ms_per_step = tr.event_ms / (calls * K)
         tm.run_iterations_per_call = K
     # one-pass gradient + combine when the sampled rows fit the register tile, else margins + half step + combine
     launches = 2 if d % 4 == 0 and ((n >= 128 and 1024 < d <= 16384) or (B <= 32 and d <= 1024) or (B <= 16 and d <= 4096)

@@ -162,9 +162,9 @@ int64_t dsgd_ceca_run_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* l
  * Iteration t (t = 0 .. iters-1) uses round (r0 + t) mod tau, the noise counter loss->k + t, the batch
  * rows batch_idx + t * n * B (device, iters * n * B int32) and the one step size lr; the result has the
  * same bits as `iters` calls of dsgd_ceca_step.  Where a workgroup can take an agent's whole rows
- * (16-byte aligned layouts, d <= 16384, and either n >= 128 with d > 1024 or a batch that fits a
- * register tile: B <= 32 at d <= 1024, 16 at 4096, 8 at 8192, 4 at 16384) each iteration after the
- * first is ONE kernel: the workgroup that takes agent i's gradient first finishes the iteration before
+ * (16-byte aligned layouts with d <= 16384 and either n >= 128 with d > 1024 or a batch that fits a
+ * register tile: B <= 32 at d <= 1024, 16 at 4096, 8 at 8192, 4 at 16384; any other layout with
+ * d <= 1024) each iteration after the first is ONE kernel: the workgroup that takes agent i's gradient first finishes the iteration before
  * for that agent (Eqs. (8), (9)) from its own and its peer's message; otherwise the call loops over
  * dsgd_ceca_step.
  * S_out may be S_in or disjoint from it; when disjoint, S_in is left unchanged.

@@ -499,7 +499,8 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   g.chunk_cols = ceca::kBlock * ceca::kChunkGroups * (gemv_vec ? 4 : 1);
   g.nchunks = (int32_t)((d + g.chunk_cols - 1) / g.chunk_cols);
   hipError_t e = hipSuccess;
-  const bool onepass = gemv_vec && g_opt_onepass.load() != 0 && ceca::launch_grad_onepass(g, st, &e);
+  const bool onepass = g_opt_onepass.load() != 0 &&
+                       (gemv_vec ? ceca::launch_grad_onepass(g, st, &e) : ceca::launch_grad_scalar(g, st, &e));
   if (onepass) {
     if (e != hipSuccess) return hip_fail(e, "one-pass gradient kernel launch");
   } else {
@@ -546,9 +547,13 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
   const int32_t tau = ceca::tau_of(n);
   char* w = reinterpret_cast<char*>(workspace);
   const int64_t nb = (int64_t)n * loss->B;
-  const bool vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
-  const bool fused = vec && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg != 1000 &&
-                     ceca::grad_fused_covers(n, d, loss->B);
+  // the gradient kernel of an iteration is chosen by the layout of the state it reads (S_in first, then
+  // S_out): the fused form needs the two to agree
+  const bool lay = ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
+  const bool vec = lay && aligned16(S_in);
+  const bool same_layout = vec == (lay && aligned16(S_out));
+  const bool fused = same_layout && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg != 1000 &&
+                     ceca::grad_fused_covers(n, d, loss->B, vec);
   ceca_loss_t one = *loss;
   if (!fused) {
     // one dsgd_ceca_step per iteration: the first from S_in to S_out, the rest in place on S_out
@@ -587,7 +592,8 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
     g.v = V[t & 1];
     if (t == 0) {
       g.zin = rd.exchange_y ? yin : xin;
-      if (!ceca::launch_grad_onepass(g, st, &e)) return fail(CECA_EINVAL, "internal: gradient kernel does not cover this shape");
+      if (!(vec ? ceca::launch_grad_onepass(g, st, &e) : ceca::launch_grad_scalar(g, st, &e)))
+        return fail(CECA_EINVAL, "internal: gradient kernel does not cover this shape");
     } else {
       // the state before iteration t-1's combine: S_in for t = 1, then S_out (updated row by row in place)
       g.px = (t == 1) ? xin : xout;
@@ -598,7 +604,7 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
       g.p_exch_y = prev.exchange_y;  g.p_read_y = prev.b_num != 0;
       g.pa = prev.a;  g.pap = prev.a_peer;  g.pb = prev.b;  g.pbp = prev.b_peer;
       g.new_exch_y = rd.exchange_y;
-      if (!ceca::launch_grad_fused(g, st, &e)) return fail(CECA_EINVAL, "internal: fused gradient kernel does not cover this shape");
+      if (!ceca::launch_grad_fused(g, vec, st, &e)) return fail(CECA_EINVAL, "internal: fused gradient kernel does not cover this shape");
     }
     if (e != hipSuccess) return hip_fail(e, "gradient kernel launch");
     prev = rd;
@@ -613,7 +619,7 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
   set_weights(prev, n, /*gossip_only=*/false, &a);
   a.aux = V[(iters - 1) & 1];
   a.ldaux = p.ldv;
-  return run_chain(a, ceca::MODE_FROMV, d, true, prev, port, st);
+  return run_chain(a, ceca::MODE_FROMV, d, aligned16(S_out) && ld % 4 == 0, prev, port, st);
 }
 
 int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, const ceca_loss_t* loss,

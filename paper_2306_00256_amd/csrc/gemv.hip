@@ -209,9 +209,11 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 // message and its peer's (Eqs. (8), (9), with the arithmetic of the combine kernel, operation for
 // operation) -- stores them, and takes the gradient at the new z.  One launch per iteration instead
 // of two, and the state rows (cache resident at these sizes) are touched once.
-template <int THREADS, int CH, int G, bool FUSE>
+// VEC = 1 is the same kernel on single columns, for layouts that are not 16-byte aligned.
+template <int VEC, int THREADS, int CH, int G, bool FUSE>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(G == 1 ? 8 : 4, 8)))
 void grad_chunked_kernel(const GemvArgs P) {
+  using V = typename VecOf<VEC>::T;
   constexpr int WAVES = THREADS / 64;
   __shared__ float red[2][WAVES][CH];     // alternating between chunks: one barrier per chunk
   static_assert(CH <= 16, "one wavefront sum per chunk");
@@ -219,18 +221,18 @@ void grad_chunked_kernel(const GemvArgs P) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int64_t col[G];
   bool on[G];
-  vf4 z[G], e[G];
+  V z[G], e[G];
 #pragma unroll
   for (int u = 0; u < G; ++u) {
-    const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * 4;
-    on[u] = c < P.d;
+    const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * VEC;
+    on[u] = c < P.d;                       // d is a multiple of VEC
     col[u] = on[u] ? c : 0;
   }
   const float* Abase = P.A + (int64_t)agent * P.N * P.lda;
   // lane j holds sample j of the whole batch (B <= 64; samples past B repeat the last)
   const int32_t myidx = min(max(P.batch_idx[(int64_t)agent * P.B + min(lane, P.B - 1)], 0), P.N - 1);
   const float tmine = P.t[(int64_t)agent * P.N + myidx];
-  vf4 a[CH][G];
+  V a[CH][G];
   // rows c0 .. c0 + CH - 1 of the batch into the register tile
   auto request_rows = [&](int c0) {
 #pragma unroll
@@ -238,7 +240,7 @@ void grad_chunked_kernel(const GemvArgs P) {
       const int32_t rj = __builtin_amdgcn_readlane(myidx, min(c0 + j, 63));
       const float* row = Abase + (int64_t)rj * P.lda;
 #pragma unroll
-      for (int u = 0; u < G; ++u) a[j][u] = ld_stream<vf4>(row + col[u]);
+      for (int u = 0; u < G; ++u) a[j][u] = ld_stream<V>(row + col[u]);
     }
   };
   // without the prologue the first rows are requested before z; with it they follow it: the prologue
@@ -246,7 +248,7 @@ void grad_chunked_kernel(const GemvArgs P) {
   if (!FUSE) request_rows(0);
 #pragma unroll
   for (int u = 0; u < G; ++u) {
-    vf4 zv;
+    V zv;
     if (FUSE) {
 #pragma clang fp contract(off)
       int p;
@@ -258,25 +260,25 @@ void grad_chunked_kernel(const GemvArgs P) {
         if (p >= P.n) p -= P.n;
       }
       const int64_t off = (int64_t)agent * P.ld + col[u];
-      const vf4 x = ld_plain<vf4>(P.px + off);
-      const vf4 y = P.p_read_y || P.p_exch_y ? ld_plain<vf4>(P.py + off) : vf4(0.0f);
-      const vf4 v = ld_plain<vf4>(P.pv + (int64_t)agent * P.ldv + col[u]);
-      const vf4 msg = ld_plain<vf4>(P.pv + (int64_t)p * P.ldv + col[u]);
-      const vf4 dz = v - (P.p_exch_y ? y : x);        // -lr e of the iteration before
-      const vf4 xs = P.p_exch_y ? x + dz : v;
-      const vf4 ys = P.p_exch_y ? v : y + dz;
-      const vf4 xn = combine(P.pa, xs, P.pap, msg);
-      const vf4 yn = P.p_read_y ? combine(P.pb, ys, P.pbp, msg) : P.pbp * msg;
+      const V x = ld_plain<V>(P.px + off);
+      const V y = P.p_read_y || P.p_exch_y ? ld_plain<V>(P.py + off) : V(0.0f);
+      const V v = ld_plain<V>(P.pv + (int64_t)agent * P.ldv + col[u]);
+      const V msg = ld_plain<V>(P.pv + (int64_t)p * P.ldv + col[u]);
+      const V dz = v - (P.p_exch_y ? y : x);        // -lr e of the iteration before
+      const V xs = P.p_exch_y ? x + dz : v;
+      const V ys = P.p_exch_y ? v : y + dz;
+      const V xn = combine(P.pa, xs, P.pap, msg);
+      const V yn = P.p_read_y ? combine(P.pb, ys, P.pbp, msg) : P.pbp * msg;
       if (on[u]) {
-        *reinterpret_cast<vf4*>(P.ox + off) = xn;
-        *reinterpret_cast<vf4*>(P.oy + off) = yn;
+        *reinterpret_cast<V*>(P.ox + off) = xn;
+        *reinterpret_cast<V*>(P.oy + off) = yn;
       }
       zv = P.new_exch_y ? yn : xn;
     } else {
-      zv = ld_plain<vf4>(P.zin + (int64_t)agent * P.ld + col[u]);
+      zv = ld_plain<V>(P.zin + (int64_t)agent * P.ld + col[u]);
     }
-    z[u] = on[u] ? zv : vf4(0.0f);
-    e[u] = vf4(0.0f);
+    z[u] = on[u] ? zv : V(0.0f);
+    e[u] = V(0.0f);
   }
   if (FUSE) request_rows(0);
   int turn = 0;
@@ -308,9 +310,9 @@ void grad_chunked_kernel(const GemvArgs P) {
   }
 #pragma unroll
   for (int u = 0; u < G; ++u) {
-    vf4 ee = e[u];
-    if (P.noise_std != 0.0f) ee += P.noise_std * noise_group<vf4>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
-    if (on[u]) *reinterpret_cast<vf4*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * ee;
+    V ee = e[u];
+    if (P.noise_std != 0.0f) ee += P.noise_std * noise_group<V>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
+    if (on[u]) *reinterpret_cast<V*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * ee;
   }
 }
 
@@ -324,10 +326,20 @@ template <bool FUSE>
 static hipError_t launch_chunked(const GemvArgs& g, hipStream_t st) {
   const int64_t d4 = g.d / 4;
   dim3 grid((unsigned)g.n);
-  if (d4 <= 256) grad_chunked_kernel<256, 8, 1, FUSE><<<grid, dim3(256), 0, st>>>(g);
-  else if (d4 <= 1024) grad_chunked_kernel<1024, 8, 1, FUSE><<<grid, dim3(1024), 0, st>>>(g);
-  else if (d4 <= 2048) grad_chunked_kernel<1024, 4, 2, FUSE><<<grid, dim3(1024), 0, st>>>(g);
-  else grad_chunked_kernel<1024, 2, 4, FUSE><<<grid, dim3(1024), 0, st>>>(g);
+  if (d4 <= 256) grad_chunked_kernel<4, 256, 8, 1, FUSE><<<grid, dim3(256), 0, st>>>(g);
+  else if (d4 <= 1024) grad_chunked_kernel<4, 1024, 8, 1, FUSE><<<grid, dim3(1024), 0, st>>>(g);
+  else if (d4 <= 2048) grad_chunked_kernel<4, 1024, 4, 2, FUSE><<<grid, dim3(1024), 0, st>>>(g);
+  else grad_chunked_kernel<4, 1024, 2, 4, FUSE><<<grid, dim3(1024), 0, st>>>(g);
+  return hipGetLastError();
+}
+
+// Layouts that are not 16-byte aligned: one column per thread, rows of at most 1024 columns, any batch.
+template <bool FUSE>
+static hipError_t launch_chunked_scalar(const GemvArgs& g, hipStream_t st) {
+  dim3 grid((unsigned)g.n);
+  if (g.d <= 64) grad_chunked_kernel<1, 64, 8, 1, FUSE><<<grid, dim3(64), 0, st>>>(g);
+  else if (g.d <= 256) grad_chunked_kernel<1, 256, 8, 1, FUSE><<<grid, dim3(256), 0, st>>>(g);
+  else grad_chunked_kernel<1, 1024, 8, 1, FUSE><<<grid, dim3(1024), 0, st>>>(g);
   return hipGetLastError();
 }
 
@@ -344,14 +356,23 @@ static bool chunked_by_default(int32_t n, int64_t d4) { return n >= 128 && d4 > 
 // Few agents with a batch too large for a register tile stay with the two-pass kernels: a handful of
 // workgroups walking megabytes of rows would be slower than three launches.
 // (d a multiple of 4, vector layouts: checked by the caller.)
-bool grad_fused_covers(int32_t n, int64_t d, int32_t B) {
+bool grad_fused_covers(int32_t n, int64_t d, int32_t B, bool vec4) {
+  if (!vec4) return n >= 2 && d <= 1024;          // the scalar chunked kernel is what a single step uses there
   const int64_t d4 = d / 4;
   return n >= 2 && d4 <= 4096 && (chunked_by_default(n, d4) || onepass_tile_exists(B, d4));
 }
 
-bool launch_grad_fused(const GemvArgs& g, hipStream_t st, hipError_t* err) {
-  if (!grad_fused_covers(g.n, g.d, g.B)) return false;
-  *err = launch_chunked<true>(g, st);
+bool launch_grad_fused(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t* err) {
+  if (!grad_fused_covers(g.n, g.d, g.B, vec4)) return false;
+  *err = vec4 ? launch_chunked<true>(g, st) : launch_chunked_scalar<true>(g, st);
+  return true;
+}
+
+// The gradient of a single step on a layout that is not 16-byte aligned; false when the rows are too long
+// for one workgroup (then the two-pass kernels run).
+bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err) {
+  if (g.d > 1024) return false;
+  *err = launch_chunked_scalar<false>(g, st);
   return true;
 }
 

@@ -150,8 +150,10 @@ hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipSt
 // one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
 // gradient kernel with the previous iteration's combine as its prologue; false when the shape is not covered
-bool launch_grad_fused(const GemvArgs& g, hipStream_t st, hipError_t* err);
-bool grad_fused_covers(int32_t n, int64_t d, int32_t B);
+bool launch_grad_fused(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t* err);
+bool grad_fused_covers(int32_t n, int64_t d, int32_t B, bool vec4);
+// single-step gradient for layouts that are not 16-byte aligned (rows up to 1024 columns); false otherwise
+bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err);
 extern int g_agents_per_wg;  // measurement knob for the one-pass kernel (0 = default)
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);

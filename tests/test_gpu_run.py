@@ -41,7 +41,9 @@ def _problem(torch, Bn, kind, n, N, d, B, iters, seed, noise=0.0):
 @pytest.mark.parametrize("kind", ["lsq", "logistic"])
 @pytest.mark.parametrize("n,port,d,B,ld", [(130, 2, 4096, 16, None), (128, 1, 2052, 5, 2056), (129, 2, 8192, 9, None),
                                            (130, 1, 16384, 3, None), (131, 2, 1100, 40, None),
-                                           (6, 1, 1000, 8, None), (5, 2, 4100, 7, None), (130, 2, 515, 4, None)])
+                                           (6, 1, 1000, 8, None), (5, 2, 4100, 7, None), (130, 2, 515, 4, None),
+                                           (258, 1, 10, 50, None), (12, 2, 63, 9, None), (9, 2, 255, 20, 258),
+                                           (6, 1, 1023, 12, None), (6, 2, 1027, 5, None), (4, 2, 1000, 40, None)])
 def test_run_equals_single_steps_and_oracle(env, kind, n, port, d, B, ld):
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
