@@ -247,8 +247,9 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
         tm.run_ms_per_step = tr.event_ms / (calls * K)
         tm.run_iterations_per_call = K
     # one-pass gradient + combine when the sampled rows fit the register tile, else margins + half step + combine
-    launches = 2 if d % 4 == 0 and ((n >= 128 and 1024 < d <= 16384) or (B <= 32 and d <= 1024) or (B <= 16 and d <= 4096)
-                                   or (B <= 8 and d <= 8192) or (B <= 4 and d <= 16384)) else 3
+    one_kernel_gradient = (d % 4 == 0 and ((n >= 128 and 1024 < d <= 16384) or (B <= 32 and d <= 1024) or (B <= 16 and d <= 4096)
+                                           or (B <= 8 and d <= 8192) or (B <= 4 and d <= 16384))) or (d % 4 != 0 and d <= 1024)
+    launches = 2 if one_kernel_gradient else 3
     return tm, launches, minibatch_bytes(B)
 
 
