@@ -111,6 +111,18 @@ def run_quad(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
+    # what the device gives the simplest kernel with this traffic mix (3 streaming reads + 2 streaming writes
+    # per element, same array sizes): out of place, and in place for the one-port workload
+    pa, pb = S[:n].reshape(-1), S[n:].reshape(-1)
+    po1, po2 = (pa, pb) if port == 1 else (T[:n].reshape(-1), T[n:].reshape(-1))
+    cnt = n * ld
+    for _ in range(3):
+        P.ceca_stream_probe(pa, pb, c.reshape(-1), po1, po2, cnt)
+    with Timer(torch) as tp:
+        for _ in range(10):
+            P.ceca_stream_probe(pa, pb, c.reshape(-1), po1, po2, cnt)
+    tm.probe = {"stream_probe_ms": tp.event_ms / 10, "stream_probe_GBs": 20.0 * cnt / (tp.event_ms / 10 * 1e-3) / 1e9}
+    S.zero_()
     # the same iterations fused: up to 50 per dsgd_ceca_steps call (same bits as the calls above), 20 bytes
     # per agent-parameter per call; bound by the noise generator's arithmetic, not by HBM
     K = min(steps, 50)
@@ -291,6 +303,7 @@ def measure(torch, P, Bn, name, steps, warmup):
     if hasattr(tm, "run_ms_per_step"):
         extra.update({"run_call_ms_per_step": tm.run_ms_per_step, "run_iterations_per_call": tm.run_iterations_per_call})
     extra.update(getattr(tm, "fused", {}))
+    extra.update(getattr(tm, "probe", {}))
     if hasattr(tm, "final"):
         extra["consensus_after_timed_steps"] = tm.final
     return {
@@ -442,6 +455,9 @@ def main():
             "bytes_per_agent_param": main_res["bytes_per_agent_param"],
             "kernel_ms": main_res["event_ms_per_step"] / main_res["kernels_per_step"],
             "gather_model_GBs": main_res["gather_model_GBs"],
+            # the simplest elementwise kernel with the same reads and writes per element, timed in this run
+            "stream_probe_GBs": main_res.get("stream_probe_GBs"),
+            "stream_probe_ms": main_res.get("stream_probe_ms"),
         },
     }
     details = {k: main_res[k] for k in ("graph_replay_ms_per_step", "run_call_ms_per_step", "run_iterations_per_call",

@@ -231,6 +231,13 @@ int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, i
                         const ceca_mix_t* specs, int32_t period, int32_t k0, int32_t rounds,
                         void* hip_stream);
 
+/* Measurement aid, not part of the method: an elementwise kernel with the traffic mix of the fused
+ * quadratic-centre step (three streaming reads a, b, c and two streaming writes o1, o2 per element;
+ * o1, o2 may be a, b), so that a benchmark can report, from the same run, the bandwidth the device gives
+ * the simplest kernel with that mix.  All pointers device, 16-byte aligned, count floats (a multiple of 4). */
+int32_t ceca_stream_probe(const float* a, const float* b, const float* c, float* o1, float* o2, int64_t count,
+                          void* hip_stream);
+
 /* Message for the calling thread's most recent error ("" if none); valid until its next failing call. */
 const char* ceca_last_error(void);
 /* hipError_t value behind the calling thread's most recent CECA_EHIP (0 if none). */

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     ceca_mix_rounds,
     ceca_schedule,
     ceca_set_option,
+    ceca_stream_probe,
     ceca_tau,
     ceca_topology_round,
     ceca_state_consensus,

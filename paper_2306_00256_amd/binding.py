@@ -16,7 +16,7 @@ MIX_MAX = 16
 
 EXPORTS = (
     "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "ceca_average", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps", "dsgd_ceca_run_workspace_bytes", "dsgd_ceca_run",
-    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_last_error", "ceca_last_hip_error",
+    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_stream_probe", "ceca_last_error", "ceca_last_hip_error",
     "ceca_set_option",
 )
 
@@ -99,6 +99,8 @@ def lib():
         L.ceca_mix_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Mix), C.c_int32,
                                       C.c_int32, C.c_int32, C.c_void_p]
         L.ceca_mix_rounds.restype = C.c_int32
+        L.ceca_stream_probe.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_void_p]
+        L.ceca_stream_probe.restype = C.c_int32
         L.ceca_last_error.restype = C.c_char_p
         L.ceca_last_hip_error.restype = C.c_int32
         L.ceca_set_option.argtypes = [C.c_int32, C.c_int32]
@@ -219,6 +221,11 @@ def ceca_state_consensus(S, n: int, d: int, out, workspace=None, ld: Optional[in
     ld = int(S.stride(0)) if ld is None else ld
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().ceca_state_consensus(_ptr(S), n, d, ld, _ptr(out), _ptr(workspace), wbytes, _stream(stream)))
+
+
+def ceca_stream_probe(a, b, c, o1, o2, count: int, stream=None) -> None:
+    """Measurement aid: elementwise kernel with three streaming reads and two streaming writes per element."""
+    _check(lib().ceca_stream_probe(_ptr(a), _ptr(b), _ptr(c), _ptr(o1), _ptr(o2), count, _stream(stream)))
 
 
 def ceca_set_option(option: int, value: int) -> None:

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libceca.so")
-SOURCES = ["api.cpp", "schedule.cpp", "chain.hip", "multi_round.hip", "mix.hip", "gemv.hip", "consensus.hip"]
+SOURCES = ["api.cpp", "schedule.cpp", "chain.hip", "multi_round.hip", "mix.hip", "gemv.hip", "consensus.hip", "probe.hip"]
 
 
 def hipcc_path() -> str:

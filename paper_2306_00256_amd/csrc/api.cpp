@@ -755,6 +755,17 @@ int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, i
   return CECA_OK;
 }
 
+int32_t ceca_stream_probe(const float* a, const float* b, const float* c, float* o1, float* o2, int64_t count,
+                          void* hip_stream) {
+  if (!a || !b || !c || !o1 || !o2) return fail(CECA_EINVAL, "null pointer");
+  if (count < 4 || count % 4 != 0) return fail(CECA_EINVAL, "count must be a positive multiple of 4");
+  if (!aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(o1) || !aligned16(o2))
+    return fail(CECA_EINVAL, "the probe takes 16-byte aligned arrays");
+  const hipError_t e = ceca::launch_stream_probe(a, b, c, o1, o2, count / 4, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "probe kernel launch");
+  return CECA_OK;
+}
+
 int64_t consensus_error_workspace_bytes(int32_t n, int64_t d) {
   if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
   return cons_plan(n, d).total;

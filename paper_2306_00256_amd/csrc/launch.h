@@ -161,6 +161,9 @@ hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);
+// measurement aid: o1, o2 <- elementwise functions of a, b, c (ngroups groups of 4 floats, 16-byte aligned)
+hipError_t launch_stream_probe(const float* a, const float* b, const float* c, float* o1, float* o2, int64_t ngroups,
+                               hipStream_t st);
 // out[10] = out[0] + out[5] (11 doubles on the device)
 hipError_t launch_phi(double* out, hipStream_t st);
 

@@ -174,3 +174,22 @@ def test_single_pass_and_two_pass_forms(env, n, d, pad, off):
             assert np.abs(xbar.cpu().numpy() - want["mean"]).max() <= 1e-6 * max(np.abs(want["mean"]).max(), 1.0), mode
     finally:
         P.ceca_set_option(Bn.OPT_CONS_SINGLE_PASS, 1)
+
+
+def test_stream_probe_values(env):
+    """The measurement aid computes what its header says (elementwise, in and out of place)."""
+    torch, P = env
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    a = torch.randn(4096 + 8, device="cuda", generator=g)[:4096]
+    b = torch.randn(4096, device="cuda", generator=g)
+    c = torch.randn(4096, device="cuda", generator=g)
+    o1, o2 = torch.empty_like(a), torch.empty_like(a)
+    P.ceca_stream_probe(a, b, c, o1, o2, 4096)
+    w1 = 0.5 * a + 0.5 * (b - 0.1 * (b - c))
+    w2 = 0.4 * b + 0.6 * (a - 0.1 * (a - c))
+    assert torch.allclose(o1, w1, rtol=1e-6, atol=1e-6) and torch.allclose(o2, w2, rtol=1e-6, atol=1e-6)
+    a2, b2 = a.clone(), b.clone()
+    P.ceca_stream_probe(a2, b2, c, a2, b2, 4096)
+    assert torch.equal(a2, o1) and torch.equal(b2, o2)
+    with pytest.raises(P.CecaError):
+        P.ceca_stream_probe(a, b, c, o1, o2, 4095)
