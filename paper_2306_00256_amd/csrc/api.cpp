@@ -285,6 +285,9 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
     case CECA_OPT_CONS_SINGLE_PASS:
       g_opt_cons_tile.store(value != 0);
       return CECA_OK;
+    case CECA_OPT_XCD_TILE_ORDER:
+      ceca::g_mix_xcd = value != 0;
+      return CECA_OK;
     case CECA_OPT_AGENTS_PER_WG:
       if (value < 0) return fail(CECA_EINVAL, "agents per workgroup must be >= 0");
       ceca::g_agents_per_wg = value;

@@ -59,6 +59,7 @@ struct MultiArgs {
   int64_t col0;
   int64_t ngroups;
   int32_t n, port, rounds;
+  int32_t xcd_tiles;        // > 0: workgroup b takes tile (b % 8) * xcd_tiles + b / 8 (set by the launcher)
   int32_t rows_per_thread;  // 1 to 16 rows of (x, y) in a thread's registers
   int32_t row_lanes;   // power of two, row_lanes * rows_per_thread >= n: threads of a workgroup that share a column group
   MultiRound round[kMultiMaxRounds];
@@ -139,6 +140,7 @@ struct MixArgs {
   int32_t n, rounds, period, k0;
   int32_t rows_per_thread;  // rows of x in a thread's registers: 1 to 32
   int32_t row_lanes;        // power of two, row_lanes * rows_per_thread >= n
+  int32_t xcd_tiles;        // > 0: workgroup b takes tile (b % 8) * xcd_tiles + b / 8 (set by the launcher)
   int32_t start[kMixMaxPeriod + 1];
   float w_self[kMixMaxPeriod];
   int32_t shift[kMixMaxPeers];
@@ -157,6 +159,7 @@ bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err);
 extern int g_agents_per_wg;  // measurement knob for the one-pass kernel (0 = default)
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
+extern int g_mix_xcd;   // measurement knob: 0 = plain tile order in the mixing kernel
 hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);

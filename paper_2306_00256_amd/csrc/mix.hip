@@ -27,7 +27,12 @@ __global__ __launch_bounds__(kBlock) void mix_rounds_kernel(const MixArgs M) {
   const int lanes = kBlock / M.row_lanes;
   const int cg = threadIdx.x % lanes;
   const int rg = threadIdx.x / lanes;
-  const int64_t g = (int64_t)blockIdx.x * lanes + cg;
+  // workgroups go round-robin over the 8 XCDs, each with its own L2: when a row of the tile is
+  // narrower than a 128-byte line, neighbouring tiles should meet in one L2, so every XCD takes a
+  // contiguous run of tiles (xcd_tiles = tiles per XCD, 0 = plain order)
+  int64_t tile = blockIdx.x;
+  if (M.xcd_tiles > 0) tile = (int64_t)(blockIdx.x & 7) * M.xcd_tiles + (blockIdx.x >> 3);
+  const int64_t g = tile * lanes + cg;
   const bool on = g < M.ngroups;
   const int64_t col = M.col0 + (on ? g : 0) * VEC; // lanes past the last column shadow column group 0
 
@@ -88,16 +93,24 @@ __global__ __launch_bounds__(kBlock) void mix_rounds_kernel(const MixArgs M) {
   }
 }
 
+int g_mix_xcd = 1;
+
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st) {
   if (m.ngroups <= 0) return hipSuccess;
   const int lanes = kBlock / m.row_lanes;
-  const int64_t blocks = (m.ngroups + lanes - 1) / lanes;
+  int64_t blocks = (m.ngroups + lanes - 1) / lanes;
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
+  MixArgs mm = m;
+  mm.xcd_tiles = 0;
+  if (lanes * (vec4 ? 16 : 4) < 128 && blocks >= 1024 && g_mix_xcd) {
+    mm.xcd_tiles = (int32_t)((blocks + 7) / 8);
+    blocks = (int64_t)mm.xcd_tiles * 8;            // tiles past the last one find no columns and leave
+  }
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
   dim3 grid((unsigned)blocks), block(kBlock);
   // 16-byte groups: exactly the rows n needs (1..32 per thread); the few scalar tail columns round up
-#define CECA_MIX4(RT) case RT: mix_rounds_kernel<4, RT><<<grid, block, lds, st>>>(m); break
-#define CECA_MIX1(RT) mix_rounds_kernel<1, RT><<<grid, block, lds, st>>>(m)
+#define CECA_MIX4(RT) case RT: mix_rounds_kernel<4, RT><<<grid, block, lds, st>>>(mm); break
+#define CECA_MIX1(RT) mix_rounds_kernel<1, RT><<<grid, block, lds, st>>>(mm)
   if (m.rows_per_thread < 1 || m.rows_per_thread > 32) return hipErrorInvalidValue;
   if (vec4) {
     switch (m.rows_per_thread) {

@@ -14,6 +14,16 @@ namespace ceca {
 // independent instances of the recursion (Sec. 3.1), and every round uses the same combine() as the
 // single-round kernel, so the result has the same bits as `rounds` separate calls.
 // ---------------------------------------------------------------------------------------------
+// Tiles per XCD for the XCD-contiguous workgroup order (rows of the tile narrower than a 128-byte line
+// and enough tiles to matter), 0 for the plain order; rounds *blocks up to 8 runs of that many tiles
+// (workgroups past the last tile find no columns and leave).
+static int32_t xcd_run(int row_bytes, int64_t* blocks) {
+  if (row_bytes >= 128 || *blocks < 1024 || !g_mix_xcd) return 0;   // small launches measured better in plain order
+  const int64_t per = (*blocks + 7) / 8;
+  *blocks = per * 8;
+  return (int32_t)per;
+}
+
 template <int VEC, int RT>
 __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) {
   using V = typename VecOf<VEC>::T;
@@ -21,7 +31,11 @@ __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) 
   const int lanes = kBlock / M.row_lanes;          // column groups per row handled by this workgroup
   const int cg = threadIdx.x % lanes;              // my column group inside the tile
   const int rg = threadIdx.x / lanes;              // my first row; I own rows rg, rg + row_lanes, ...
-  const int64_t g = (int64_t)blockIdx.x * lanes + cg;
+  // narrow tiles: every XCD (workgroups go round-robin over 8 of them, each with its own L2) takes a
+  // contiguous run of tiles, so that the two halves of a 128-byte line meet in one L2
+  int64_t tile = blockIdx.x;
+  if (M.xcd_tiles > 0) tile = (int64_t)(blockIdx.x & 7) * M.xcd_tiles + (blockIdx.x >> 3);
+  const int64_t g = tile * lanes + cg;
   const bool on = g < M.ngroups;
   const int64_t col = M.col0 + (on ? g : 0) * VEC; // lanes past the last column shadow column group 0
 
@@ -115,7 +129,11 @@ __global__ __launch_bounds__(kBlock) void multi_step_kernel(const StepsArgs S) {
   const int lanes = kBlock / M.row_lanes;
   const int cg = threadIdx.x % lanes;
   const int rg = threadIdx.x / lanes;
-  const int64_t g = (int64_t)blockIdx.x * lanes + cg;
+  // narrow tiles: every XCD (workgroups go round-robin over 8 of them, each with its own L2) takes a
+  // contiguous run of tiles, so that the two halves of a 128-byte line meet in one L2
+  int64_t tile = blockIdx.x;
+  if (M.xcd_tiles > 0) tile = (int64_t)(blockIdx.x & 7) * M.xcd_tiles + (blockIdx.x >> 3);
+  const int64_t g = tile * lanes + cg;
   const bool on = g < M.ngroups;
   const int64_t col = M.col0 + (on ? g : 0) * VEC; // lanes past the last column shadow column group 0
 
@@ -198,12 +216,14 @@ hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st) {
   const MultiArgs& m = s.m;
   if (m.ngroups <= 0) return hipSuccess;
   const int lanes = kBlock / m.row_lanes;
-  const int64_t blocks = (m.ngroups + lanes - 1) / lanes;
+  int64_t blocks = (m.ngroups + lanes - 1) / lanes;
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
+  StepsArgs ss = s;
+  ss.m.xcd_tiles = xcd_run(lanes * (vec4 ? 16 : 4), &blocks);
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
   dim3 grid((unsigned)blocks), block(kBlock);
-#define CECA_STEPS4(RT) case RT: multi_step_kernel<4, RT><<<grid, block, lds, st>>>(s); break
-#define CECA_STEPS1(RT) multi_step_kernel<1, RT><<<grid, block, lds, st>>>(s)
+#define CECA_STEPS4(RT) case RT: multi_step_kernel<4, RT><<<grid, block, lds, st>>>(ss); break
+#define CECA_STEPS1(RT) multi_step_kernel<1, RT><<<grid, block, lds, st>>>(ss)
   if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows) return hipErrorInvalidValue;
   if (vec4) {
     switch (m.rows_per_thread) {
@@ -222,13 +242,15 @@ hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st) {
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st) {
   if (m.ngroups <= 0) return hipSuccess;
   const int lanes = kBlock / m.row_lanes;
-  const int64_t blocks = (m.ngroups + lanes - 1) / lanes;
+  int64_t blocks = (m.ngroups + lanes - 1) / lanes;
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
+  MultiArgs mm = m;
+  mm.xcd_tiles = xcd_run(lanes * (vec4 ? 16 : 4), &blocks);
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
   dim3 grid((unsigned)blocks), block(kBlock);
   // 16-byte groups: exactly the rows n needs (1..16 per thread); the few scalar tail columns round up
-#define CECA_MULTI4(RT) case RT: multi_round_kernel<4, RT><<<grid, block, lds, st>>>(m); break
-#define CECA_MULTI1(RT) multi_round_kernel<1, RT><<<grid, block, lds, st>>>(m)
+#define CECA_MULTI4(RT) case RT: multi_round_kernel<4, RT><<<grid, block, lds, st>>>(mm); break
+#define CECA_MULTI1(RT) multi_round_kernel<1, RT><<<grid, block, lds, st>>>(mm)
   if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows) return hipErrorInvalidValue;
   if (vec4) {
     switch (m.rows_per_thread) {

@@ -125,3 +125,31 @@ def test_minibatch_losses_refuse_more_than_65535_agents(env):
     with pytest.raises(P.CecaError) as e:
         P.dsgd_ceca_step(S, S, n, d, loss, idx, 0.1, 0, 2, workspace=ws)
     assert e.value.code == Bn.CECA_EINVAL
+
+
+def test_xcd_tile_order_does_not_change_results(env):
+    """Many narrow tiles (more than 1024 agents-wide tiles of 64-byte rows): the XCD-contiguous workgroup
+    order and the plain order give the same bits in the fused rounds, fused iterations and mixing kernels."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, port = 1026, 16 * 1500 + 4, 1
+    x0 = WL.initial_state(n, d, seed=3)
+    c = torch.from_numpy(WL.quad_centers(n, d, 4)).cuda()
+    ring = [P.ceca_topology_round(Bn.TOPO_RING, n)]
+    outs = []
+    try:
+        for order in (1, 0):
+            P.ceca_set_option(Bn.OPT_XCD_TILE_ORDER, order)
+            S = make_state(torch, x0)
+            P.ceca_gossip_rounds(S, S, n, d, 5, port)
+            P.dsgd_ceca_steps(S, S, n, d, Bn.make_quad_center_loss(c, 0.01, 1, 0), 0.1, 5 % OS.num_rounds(n), 3, port)
+            P.ceca_mix_rounds(S[:n], S[:n], n, d, ring, 2)
+            outs.append(S.clone())
+    finally:
+        P.ceca_set_option(Bn.OPT_XCD_TILE_ORDER, 1)
+    assert torch.equal(outs[0], outs[1])
+    x, y = OC.run(x0, port, 0.0, None, 5, store32=True)
+    ref = make_state(torch, x0)
+    P.ceca_gossip_rounds(ref, ref, n, d, 5, port)
+    gx, gy = split_state(ref, n, d)
+    assert max(rel_err(gx, x)) <= 1e-5 and max(rel_err(gy, y)) <= 1e-5
