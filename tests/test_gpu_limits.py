@@ -153,3 +153,32 @@ def test_xcd_tile_order_does_not_change_results(env):
     P.ceca_gossip_rounds(ref, ref, n, d, 5, port)
     gx, gy = split_state(ref, n, d)
     assert max(rel_err(gx, x)) <= 1e-5 and max(rel_err(gy, y)) <= 1e-5
+
+
+def test_more_rounds_than_one_kernel_takes(env):
+    """ceca_gossip_rounds beyond 64 rounds (one launch per round then) and ceca_mix_rounds with hundreds of
+    rounds in one kernel: same bits as the calls split into shorter runs, and the oracle's values."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, port = 12, 300, 2
+    tau = OS.num_rounds(n)
+    x0 = WL.initial_state(n, d, seed=8)
+    A = make_state(torch, x0)
+    P.ceca_gossip_rounds(A, A, n, d, 70, port)
+    B = make_state(torch, x0)
+    P.ceca_gossip_rounds(B, B, n, d, 64, port)
+    for t in range(64, 70):
+        P.ceca_gossip_round(B, B, n, d, t % tau, port)
+    assert torch.equal(A, B)
+    x, y = OC.run(x0, port, 0.0, None, 70, store32=True)
+    gx, gy = split_state(A, n, d)
+    assert max(rel_err(gx, x)) <= 1e-5 and max(rel_err(gy, y)) <= 1e-5
+    ring = [P.ceca_topology_round(Bn.TOPO_RING, n)]
+    X = torch.from_numpy(x0).cuda()
+    Y = X.clone()
+    P.ceca_mix_rounds(X, X, n, d, ring, 300)
+    for _ in range(3):
+        P.ceca_mix_rounds(Y, Y, n, d, ring, 100)
+    assert torch.equal(X, Y)
+    want = OT.run(x0, [OT.ring(n)], 300)
+    assert max(rel_err(X.cpu().numpy(), want)) <= 1e-4
