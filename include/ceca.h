@@ -114,8 +114,9 @@ int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d,
  * y_i (Lemma 4.2) -- the global averaging that Theorem 4.3 asks for before the first iteration.
  * The result has the same bits as `rounds` calls of ceca_gossip_round.  Because the sequence starts
  * at round 0, the y rows of S_in are never read.  S_out may be S_in or disjoint from it.
- * Up to 4096 agents and 64 rounds run as one kernel that moves 12 bytes per agent-parameter; larger
- * cases fall back to one launch per round (in place on S_out after the first). */
+ * Up to 4096 agents run through kernels that move 12 bytes per agent-parameter for as many whole cycles
+ * as fit in 64 rounds each (longer runs take several such kernels, in place on S_out after the first);
+ * more agents fall back to one launch per round (in place on S_out after the first). */
 int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                            int32_t rounds, int32_t port, void* hip_stream);
 
@@ -149,8 +150,8 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
  * CECA_LOSS_QUAD_CENTER is taken (CECA_EINVAL otherwise): its gradient is elementwise, so columns stay
  * independent across whole iterations and a workgroup can carry a column tile of x, y and c through all
  * of them in registers -- 20 bytes per agent-parameter for the whole call instead of per iteration.
- * S_out may be S_in or disjoint from it.  Up to 4096 agents and 64 iterations run as one kernel; larger
- * cases fall back to one dsgd_ceca_step per iteration (in place on S_out after the first). */
+ * S_out may be S_in or disjoint from it.  Up to 4096 agents run as one kernel per 64 iterations (in place
+ * on S_out after the first); more agents fall back to one dsgd_ceca_step per iteration (likewise). */
 int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                         const ceca_loss_t* loss, float lr, int32_t r0, int32_t steps, int32_t port,
                         void* hip_stream);

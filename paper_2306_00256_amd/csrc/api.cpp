@@ -1,6 +1,7 @@
 // C ABI of the DSGD-CECA hot path: argument checking, round schedule, launch shapes.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstdarg>
 #include <cstdint>
@@ -286,11 +287,11 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       g_opt_cons_tile.store(value != 0);
       return CECA_OK;
     case CECA_OPT_XCD_TILE_ORDER:
-      ceca::g_mix_xcd = value != 0;
+      ceca::g_mix_xcd.store(value != 0);
       return CECA_OK;
     case CECA_OPT_AGENTS_PER_WG:
       if (value < 0) return fail(CECA_EINVAL, "agents per workgroup must be >= 0");
-      ceca::g_agents_per_wg = value;
+      ceca::g_agents_per_wg.store(value);
       return CECA_OK;
     case CECA_OPT_BAND:
       if (value < 0) return fail(CECA_EINVAL, "band width must be >= 0");
@@ -350,7 +351,7 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
   int32_t row_lanes = 1;
   while (row_lanes * cap < n) row_lanes *= 2;
   const int32_t rpt = (n + row_lanes - 1) / row_lanes;   // exactly the rows n needs with that many row lanes
-  if (n == 1 || rounds > ceca::kMultiMaxRounds || row_lanes > ceca::kBlock) {
+  if (n == 1 || row_lanes > ceca::kBlock) {
     // too many agents for one workgroup's registers (or nothing to fuse): one launch per round, the
     // first from S_in to S_out, the rest in place on S_out (whole cycles / pairs read before they write)
     for (int32_t t = 0; t < rounds; ++t) {
@@ -359,30 +360,37 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
     }
     return CECA_OK;
   }
-  ceca::MultiArgs m{};
-  m.xin = S_in;
-  m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
-  m.ld = ld;
-  m.n = n;  m.port = port;  m.rounds = rounds;
-  m.row_lanes = row_lanes;
-  m.rows_per_thread = rpt;
-  for (int32_t t = 0; t < rounds; ++t) {
-    ceca::fill_round(n, t % tau, port, &rd);
-    ceca::MultiRound& R = m.round[t];
-    R.shift = rd.shift;  R.exch_y = rd.exchange_y;  R.read_y = rd.b_num != 0;
-    R.a = rd.a;  R.ap = rd.a_peer;  R.b = rd.b;  R.bp = rd.b_peer;
-  }
   const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
   const int64_t d4 = can_vec ? d / 4 : 0;
-  if (d4 > 0) {
-    m.col0 = 0;  m.ngroups = d4;
-    const hipError_t e = ceca::launch_multi_round(m, true, st);
-    if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch");
-  }
-  if (d - 4 * d4 > 0) {
-    m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
-    const hipError_t e = ceca::launch_multi_round(m, false, st);
-    if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch (scalar columns)");
+  // one kernel takes up to kMultiMaxRounds rounds; longer runs go in pieces of whole cycles (the
+  // kernel starts at round 0, which reads no y), the first from S_in to S_out and the rest in place
+  // on S_out (a workgroup holds its whole tile before it writes)
+  const int32_t piece = ceca::kMultiMaxRounds / tau * tau;     // tau <= 12 for the agent counts that reach here
+  for (int32_t t0 = 0; t0 < rounds; t0 += piece) {
+    const int32_t cnt = std::min(rounds - t0, piece);
+    ceca::MultiArgs m{};
+    m.xin = t0 == 0 ? S_in : S_out;
+    m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
+    m.ld = ld;
+    m.n = n;  m.port = port;  m.rounds = cnt;
+    m.row_lanes = row_lanes;
+    m.rows_per_thread = rpt;
+    for (int32_t t = 0; t < cnt; ++t) {
+      ceca::fill_round(n, (t0 + t) % tau, port, &rd);
+      ceca::MultiRound& R = m.round[t];
+      R.shift = rd.shift;  R.exch_y = rd.exchange_y;  R.read_y = rd.b_num != 0;
+      R.a = rd.a;  R.ap = rd.a_peer;  R.b = rd.b;  R.bp = rd.b_peer;
+    }
+    if (d4 > 0) {
+      m.col0 = 0;  m.ngroups = d4;
+      const hipError_t e = ceca::launch_multi_round(m, true, st);
+      if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch");
+    }
+    if (d - 4 * d4 > 0) {
+      m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+      const hipError_t e = ceca::launch_multi_round(m, false, st);
+      if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch (scalar columns)");
+    }
   }
   return CECA_OK;
 }
@@ -555,7 +563,7 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
   const bool lay = ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
   const bool vec = lay && aligned16(S_in);
   const bool same_layout = vec == (lay && aligned16(S_out));
-  const bool fused = same_layout && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg != 1000 &&
+  const bool fused = same_layout && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg.load() != 1000 &&
                      ceca::grad_fused_covers(n, d, loss->B, vec);
   ceca_loss_t one = *loss;
   if (!fused) {
@@ -648,7 +656,7 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
   while (row_lanes * cap < n) row_lanes *= 2;
   if (row_lanes > ceca::kBlock) { row_lanes = ceca::kBlock; }
   const int32_t rpt = (n + row_lanes - 1) / row_lanes;
-  if (n == 1 || steps > ceca::kMultiMaxRounds || rpt > ceca::kMultiRows) {
+  if (n == 1 || rpt > ceca::kMultiRows) {
     ceca_loss_t one = *loss;
     for (int32_t t = 0; t < steps; ++t) {
       one.k = loss->k + (uint32_t)t;
@@ -658,34 +666,40 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
     }
     return CECA_OK;
   }
-  ceca::StepsArgs a{};
-  ceca::MultiArgs& m = a.m;
-  m.xin = S_in;
-  m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
-  m.ld = ld;
-  m.n = n;  m.port = port;  m.rounds = steps;
-  m.row_lanes = row_lanes;
-  m.rows_per_thread = rpt;
-  for (int32_t t = 0; t < steps; ++t) {
-    ceca::fill_round(n, (r0 + t) % tau, port, &rd);
-    ceca::MultiRound& R = m.round[t];
-    R.shift = rd.shift;  R.exch_y = rd.exchange_y;  R.read_y = rd.b_num != 0;
-    R.a = rd.a;  R.ap = rd.a_peer;  R.b = rd.b;  R.bp = rd.b_peer;
-  }
-  a.yin = S_in + (int64_t)n * ld;
-  a.c = loss->c;  a.ldc = loss->ldc;
-  a.lr = lr;  a.noise_std = loss->noise_std;  a.seed = loss->seed;  a.k0 = loss->k;
   const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->c) && loss->ldc % 4 == 0;
   const int64_t d4 = can_vec ? d / 4 : 0;
-  if (d4 > 0) {
-    m.col0 = 0;  m.ngroups = d4;
-    const hipError_t e = ceca::launch_multi_step(a, true, st);
-    if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch");
-  }
-  if (d - 4 * d4 > 0) {
-    m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
-    const hipError_t e = ceca::launch_multi_step(a, false, st);
-    if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch (scalar columns)");
+  // one kernel takes up to kMultiMaxRounds iterations; longer runs go in pieces, the first from S_in
+  // to S_out and the rest in place on S_out (a workgroup holds its whole tile before it writes)
+  for (int32_t t0 = 0; t0 < steps; t0 += ceca::kMultiMaxRounds) {
+    const int32_t cnt = std::min(steps - t0, ceca::kMultiMaxRounds);
+    const float* src = t0 == 0 ? S_in : S_out;
+    ceca::StepsArgs a{};
+    ceca::MultiArgs& m = a.m;
+    m.xin = src;
+    m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
+    m.ld = ld;
+    m.n = n;  m.port = port;  m.rounds = cnt;
+    m.row_lanes = row_lanes;
+    m.rows_per_thread = rpt;
+    for (int32_t t = 0; t < cnt; ++t) {
+      ceca::fill_round(n, (r0 + t0 + t) % tau, port, &rd);
+      ceca::MultiRound& R = m.round[t];
+      R.shift = rd.shift;  R.exch_y = rd.exchange_y;  R.read_y = rd.b_num != 0;
+      R.a = rd.a;  R.ap = rd.a_peer;  R.b = rd.b;  R.bp = rd.b_peer;
+    }
+    a.yin = src + (int64_t)n * ld;
+    a.c = loss->c;  a.ldc = loss->ldc;
+    a.lr = lr;  a.noise_std = loss->noise_std;  a.seed = loss->seed;  a.k0 = loss->k + (uint32_t)t0;
+    if (d4 > 0) {
+      m.col0 = 0;  m.ngroups = d4;
+      const hipError_t e = ceca::launch_multi_step(a, true, st);
+      if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch");
+    }
+    if (d - 4 * d4 > 0) {
+      m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+      const hipError_t e = ceca::launch_multi_step(a, false, st);
+      if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch (scalar columns)");
+    }
   }
   return CECA_OK;
 }

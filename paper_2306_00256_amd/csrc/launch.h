@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 
 namespace ceca {
@@ -156,10 +157,10 @@ bool launch_grad_fused(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t*
 bool grad_fused_covers(int32_t n, int64_t d, int32_t B, bool vec4);
 // single-step gradient for layouts that are not 16-byte aligned (rows up to 1024 columns); false otherwise
 bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err);
-extern int g_agents_per_wg;  // measurement knob for the one-pass kernel (0 = default)
+extern std::atomic<int> g_agents_per_wg;  // measurement knob for the one-pass kernel (0 = default)
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
-extern int g_mix_xcd;   // measurement knob: 0 = plain tile order in the mixing kernel
+extern std::atomic<int> g_mix_xcd;   // measurement knob: 0 = plain tile order in the mixing kernel
 hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kBlock) void mix_rounds_kernel(const MixArgs M) {
   }
 }
 
-int g_mix_xcd = 1;
+std::atomic<int> g_mix_xcd{1};
 
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st) {
   if (m.ngroups <= 0) return hipSuccess;

@@ -156,10 +156,28 @@ def test_xcd_tile_order_does_not_change_results(env):
 
 
 def test_more_rounds_than_one_kernel_takes(env):
-    """ceca_gossip_rounds beyond 64 rounds (one launch per round then) and ceca_mix_rounds with hundreds of
-    rounds in one kernel: same bits as the calls split into shorter runs, and the oracle's values."""
+    """ceca_gossip_rounds beyond 64 rounds (several kernels of whole cycles, in place after the first) and
+    ceca_mix_rounds with hundreds of rounds in one kernel: same bits as the calls split into shorter runs,
+    and the oracle's values."""
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
+    # tau = 5 does not divide 64 (pieces of 60 rounds), out of place, ragged columns, both ports
+    for n2, port2 in [(20, 2), (18, 1)]:
+        d2, rounds = 1027, 131
+        tau2 = OS.num_rounds(n2)
+        z0 = WL.initial_state(n2, d2, seed=9)
+        src = make_state(torch, z0)
+        keep = src.clone()
+        dst = torch.full_like(src, float("nan"))
+        P.ceca_gossip_rounds(src, dst, n2, d2, rounds, port2)
+        assert torch.equal(src, keep)
+        ref = make_state(torch, z0)
+        for t in range(rounds):
+            P.ceca_gossip_round(ref, ref, n2, d2, t % tau2, port2)
+        assert torch.equal(dst, ref), (n2, port2)
+        x, y = OC.run(z0, port2, 0.0, None, rounds, store32=True)
+        gx, gy = split_state(dst, n2, d2)
+        assert max(rel_err(gx, x)) <= 1e-5 and max(rel_err(gy, y)) <= 1e-5
     n, d, port = 12, 300, 2
     tau = OS.num_rounds(n)
     x0 = WL.initial_state(n, d, seed=8)

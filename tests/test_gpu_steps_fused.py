@@ -79,8 +79,8 @@ def test_first_round_zero_does_not_read_y(env):
 
 
 def test_tile_shapes_and_long_runs(env):
-    """Rows per thread do not change the bits; more iterations than one kernel takes fall back to
-    single steps with the same result."""
+    """Rows per thread do not change the bits; more iterations than one kernel takes run as several
+    kernels with the same result as shorter calls and as single steps, in place and out of place."""
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
     n, d, port, seed = 30, 1540, 1, 2
@@ -97,11 +97,21 @@ def test_tile_shapes_and_long_runs(env):
         P.ceca_set_option(Bn.OPT_ROWS, 0)
     assert all(torch.equal(outs[0], o) for o in outs[1:])
     A = make_state(torch, x0)
-    P.dsgd_ceca_steps(A, A, n, d, Bn.make_quad_center_loss(c, 0.01, seed, 0), 0.1, 0, 70, port)     # > 64: falls back
+    P.dsgd_ceca_steps(A, A, n, d, Bn.make_quad_center_loss(c, 0.01, seed, 0), 0.1, 0, 70, port)     # > 64: two kernels
     Bs = make_state(torch, x0)
     P.dsgd_ceca_steps(Bs, Bs, n, d, Bn.make_quad_center_loss(c, 0.01, seed, 0), 0.1, 0, 35, port)
     P.dsgd_ceca_steps(Bs, Bs, n, d, Bn.make_quad_center_loss(c, 0.01, seed, 35), 0.1, 35 % 5, 35, port)
     assert torch.equal(A, Bs)
+    # out of place from round 2 of the cycle, 150 iterations (three kernels), against single steps
+    src = make_state(torch, x0)
+    keep = src.clone()
+    dst = torch.full_like(src, float("nan"))
+    P.dsgd_ceca_steps(src, dst, n, d, Bn.make_quad_center_loss(c, 0.01, seed, 7), 0.1, 2, 150, port)
+    assert torch.equal(src, keep)
+    R = make_state(torch, x0)
+    for t in range(150):
+        P.dsgd_ceca_step(R, R, n, d, Bn.make_quad_center_loss(c, 0.01, seed, 7 + t), None, 0.1, (2 + t) % 5, port)
+    assert torch.equal(dst, R)
 
 
 def test_rejects_other_losses(env):
