@@ -259,9 +259,12 @@ int32_t ceca_last_hip_error(void);
  *                     hold a column tile of every agent; 0: always the two-pass kernels
  *   CECA_OPT_XCD_TILE_ORDER  1 (default): register-tile kernels whose tile rows are narrower than 128 bytes give
  *                     each of the 8 XCDs a contiguous run of tiles; 0: plain order
+ *   CECA_OPT_TILE_THREADS  threads per workgroup of the fused gossip-rounds kernel: 256, 512 or 1024
+ *                     (0 = library default); more threads make the rows of a tile wider
  * Returns CECA_EINVAL for an unknown option or value. */
 enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5,
-       CECA_OPT_AGENTS_PER_WG = 7, CECA_OPT_CONS_SINGLE_PASS = 8, CECA_OPT_XCD_TILE_ORDER = 9 };
+       CECA_OPT_AGENTS_PER_WG = 7, CECA_OPT_CONS_SINGLE_PASS = 8, CECA_OPT_XCD_TILE_ORDER = 9,
+       CECA_OPT_TILE_THREADS = 10 };
 int32_t ceca_set_option(int32_t option, int32_t value);
 
 #ifdef __cplusplus

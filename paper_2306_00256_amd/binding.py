@@ -10,7 +10,7 @@ _LIB_PATH = os.path.join(_HERE, "libceca.so")
 
 CECA_OK, CECA_EINVAL, CECA_EODD1P, CECA_EWORKSPACE, CECA_EHIP = 0, -1, -2, -3, -4
 LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER = 0, 1, 2
-OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS, OPT_AGENTS_PER_WG, OPT_CONS_SINGLE_PASS, OPT_XCD_TILE_ORDER = 1, 2, 3, 4, 5, 7, 8, 9
+OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS, OPT_AGENTS_PER_WG, OPT_CONS_SINGLE_PASS, OPT_XCD_TILE_ORDER, OPT_TILE_THREADS = 1, 2, 3, 4, 5, 7, 8, 9, 10
 TOPO_RING, TOPO_STATIC_EXP, TOPO_ONE_PEER_EXP = 0, 1, 2
 MIX_MAX = 16
 

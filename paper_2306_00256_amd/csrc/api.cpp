@@ -22,6 +22,7 @@ std::atomic<int32_t> g_opt_band{0};
 std::atomic<int32_t> g_opt_wgs{0};
 std::atomic<int32_t> g_opt_onepass{1};
 std::atomic<int32_t> g_opt_cons_tile{1};
+std::atomic<int32_t> g_opt_tile_threads{0};
 
 int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -258,6 +259,36 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
   return p;
 }
 
+
+// Tile of the fused gossip-rounds kernel: threads per workgroup, threads that share a column group
+// (a power of two) and rows of (x, y) per thread (the least that covers n); ok = false when no tile
+// holds n agents.
+struct TileShape {
+  int32_t threads, row_lanes, rows_per_thread;
+  bool ok;
+};
+
+TileShape rounds_tile(int32_t n, bool vec4) {
+  TileShape t{};
+  int32_t cap = g_opt_rows.load();
+  const bool cap_given = cap >= 4 && cap <= ceca::kMultiRows;
+  t.threads = vec4 ? g_opt_tile_threads.load() : ceca::kBlock;
+  // Measured on MI355X (n = 31 ... 4096): 512-thread workgroups with up to 9 rows per thread (128
+  // registers: two workgroups per compute unit) make the rows of the tile two to four times wider than
+  // 256-thread ones and run 1.1x (n = 31) to 3x (n = 1026) faster; beyond 9 x 128 agents only a
+  // 1024-thread workgroup keeps the rows at 64 bytes (4.6x at n = 2050).
+  if (t.threads == 0) t.threads = n > 9 * 128 ? 1024 : 512;
+  // 256-thread tiles: 8 rows leave room for twice as many workgroups per CU as 16 (1.5x faster at
+  // n = 100) as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
+  if (!cap_given) cap = t.threads == ceca::kBlock ? (n <= 256 ? 8 : ceca::kMultiRows) : 9;
+  t.row_lanes = 1;
+  while ((int64_t)t.row_lanes * cap < n) t.row_lanes *= 2;
+  t.rows_per_thread = (n + t.row_lanes - 1) / t.row_lanes;
+  const int64_t lds = t.row_lanes <= t.threads ? (int64_t)n * (t.threads / t.row_lanes) * (vec4 ? 16 : 4) : 0;
+  t.ok = t.row_lanes <= t.threads && lds <= (int64_t)ceca::kMultiMaxLds;
+  return t;
+}
+
 }  // namespace
 
 extern "C" {
@@ -285,6 +316,11 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       return CECA_OK;
     case CECA_OPT_CONS_SINGLE_PASS:
       g_opt_cons_tile.store(value != 0);
+      return CECA_OK;
+    case CECA_OPT_TILE_THREADS:
+      if (value != 0 && value != 256 && value != 512 && value != 1024)
+        return fail(CECA_EINVAL, "tile threads must be 0, 256, 512 or 1024");
+      g_opt_tile_threads.store(value);
       return CECA_OK;
     case CECA_OPT_XCD_TILE_ORDER:
       ceca::g_mix_xcd.store(value != 0);
@@ -344,14 +380,8 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
   if (rounds < 1) return fail(CECA_EINVAL, "rounds = %d: need at least one", rounds);
   hipStream_t st = (hipStream_t)hip_stream;
   const int32_t tau = ceca::tau_of(n);
-  // rows per thread: 8 leaves room for twice as many workgroups per CU (measured 1.5x faster at n = 100)
-  // as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
-  int32_t cap = g_opt_rows.load();
-  if (cap < 4 || cap > ceca::kMultiRows) cap = (n <= 256) ? 8 : ceca::kMultiRows;
-  int32_t row_lanes = 1;
-  while (row_lanes * cap < n) row_lanes *= 2;
-  const int32_t rpt = (n + row_lanes - 1) / row_lanes;   // exactly the rows n needs with that many row lanes
-  if (n == 1 || row_lanes > ceca::kBlock) {
+  const TileShape tv = rounds_tile(n, true), ts = rounds_tile(n, false);
+  if (n == 1 || !tv.ok || !ts.ok) {
     // too many agents for one workgroup's registers (or nothing to fuse): one launch per round, the
     // first from S_in to S_out, the rest in place on S_out (whole cycles / pairs read before they write)
     for (int32_t t = 0; t < rounds; ++t) {
@@ -373,8 +403,6 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
     m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
     m.ld = ld;
     m.n = n;  m.port = port;  m.rounds = cnt;
-    m.row_lanes = row_lanes;
-    m.rows_per_thread = rpt;
     for (int32_t t = 0; t < cnt; ++t) {
       ceca::fill_round(n, (t0 + t) % tau, port, &rd);
       ceca::MultiRound& R = m.round[t];
@@ -383,11 +411,13 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
     }
     if (d4 > 0) {
       m.col0 = 0;  m.ngroups = d4;
+      m.threads = tv.threads;  m.row_lanes = tv.row_lanes;  m.rows_per_thread = tv.rows_per_thread;
       const hipError_t e = ceca::launch_multi_round(m, true, st);
       if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch");
     }
     if (d - 4 * d4 > 0) {
       m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+      m.threads = ts.threads;  m.row_lanes = ts.row_lanes;  m.rows_per_thread = ts.rows_per_thread;
       const hipError_t e = ceca::launch_multi_round(m, false, st);
       if (e != hipSuccess) return hip_fail(e, "multi-round kernel launch (scalar columns)");
     }
@@ -406,18 +436,13 @@ int32_t ceca_average(const float* X_in, float* X_out, int32_t n, int64_t d, int6
     return fail(CECA_EINVAL, "X_out partially overlaps X_in");
   hipStream_t st = (hipStream_t)hip_stream;
   const int32_t tau = ceca::tau_of(n);
-  int32_t cap = g_opt_rows.load();
-  if (cap < 4 || cap > ceca::kMultiRows) cap = (n <= 256) ? 8 : ceca::kMultiRows;
-  int32_t row_lanes = 1;
-  while (row_lanes * cap < n) row_lanes *= 2;
-  if (row_lanes > ceca::kBlock) row_lanes = ceca::kBlock;
+  const TileShape tv = rounds_tile(n, true), ts = rounds_tile(n, false);
+  if (!tv.ok || !ts.ok) return fail(CECA_EINVAL, "internal: no tile holds n = %d agents", n);
   ceca::MultiArgs m{};
   m.xin = X_in;
   m.xout = X_out;  m.yout = nullptr;
   m.ld = ld;
   m.n = n;  m.port = port;  m.rounds = tau;          // n = 1: no rounds, the kernel copies
-  m.row_lanes = row_lanes;
-  m.rows_per_thread = (n + row_lanes - 1) / row_lanes;
   ceca_round_t rd;
   for (int32_t t = 0; t < tau; ++t) {
     ceca::fill_round(n, t, port, &rd);
@@ -429,11 +454,13 @@ int32_t ceca_average(const float* X_in, float* X_out, int32_t n, int64_t d, int6
   const int64_t d4 = can_vec ? d / 4 : 0;
   if (d4 > 0) {
     m.col0 = 0;  m.ngroups = d4;
+    m.threads = tv.threads;  m.row_lanes = tv.row_lanes;  m.rows_per_thread = tv.rows_per_thread;
     const hipError_t e = ceca::launch_multi_round(m, true, st);
     if (e != hipSuccess) return hip_fail(e, "averaging kernel launch");
   }
   if (d - 4 * d4 > 0) {
     m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+    m.threads = ts.threads;  m.row_lanes = ts.row_lanes;  m.rows_per_thread = ts.rows_per_thread;
     const hipError_t e = ceca::launch_multi_round(m, false, st);
     if (e != hipSuccess) return hip_fail(e, "averaging kernel launch (scalar columns)");
   }

@@ -51,6 +51,7 @@ struct MultiRound {
 
 constexpr int kMultiRows = 16;       // most rows of (x, y) a thread of the multi-round kernel keeps in registers
 constexpr int kMultiMaxRounds = 64;
+constexpr size_t kMultiMaxLds = 160 * 1024;   // LDS one workgroup can have on gfx950
 
 struct MultiArgs {
   const float* xin;    // row 0 of x in S_in (y of S_in is not read: round 0 overwrites it)
@@ -63,6 +64,8 @@ struct MultiArgs {
   int32_t xcd_tiles;        // > 0: workgroup b takes tile (b % 8) * xcd_tiles + b / 8 (set by the launcher)
   int32_t rows_per_thread;  // 1 to 16 rows of (x, y) in a thread's registers
   int32_t row_lanes;   // power of two, row_lanes * rows_per_thread >= n: threads of a workgroup that share a column group
+  int32_t threads;     // threads per workgroup of the gossip-rounds kernel: 0 = 256, or 512 / 1024 (16-byte groups only);
+                       // 512 / 1024 keep at most 9 rows per thread in registers without spilling
   MultiRound round[kMultiMaxRounds];
 };
 

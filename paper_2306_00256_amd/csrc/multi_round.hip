@@ -24,13 +24,21 @@ static int32_t xcd_run(int row_bytes, int64_t* blocks) {
   return (int32_t)per;
 }
 
-template <int VEC, int RT>
-__global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) {
+// Wavefronts per SIMD the kernel is compiled for: workgroups wider than 256 threads hold many agents'
+// rows and must fit 128 registers per thread (four wavefronts per SIMD: one 1024-thread workgroup or two
+// 512-thread ones per compute unit); 256-thread workgroups take what their rows need.
+template <int THREADS>
+constexpr int multi_round_waves() { return THREADS > 256 ? 4 : 1; }
+
+template <int VEC, int RT, int THREADS>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(multi_round_waves<THREADS>())))
+void multi_round_kernel(const MultiArgs M) {
   using V = typename VecOf<VEC>::T;
   extern __shared__ float lds_z[];                 // [n][lanes] groups of VEC floats
-  const int lanes = kBlock / M.row_lanes;          // column groups per row handled by this workgroup
-  const int cg = threadIdx.x % lanes;              // my column group inside the tile
-  const int rg = threadIdx.x / lanes;              // my first row; I own rows rg, rg + row_lanes, ...
+  const int lanes = THREADS / M.row_lanes;         // column groups per row handled by this workgroup
+  const int tid = threadIdx.x;
+  const int cg = tid % lanes;                      // my column group inside the tile
+  const int rg = tid / lanes;                      // my first row; I own rows rg, rg + row_lanes, ...
   // narrow tiles: every XCD (workgroups go round-robin over 8 of them, each with its own L2) takes a
   // contiguous run of tiles, so that the two halves of a 128-byte line meet in one L2
   int64_t tile = blockIdx.x;
@@ -49,62 +57,78 @@ __global__ __launch_bounds__(kBlock) void multi_round_kernel(const MultiArgs M) 
     y[k] = V(0.0f);                                // round 0 has b = 0: y(0) is never used
   }
   V* zs = reinterpret_cast<V*>(lds_z);
-  // LDS slot of each of my rows (rows past the last agent shadow it and are never published)
-  int slot[RT];
-  bool mine[RT];
-#pragma unroll
-  for (int k = 0; k < RT; ++k) {
-    const int i = rg + k * M.row_lanes;
-    mine[k] = i < M.n;
-    slot[k] = min(i, M.n - 1) * lanes + cg;
-  }
+  // Row i, column group c sits in LDS slot i * lanes + c, so my row k is slot tid + k * THREADS
+  // (row_lanes * lanes = THREADS).  rows_per_thread is the least that covers n, so only my last row can
+  // lie past the last agent: it then shadows agent n - 1 and is never published.
+  constexpr int L = RT - 1;
+  const bool last_mine = rg + L * M.row_lanes < M.n;
+  const int slot_last = last_mine ? tid + L * THREADS : (M.n - 1) * lanes + cg;
   const int wrap = M.n * lanes;
+  // one port: even rows look ahead, odd rows back (Eq. (7)); my rows rg + k * row_lanes share rg's parity
+  // unless I hold consecutive rows (row_lanes = 1)
+  const bool alternate = M.row_lanes == 1;
+  const bool rg_odd = (rg & 1) != 0;
+  // rows whose messages are read from LDS together: all of them, or a few at a time where registers are short
+  constexpr int KB = (THREADS > 256 && RT > 4) ? (RT > 7 ? 2 : 4) : RT;
   for (int t = 0; t < M.rounds; ++t) {
     const MultiRound R = M.round[t];
     // the round's flags are the same for every thread: branches, not per-element selects
     if (R.exch_y) {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) if (mine[k]) zs[slot[k]] = y[k];
+      for (int k = 0; k < L; ++k) zs[tid + k * THREADS] = y[k];
+      if (last_mine) zs[slot_last] = y[L];
     } else {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) if (mine[k]) zs[slot[k]] = x[k];
+      for (int k = 0; k < L; ++k) zs[tid + k * THREADS] = x[k];
+      if (last_mine) zs[slot_last] = x[L];
     }
     __syncthreads();
-    // no branch around the LDS reads, so a thread's RT reads issue back to back
-    V zp[RT];
     const int back = R.shift * lanes;
-    if (M.port == 2) {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) {
-        int q = slot[k] - back;
-        if (q < 0) q += wrap;
-        zp[k] = zs[q];
+    for (int k0 = 0; k0 < RT; k0 += KB) {
+      // no branch around the LDS reads, so the reads of a batch issue back to back
+      V zp[KB];
+#pragma unroll
+      for (int j = 0; j < KB; ++j) {
+        const int k = k0 + j;
+        if (k < RT) {
+          const int s = (k == L) ? slot_last : tid + k * THREADS;
+          int q;
+          if (M.port == 2) {
+            q = s - back;
+            if (q < 0) q += wrap;
+          } else {
+            const bool odd = alternate ? ((k & 1) != 0) : rg_odd;
+            q = odd ? s - back : s + back;
+            if (q < 0) q += wrap;
+            if (q >= wrap) q -= wrap;
+          }
+          zp[j] = zs[q];
+        }
       }
-    } else {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) {
-        const int i = min(rg + k * M.row_lanes, M.n - 1);
-        int q = (i & 1) ? slot[k] - back : slot[k] + back;     // even rows look ahead, odd rows back (Eq. (7))
-        if (q < 0) q += wrap;
-        if (q >= wrap) q -= wrap;
-        zp[k] = zs[q];
+      for (int j = 0; j < KB; ++j)
+        if (k0 + j < RT) x[k0 + j] = combine(R.a, x[k0 + j], R.ap, zp[j]);
+      if (R.read_y) {
+#pragma unroll
+        for (int j = 0; j < KB; ++j)
+          if (k0 + j < RT) y[k0 + j] = combine(R.b, y[k0 + j], R.bp, zp[j]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < KB; ++j)
+          if (k0 + j < RT) y[k0 + j] = R.bp * zp[j];
       }
-    }
-#pragma unroll
-    for (int k = 0; k < RT; ++k) x[k] = combine(R.a, x[k], R.ap, zp[k]);
-    if (R.read_y) {
-#pragma unroll
-      for (int k = 0; k < RT; ++k) y[k] = combine(R.b, y[k], R.bp, zp[k]);
-    } else {
-#pragma unroll
-      for (int k = 0; k < RT; ++k) y[k] = R.bp * zp[k];
+      if (KB < RT) __builtin_amdgcn_sched_barrier(0);    // keep the batches apart
     }
     __syncthreads();
   }
   if (!on) return;
+  // the row addresses are worked out here, after the rounds: nothing of them occupies registers meanwhile
+  int rg_out = rg;
+  asm volatile("" : "+v"(rg_out));
 #pragma unroll
   for (int k = 0; k < RT; ++k) {
-    const int i = rg + k * M.row_lanes;
+    const int i = rg_out + k * M.row_lanes;
     if (i < M.n) {
       st_stream<V>(M.xout + (int64_t)i * M.ld + col, x[k]);
       if (M.yout) st_stream<V>(M.yout + (int64_t)i * M.ld + col, y[k]);   // same for every thread
@@ -239,31 +263,51 @@ hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int VEC, int RT, int THREADS>
+static hipError_t launch_rounds(const MultiArgs& mm, unsigned blocks, size_t lds, hipStream_t st) {
+  if (lds > 64 * 1024) {
+    // more than 64 KB of LDS per workgroup has to be asked for
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&multi_round_kernel<VEC, RT, THREADS>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  multi_round_kernel<VEC, RT, THREADS><<<dim3(blocks), dim3(THREADS), lds, st>>>(mm);
+  return hipGetLastError();
+}
+
+template <int VEC, int THREADS>
+static hipError_t launch_rounds_rt(const MultiArgs& mm, unsigned blocks, size_t lds, hipStream_t st) {
+  switch (mm.rows_per_thread) {
+#define CECA_RT(RT) case RT: return launch_rounds<VEC, RT, THREADS>(mm, blocks, lds, st)
+    CECA_RT(1); CECA_RT(2); CECA_RT(3); CECA_RT(4); CECA_RT(5); CECA_RT(6); CECA_RT(7); CECA_RT(8);
+    CECA_RT(9); CECA_RT(10); CECA_RT(11); CECA_RT(12); CECA_RT(13); CECA_RT(14); CECA_RT(15); CECA_RT(16);
+#undef CECA_RT
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st) {
   if (m.ngroups <= 0) return hipSuccess;
-  const int lanes = kBlock / m.row_lanes;
+  const int threads = m.threads > 0 ? m.threads : kBlock;
+  if (threads != 256 && threads != 512 && threads != 1024) return hipErrorInvalidValue;
+  if (!vec4 && threads != 256) return hipErrorInvalidValue;          // scalar columns: 256-thread tiles only
+  if (m.row_lanes < 1 || m.row_lanes > threads || (m.row_lanes & (m.row_lanes - 1)) != 0) return hipErrorInvalidValue;
+  // the kernel relies on rows_per_thread being the least that covers n (only a thread's last row can
+  // lie past the last agent)
+  if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows ||
+      (int64_t)m.rows_per_thread * m.row_lanes < m.n || (int64_t)(m.rows_per_thread - 1) * m.row_lanes >= m.n)
+    return hipErrorInvalidValue;
+  const int lanes = threads / m.row_lanes;
   int64_t blocks = (m.ngroups + lanes - 1) / lanes;
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
   MultiArgs mm = m;
   mm.xcd_tiles = xcd_run(lanes * (vec4 ? 16 : 4), &blocks);
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
-  dim3 grid((unsigned)blocks), block(kBlock);
-  // 16-byte groups: exactly the rows n needs (1..16 per thread); the few scalar tail columns round up
-#define CECA_MULTI4(RT) case RT: multi_round_kernel<4, RT><<<grid, block, lds, st>>>(mm); break
-#define CECA_MULTI1(RT) multi_round_kernel<1, RT><<<grid, block, lds, st>>>(mm)
-  if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows) return hipErrorInvalidValue;
-  if (vec4) {
-    switch (m.rows_per_thread) {
-      CECA_MULTI4(1); CECA_MULTI4(2); CECA_MULTI4(3); CECA_MULTI4(4); CECA_MULTI4(5); CECA_MULTI4(6);
-      CECA_MULTI4(7); CECA_MULTI4(8); CECA_MULTI4(9); CECA_MULTI4(10); CECA_MULTI4(11); CECA_MULTI4(12);
-      CECA_MULTI4(13); CECA_MULTI4(14); CECA_MULTI4(15); CECA_MULTI4(16);
-    }
-  } else if (m.rows_per_thread <= 4) CECA_MULTI1(4);
-  else if (m.rows_per_thread <= 8) CECA_MULTI1(8);
-  else CECA_MULTI1(16);
-#undef CECA_MULTI4
-#undef CECA_MULTI1
-  return hipGetLastError();
+  if (lds > kMultiMaxLds) return hipErrorInvalidValue;
+  if (!vec4) return launch_rounds_rt<1, 256>(mm, (unsigned)blocks, lds, st);
+  if (threads == 256) return launch_rounds_rt<4, 256>(mm, (unsigned)blocks, lds, st);
+  if (threads == 512) return launch_rounds_rt<4, 512>(mm, (unsigned)blocks, lds, st);
+  return launch_rounds_rt<4, 1024>(mm, (unsigned)blocks, lds, st);
 }
 
 }  // namespace ceca
