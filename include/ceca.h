@@ -246,9 +246,11 @@ int32_t ceca_last_hip_error(void);
 
 /* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe against running calls):
  *   CECA_OPT_SEGMENT  agents a 2-port chain walks before it starts a new one (0 = library default)
- *   CECA_OPT_ROWS     state rows whose loads one thread keeps in flight: 1, 2, 4 or 8 (0 = library default);
- *                     for ceca_gossip_rounds: rows of the tile per thread, 4, 8 or 16
- *                     for ceca_mix_rounds: most rows of the tile per thread, a multiple of 4 up to 32
+ *   CECA_OPT_ROWS     0..32 (0 = library default).  Single rounds and steps: state rows whose loads one
+ *                     thread keeps in flight, 1, 2, 4 or 8 (other values: 4).  Register-tile kernels: most
+ *                     rows of the tile a thread holds -- 4..16 for ceca_gossip_rounds / ceca_average,
+ *                     1..16 for dsgd_ceca_steps, 4..32 for ceca_mix_rounds and the single-pass consensus
+ *                     (values outside a kernel's range leave that kernel at its default)
  *   CECA_OPT_BAND     column tiles (of 1024 columns) per band of the launch order (0 = library default)
  *   CECA_OPT_WG_PER_CU  cap on workgroups resident per compute unit, 2..8 (0 = library default)
  *   CECA_OPT_ONEPASS  1 (default): minibatch gradients keep the sampled rows in registers and read A once when
@@ -259,8 +261,9 @@ int32_t ceca_last_hip_error(void);
  *                     hold a column tile of every agent; 0: always the two-pass kernels
  *   CECA_OPT_XCD_TILE_ORDER  1 (default): register-tile kernels whose tile rows are narrower than 128 bytes give
  *                     each of the 8 XCDs a contiguous run of tiles; 0: plain order
- *   CECA_OPT_TILE_THREADS  threads per workgroup of the fused gossip-rounds kernel: 256, 512 or 1024
- *                     (0 = library default); more threads make the rows of a tile wider
+ *   CECA_OPT_TILE_THREADS  threads per workgroup of the fused gossip-rounds and mixing kernels: 256, 512 or
+ *                     1024 (0 = library default); more threads make the rows of a tile wider.  A tile
+ *                     shape that cannot hold n agents is replaced by the library's own
  * Returns CECA_EINVAL for an unknown option or value. */
 enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5,
        CECA_OPT_AGENTS_PER_WG = 7, CECA_OPT_CONS_SINGLE_PASS = 8, CECA_OPT_XCD_TILE_ORDER = 9,

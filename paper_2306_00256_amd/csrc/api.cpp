@@ -268,11 +268,11 @@ struct TileShape {
   bool ok;
 };
 
-TileShape rounds_tile(int32_t n, bool vec4) {
+TileShape rounds_tile_for(int32_t n, bool vec4, bool knobs) {
   TileShape t{};
-  int32_t cap = g_opt_rows.load();
+  int32_t cap = knobs ? g_opt_rows.load() : 0;
   const bool cap_given = cap >= 4 && cap <= ceca::kMultiRows;
-  t.threads = vec4 ? g_opt_tile_threads.load() : ceca::kBlock;
+  t.threads = vec4 ? (knobs ? g_opt_tile_threads.load() : 0) : ceca::kBlock;
   // Measured on MI355X (n = 31 ... 4096): 512-thread workgroups with up to 9 rows per thread (128
   // registers: two workgroups per compute unit) make the rows of the tile two to four times wider than
   // 256-thread ones and run 1.1x (n = 31) to 3x (n = 1026) faster; beyond 9 x 128 agents only a
@@ -289,6 +289,13 @@ TileShape rounds_tile(int32_t n, bool vec4) {
   return t;
 }
 
+// The tile the option knobs ask for when it holds n agents, else the library's own choice (which holds
+// up to 4096).
+TileShape rounds_tile(int32_t n, bool vec4) {
+  const TileShape t = rounds_tile_for(n, vec4, true);
+  return t.ok ? t : rounds_tile_for(n, vec4, false);
+}
+
 }  // namespace
 
 extern "C" {
@@ -303,8 +310,7 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
       g_opt_segment.store(value);
       return CECA_OK;
     case CECA_OPT_ROWS:
-      if (value != 0 && value != 1 && value != 2 && !(value >= 4 && value <= 32 && value % 4 == 0))
-        return fail(CECA_EINVAL, "rows must be 0, 1, 2 or a multiple of 4 up to 32");
+      if (value < 0 || value > 32) return fail(CECA_EINVAL, "rows must be 0..32");
       g_opt_rows.store(value);
       return CECA_OK;
     case CECA_OPT_WG_PER_CU:
@@ -768,31 +774,48 @@ int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, i
   m.n = n;  m.rounds = rounds;  m.period = period;  m.k0 = k0 % period;
   // Tile shape: a thread keeps up to `cap` rows; the fewest row lanes (a power of two) that cover n
   // rows give the widest row segments, and the row count is then trimmed to what n needs.
-  int32_t cap = g_opt_rows.load();
-  if (cap < 4 || cap > 32) {
-    // measured on MI355X (n = 31, 130, 258, 1026): one or two peers per round want wide row segments,
-    // many peers per round (LDS-read bound) want more resident workgroups
-    int32_t most = 0;
-    for (int32_t q = 0; q < period; ++q) most = std::max(most, specs[q].m);
-    const bool heavy = most >= 4;
-    cap = n <= 32 ? 12 : (n <= 192 ? (heavy ? 8 : 16) : (n <= 512 ? 16 : (heavy ? 16 : 24)));
-  }
-  int32_t row_lanes = 1;
-  while (row_lanes * cap < n) row_lanes *= 2;
-  if (row_lanes > ceca::kBlock) { row_lanes = ceca::kBlock; }
-  const int32_t rpt = (n + row_lanes - 1) / row_lanes;
-  m.rows_per_thread = rpt;
-  m.row_lanes = row_lanes;
+  int32_t most = 0;
+  for (int32_t q = 0; q < period; ++q) most = std::max(most, specs[q].m);
+  const bool heavy = most >= 4;
+  auto tile = [&](bool vec4, bool knobs) {
+    TileShape t{};
+    int32_t cap = knobs ? g_opt_rows.load() : 0;
+    t.threads = vec4 ? (knobs ? g_opt_tile_threads.load() : 0) : ceca::kBlock;
+    // measured on MI355X (n = 31 ... 4096, all three topologies): 256-thread workgroups are best up to
+    // about 512 agents; 512-thread ones (13 rows per thread in 128 registers, two per compute unit) gain
+    // 1.2x at n = 1026, and beyond 13 x 128 agents a 1024-thread workgroup keeps the rows of the tile at
+    // 64 bytes (1.7x at n = 2050, 2.5x at n = 4096)
+    if (t.threads == 0) t.threads = n <= 512 ? ceca::kBlock : (n <= 13 * 128 ? 512 : 1024);
+    const int32_t cap_max = t.threads == ceca::kBlock ? 32 : 16;
+    if (cap < 4 || cap > cap_max) {
+      // 256 threads (n = 31, 130, 258, 1026): one or two peers per round want wide row segments, many
+      // peers per round (LDS-read bound) want more resident workgroups
+      cap = t.threads != ceca::kBlock ? 13
+                                      : n <= 32 ? 12 : (n <= 192 ? (heavy ? 8 : 16) : (n <= 512 ? 16 : (heavy ? 16 : 24)));
+    }
+    t.row_lanes = 1;
+    while ((int64_t)t.row_lanes * cap < n) t.row_lanes *= 2;
+    t.rows_per_thread = (n + t.row_lanes - 1) / t.row_lanes;
+    const int64_t lds = t.row_lanes <= t.threads ? (int64_t)n * (t.threads / t.row_lanes) * (vec4 ? 16 : 4) : 0;
+    t.ok = t.row_lanes <= t.threads && lds <= (int64_t)ceca::kMultiMaxLds;
+    return t;
+  };
+  TileShape tv = tile(true, true), ts = tile(false, true);
+  if (!tv.ok) tv = tile(true, false);
+  if (!ts.ok) ts = tile(false, false);
+  if (!tv.ok || !ts.ok) return fail(CECA_EINVAL, "internal: no tile holds n = %d agents", n);
   hipStream_t st = (hipStream_t)hip_stream;
   const bool can_vec = aligned16(X_in) && aligned16(X_out) && ld % 4 == 0;
   const int64_t d4 = can_vec ? d / 4 : 0;
   if (d4 > 0) {
     m.col0 = 0;  m.ngroups = d4;
+    m.threads = tv.threads;  m.row_lanes = tv.row_lanes;  m.rows_per_thread = tv.rows_per_thread;
     const hipError_t e = ceca::launch_mix_rounds(m, true, st);
     if (e != hipSuccess) return hip_fail(e, "mixing kernel launch");
   }
   if (d - 4 * d4 > 0) {
     m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+    m.threads = ts.threads;  m.row_lanes = ts.row_lanes;  m.rows_per_thread = ts.rows_per_thread;
     const hipError_t e = ceca::launch_mix_rounds(m, false, st);
     if (e != hipSuccess) return hip_fail(e, "mixing kernel launch (scalar columns)");
   }

@@ -142,8 +142,9 @@ struct MixArgs {
   int64_t col0;
   int64_t ngroups;
   int32_t n, rounds, period, k0;
-  int32_t rows_per_thread;  // rows of x in a thread's registers: 1 to 32
+  int32_t rows_per_thread;  // rows of x in a thread's registers: 1 to 32, the least that covers n
   int32_t row_lanes;        // power of two, row_lanes * rows_per_thread >= n
+  int32_t threads;          // threads per workgroup: 0 = 256, or 512 / 1024 (16-byte groups only, at most 16 rows per thread)
   int32_t xcd_tiles;        // > 0: workgroup b takes tile (b % 8) * xcd_tiles + b / 8 (set by the launcher)
   int32_t start[kMixMaxPeriod + 1];
   float w_self[kMixMaxPeriod];

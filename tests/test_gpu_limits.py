@@ -200,3 +200,62 @@ def test_more_rounds_than_one_kernel_takes(env):
     assert torch.equal(X, Y)
     want = OT.run(x0, [OT.ring(n)], 300)
     assert max(rel_err(X.cpu().numpy(), want)) <= 1e-4
+
+
+@pytest.mark.parametrize("n,port", [(2, 2), (6, 1), (9, 2), (31, 2), (100, 1), (145, 2), (1026, 1), (1153, 2), (2050, 1), (4096, 2)])
+def test_workgroup_widths_of_the_fused_rounds_give_the_same_bits(env, n, port):
+    """256-, 512- and 1024-thread workgroups of the fused-rounds kernel (tile rows of different widths, up
+    to 144 KB of LDS), with the library's rows per thread and with fewer: same bits as single rounds, for
+    16-byte column groups with a scalar tail and for an unaligned layout; exact averaging and the mixing
+    rounds of the comparison topologies likewise (those against the oracle too)."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    tau = OS.num_rounds(n)
+    rounds = tau + 1
+    d = 4 * (37 if n > 1000 else 301) + 3
+    x0 = WL.initial_state(n, d, seed=n + port)
+    ref = make_state(torch, x0)
+    for r in range(rounds):
+        P.ceca_gossip_round(ref, ref, n, d, r % tau, port)
+    x, y = OC.run(x0, port, 0.0, None, rounds, store32=True)
+    gx, gy = split_state(ref, n, d)
+    assert max(rel_err(gx, x)) <= 1e-5 and max(rel_err(gy, y)) <= 1e-5
+    avg_ref = make_state(torch, x0)
+    for r in range(tau):
+        P.ceca_gossip_round(avg_ref, avg_ref, n, d, r, port)
+    # an unaligned copy of the same state: rows of d + 1 floats starting 4 bytes into an allocation
+    flat = torch.full((2 * n * (d + 1) + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    topos = {"ring": [P.ceca_topology_round(Bn.TOPO_RING, n)], "static": [P.ceca_topology_round(Bn.TOPO_STATIC_EXP, n)],
+             "one_peer": [P.ceca_topology_round(Bn.TOPO_ONE_PEER_EXP, n, k) for k in range(max(tau, 1))]}
+    mixed = {}
+    try:
+        for threads in (256, 512, 1024):
+            for rows in (0, 5):
+                P.ceca_set_option(Bn.OPT_TILE_THREADS, threads)
+                P.ceca_set_option(Bn.OPT_ROWS, rows)
+                S = make_state(torch, x0)
+                T = torch.full_like(S, float("nan"))
+                P.ceca_gossip_rounds(S, T, n, d, rounds, port)
+                assert torch.equal(T, ref), (threads, rows)
+                U = flat[1:].view(2 * n, d + 1)
+                U[:, :d] = make_state(torch, x0)
+                P.ceca_gossip_rounds(U, U, n, d, rounds, port, ld=d + 1)
+                assert torch.equal(U[:, :d], ref), (threads, rows, "unaligned")
+                X = torch.from_numpy(x0).cuda()
+                P.ceca_average(X, X, n, d, port)
+                assert torch.equal(X, avg_ref[:n]), (threads, rows, "average")
+                for name, specs in topos.items():
+                    X = torch.from_numpy(x0).cuda()
+                    Y = torch.full_like(X, float("nan"))
+                    P.ceca_mix_rounds(X, Y, n, d, specs, 3, k0=1)
+                    if name not in mixed:
+                        mixed[name] = Y                     # first pass: 256-thread tiles, checked against the oracle below
+                    assert torch.equal(Y, mixed[name]), (threads, rows, name)
+    finally:
+        P.ceca_set_option(Bn.OPT_TILE_THREADS, 0)
+        P.ceca_set_option(Bn.OPT_ROWS, 0)
+    otop = {"ring": [OT.ring(n)], "static": [OT.static_exponential(n)],
+            "one_peer": [OT.one_peer_exponential(n, k) for k in range(max(tau, 1))]}
+    for name, specs in otop.items():
+        want = OT.run(x0, specs, 3, k0=1)
+        assert max(rel_err(mixed[name].cpu().numpy(), want)) <= 1e-5, name
