@@ -288,6 +288,18 @@ def run_mix(torch, P, Bn, n, d, steps, warmup):
         ms = tm.event_ms / steps
         out[kind] = {"ms_per_call": ms, "GBs": 8.0 * n * d / (ms * 1e-3) / 1e9,
                      "agent_param_rounds_per_s": tau * n * d / (ms * 1e-3)}
+    # CECA beside them: the same tau rounds on the same x reach the exact mean (ceca_average keeps the
+    # auxiliary y in registers, so it also moves 8 bytes per agent-parameter)
+    for port in (2, 1) if n % 2 == 0 else (2,):
+        for _ in range(warmup):
+            P.ceca_average(X, Y, n, d, port, ld=ld)
+        tm = Timer(torch)
+        with tm:
+            for _ in range(steps):
+                P.ceca_average(X, Y, n, d, port, ld=ld)
+        ms = tm.event_ms / steps
+        out[f"ceca_{port}p"] = {"ms_per_call": ms, "GBs": 8.0 * n * d / (ms * 1e-3) / 1e9,
+                                "agent_param_rounds_per_s": tau * n * d / (ms * 1e-3)}
     return out
 
 
