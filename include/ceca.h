@@ -115,8 +115,10 @@ int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d,
  * The result has the same bits as `rounds` calls of ceca_gossip_round.  Because the sequence starts
  * at round 0, the y rows of S_in are never read.  S_out may be S_in or disjoint from it.
  * Up to 4096 agents run through kernels that move 12 bytes per agent-parameter for as many whole cycles
- * as fit in 64 rounds each (longer runs take several such kernels, in place on S_out after the first);
- * more agents fall back to one launch per round (in place on S_out after the first). */
+ * as fit in 64 rounds each (longer runs take several such kernels, in place on S_out after the first).
+ * More agents, a single round, and -- with one port or at least 2^20 columns -- fewer than 3-5 rounds on
+ * more than about 1150 agents (where the fused pass costs more than that many streaming rounds) take one
+ * launch per round instead (in place on S_out after the first). */
 int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                            int32_t rounds, int32_t port, void* hip_stream);
 
@@ -151,7 +153,9 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
  * independent across whole iterations and a workgroup can carry a column tile of x, y and c through all
  * of them in registers -- 20 bytes per agent-parameter for the whole call instead of per iteration.
  * S_out may be S_in or disjoint from it.  Up to 4096 agents run as one kernel per 64 iterations (in place
- * on S_out after the first); more agents fall back to one dsgd_ceca_step per iteration (likewise). */
+ * on S_out after the first).  More agents, and -- with one port or at least 2^20 columns -- runs too short
+ * to repay a narrow tile (fewer than 3, 8 or 14 iterations on more than 640, 1280 or 2560 agents), take one
+ * dsgd_ceca_step per iteration (likewise). */
 int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
                         const ceca_loss_t* loss, float lr, int32_t r0, int32_t steps, int32_t port,
                         void* hip_stream);
@@ -261,9 +265,9 @@ int32_t ceca_last_hip_error(void);
  *                     hold a column tile of every agent; 0: always the two-pass kernels
  *   CECA_OPT_XCD_TILE_ORDER  1 (default): register-tile kernels whose tile rows are narrower than 128 bytes give
  *                     each of the 8 XCDs a contiguous run of tiles; 0: plain order
- *   CECA_OPT_TILE_THREADS  threads per workgroup of the fused gossip-rounds and mixing kernels: 256, 512 or
- *                     1024 (0 = library default); more threads make the rows of a tile wider.  A tile
- *                     shape that cannot hold n agents is replaced by the library's own
+ *   CECA_OPT_TILE_THREADS  threads per workgroup of the fused rounds, fused iterations and mixing kernels:
+ *                     256, 512 or 1024 (0 = library default); more threads make the rows of a tile
+ *                     wider.  A tile shape that cannot hold n agents is replaced by the library's own
  * Returns CECA_EINVAL for an unknown option or value. */
 enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5,
        CECA_OPT_AGENTS_PER_WG = 7, CECA_OPT_CONS_SINGLE_PASS = 8, CECA_OPT_XCD_TILE_ORDER = 9,

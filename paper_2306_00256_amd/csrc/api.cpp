@@ -387,8 +387,18 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
   hipStream_t st = (hipStream_t)hip_stream;
   const int32_t tau = ceca::tau_of(n);
   const TileShape tv = rounds_tile(n, true), ts = rounds_tile(n, false);
-  if (n == 1 || !tv.ok || !ts.ok) {
-    // too many agents for one workgroup's registers (or nothing to fuse): one launch per round, the
+  const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
+  // A single round is the streaming kernel's job, and tiles with rows narrower than a 128-byte line pay
+  // off only over a few rounds (measured: the fused pass costs about 1.5, 2.5 and 4.7 single rounds at
+  // n = 1026, 2050 and 4096).
+  const int32_t row_bytes = can_vec ? (tv.threads / std::max(tv.row_lanes, 1)) * 16 : (ts.threads / std::max(ts.row_lanes, 1)) * 4;
+  const int32_t worth = row_bytes >= 64 ? (tv.threads == 1024 && can_vec ? 3 : 2) : 5;
+  const bool knobs = g_opt_rows.load() != 0 || g_opt_tile_threads.load() != 0;
+  // (rounds after the first run in place on S_out: with two ports those walk whole cycles, which needs
+  // many column tiles to fill the device)
+  const bool rounds_fill = port == 1 || d >= 1024 * 1024 || rounds == 1;
+  if (n == 1 || !tv.ok || !ts.ok || (rounds < worth && rounds_fill && !knobs)) {
+    // too many agents for one workgroup's registers (or too little to fuse): one launch per round, the
     // first from S_in to S_out, the rest in place on S_out (whole cycles / pairs read before they write)
     for (int32_t t = 0; t < rounds; ++t) {
       const int32_t r1 = ceca_gossip_round(t == 0 ? S_in : S_out, S_out, n, d, ld, n == 1 ? 0 : t % tau, port, st);
@@ -396,7 +406,6 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
     }
     return CECA_OK;
   }
-  const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
   const int64_t d4 = can_vec ? d / 4 : 0;
   // one kernel takes up to kMultiMaxRounds rounds; longer runs go in pieces of whole cycles (the
   // kernel starts at round 0, which reads no y), the first from S_in to S_out and the rest in place
@@ -681,15 +690,40 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
   hipStream_t st = (hipStream_t)hip_stream;
   const int32_t tau = ceca::tau_of(n);
   // The tile holds x, y and c, and with noise the kernel is bound by the generator's arithmetic: few rows
-  // per thread (small register footprint, many resident wavefronts) measured best on MI355X; many
-  // agents need more rows per thread to keep a row of the tile at least 32-64 bytes wide.
-  int32_t cap = g_opt_rows.load();
-  if (cap < 1 || cap > ceca::kMultiRows) cap = n <= 128 ? 4 : (n <= 512 ? 8 : (steps <= 16 ? 16 : 8));
-  int32_t row_lanes = 1;
-  while (row_lanes * cap < n) row_lanes *= 2;
-  if (row_lanes > ceca::kBlock) { row_lanes = ceca::kBlock; }
-  const int32_t rpt = (n + row_lanes - 1) / row_lanes;
-  if (n == 1 || rpt > ceca::kMultiRows) {
+  // per thread (small register footprint, many resident wavefronts) measured best on MI355X.  More
+  // agents need wider workgroups to keep a row of the tile 64 bytes wide: x, y and c of 5 rows fit the
+  // 128 registers of a 512-thread (two per compute unit) or 1024-thread workgroup.  Measured against
+  // 256-thread tiles, 4 iterations, 2^26 elements: n = 258 0.19 -> 0.13 ms, n = 640 0.27 -> 0.23,
+  // n = 1026 0.72 -> 0.26, n = 2050 1.39 -> 0.62.
+  auto tile = [&](bool vec4, bool knobs) {
+    TileShape t{};
+    int32_t cap = knobs ? g_opt_rows.load() : 0;
+    t.threads = vec4 ? (knobs ? g_opt_tile_threads.load() : 0) : ceca::kBlock;
+    if (t.threads == 0) t.threads = n <= 128 ? ceca::kBlock : (n <= 5 * 128 ? 512 : 1024);
+    const int32_t cap_max = t.threads == ceca::kBlock ? ceca::kMultiRows : 8;
+    if (cap < 1 || cap > cap_max)
+      cap = t.threads != ceca::kBlock ? 5 : (n <= 128 ? 4 : (n <= 512 ? 8 : (steps <= 16 ? 16 : 8)));
+    t.row_lanes = 1;
+    while ((int64_t)t.row_lanes * cap < n) t.row_lanes *= 2;
+    t.rows_per_thread = (n + t.row_lanes - 1) / t.row_lanes;
+    const int64_t lds = t.row_lanes <= t.threads ? (int64_t)n * (t.threads / t.row_lanes) * (vec4 ? 16 : 4) : 0;
+    t.ok = t.row_lanes <= t.threads && lds <= (int64_t)ceca::kMultiMaxLds;
+    return t;
+  };
+  TileShape tv = tile(true, true), ts = tile(false, true);
+  if (!tv.ok) tv = tile(true, false);
+  if (!ts.ok) ts = tile(false, false);
+  const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->c) && loss->ldc % 4 == 0;
+  // A tile row narrower than a 128-byte line reads and writes HBM several times less efficiently than
+  // the streaming single-step kernel, which only pays off over enough iterations (measured at n = 1026,
+  // 2050, 4096: the fused pass costs about 2, 6 and 11 single steps at 64, 32 and 16 bytes).
+  const int32_t row_bytes = can_vec ? (tv.threads / std::max(tv.row_lanes, 1)) * 16 : (ts.threads / std::max(ts.row_lanes, 1)) * 4;
+  const int32_t worth = row_bytes >= 128 ? 1 : (row_bytes >= 64 ? 3 : (row_bytes >= 32 ? 8 : 14));
+  // (the steps after the first run in place on S_out: with two ports those walk whole cycles, which
+  // needs many column tiles to fill the device)
+  const bool steps_fill = port == 1 || d >= 1024 * 1024;
+  const bool knobs = g_opt_rows.load() != 0 || g_opt_tile_threads.load() != 0;
+  if (n == 1 || !tv.ok || !ts.ok || (steps < worth && steps_fill && !knobs)) {
     ceca_loss_t one = *loss;
     for (int32_t t = 0; t < steps; ++t) {
       one.k = loss->k + (uint32_t)t;
@@ -699,7 +733,6 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
     }
     return CECA_OK;
   }
-  const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->c) && loss->ldc % 4 == 0;
   const int64_t d4 = can_vec ? d / 4 : 0;
   // one kernel takes up to kMultiMaxRounds iterations; longer runs go in pieces, the first from S_in
   // to S_out and the rest in place on S_out (a workgroup holds its whole tile before it writes)
@@ -712,8 +745,6 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
     m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
     m.ld = ld;
     m.n = n;  m.port = port;  m.rounds = cnt;
-    m.row_lanes = row_lanes;
-    m.rows_per_thread = rpt;
     for (int32_t t = 0; t < cnt; ++t) {
       ceca::fill_round(n, (r0 + t0 + t) % tau, port, &rd);
       ceca::MultiRound& R = m.round[t];
@@ -725,11 +756,13 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
     a.lr = lr;  a.noise_std = loss->noise_std;  a.seed = loss->seed;  a.k0 = loss->k + (uint32_t)t0;
     if (d4 > 0) {
       m.col0 = 0;  m.ngroups = d4;
+      m.threads = tv.threads;  m.row_lanes = tv.row_lanes;  m.rows_per_thread = tv.rows_per_thread;
       const hipError_t e = ceca::launch_multi_step(a, true, st);
       if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch");
     }
     if (d - 4 * d4 > 0) {
       m.col0 = 4 * d4;  m.ngroups = d - 4 * d4;
+      m.threads = ts.threads;  m.row_lanes = ts.row_lanes;  m.rows_per_thread = ts.rows_per_thread;
       const hipError_t e = ceca::launch_multi_step(a, false, st);
       if (e != hipSuccess) return hip_fail(e, "multi-step kernel launch (scalar columns)");
     }

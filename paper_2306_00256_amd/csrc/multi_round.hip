@@ -144,15 +144,17 @@ void multi_round_kernel(const MultiArgs M) {
 // Eqs. (8), (9)), `rounds` times.  20 bytes per agent-parameter for any number of iterations.  The
 // arithmetic per iteration is that of the single-step kernel, operation for operation.
 // ---------------------------------------------------------------------------------------------
-template <int VEC, int RT>
-__global__ __launch_bounds__(kBlock) void multi_step_kernel(const StepsArgs S) {
+template <int VEC, int RT, int THREADS>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(multi_round_waves<THREADS>())))
+void multi_step_kernel(const StepsArgs S) {
 #pragma clang fp contract(off)
   using V = typename VecOf<VEC>::T;
   const MultiArgs& M = S.m;
   extern __shared__ float lds_z[];                 // [n][lanes] groups of VEC floats
-  const int lanes = kBlock / M.row_lanes;
-  const int cg = threadIdx.x % lanes;
-  const int rg = threadIdx.x / lanes;
+  const int lanes = THREADS / M.row_lanes;
+  const int tid = threadIdx.x;
+  const int cg = tid % lanes;
+  const int rg = tid / lanes;
   // narrow tiles: every XCD (workgroups go round-robin over 8 of them, each with its own L2) takes a
   // contiguous run of tiles, so that the two halves of a 128-byte line meet in one L2
   int64_t tile = blockIdx.x;
@@ -180,55 +182,93 @@ __global__ __launch_bounds__(kBlock) void multi_step_kernel(const StepsArgs S) {
     for (int k = 0; k < RT; ++k) y[k] = V(0.0f);
   }
   V* zs = reinterpret_cast<V*>(lds_z);
+  // Row i, column group c sits in LDS slot i * lanes + c, so my row k is slot tid + k * THREADS
+  // (row_lanes * lanes = THREADS).  rows_per_thread is the least that covers n, so only my last row can
+  // lie past the last agent: it then shadows agent n - 1 and is never published.
+  constexpr int L = RT - 1;
+  const bool last_mine = rg + L * M.row_lanes < M.n;
+  const int slot_last = last_mine ? tid + L * THREADS : (M.n - 1) * lanes + cg;
+  const int wrap = M.n * lanes;
+  const bool alternate = M.row_lanes == 1;         // one port: my rows share rg's parity unless consecutive
+  const bool rg_odd = (rg & 1) != 0;
   for (int t = 0; t < M.rounds; ++t) {
     const MultiRound R = M.round[t];
-    V ge[RT];
-    // local step of row k at z (its x or y): lr * e stays in registers, the message v_i goes to LDS
-    auto half_step = [&](int k, const V& z) {
+    // Local step of row k at z (its x or y): both x and y move by lr * e (Algorithm 1; x - lr e and
+    // y - lr e are what Eqs. (8), (9) combine), and the moved z is the message v.
+    auto local_step = [&](int k, const V& z) {
       const int i = min(rg + k * M.row_lanes, M.n - 1);
       V e = z - c[k];
       if (S.noise_std != 0.0f) e += S.noise_std * noise_group<V>(col, noise_keys(S.seed, S.k0 + (uint32_t)t, (uint32_t)i));
-      ge[k] = S.lr * e;
-      if (rg + k * M.row_lanes < M.n) zs[i * lanes + cg] = z - ge[k];
+      const V ge = S.lr * e;
+      x[k] = x[k] - ge;
+      y[k] = y[k] - ge;
     };
     // the round's flags are the same for every thread: branches, not per-element selects
     if (R.exch_y) {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) half_step(k, y[k]);
+      for (int k = 0; k < RT; ++k) {
+        local_step(k, y[k]);
+        if (k < L) zs[tid + k * THREADS] = y[k];
+        else if (last_mine) zs[slot_last] = y[k];
+        if (THREADS > 256) __builtin_amdgcn_sched_barrier(0);     // row by row where registers are short
+      }
     } else {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) half_step(k, x[k]);
+      for (int k = 0; k < RT; ++k) {
+        local_step(k, x[k]);
+        if (k < L) zs[tid + k * THREADS] = x[k];
+        else if (last_mine) zs[slot_last] = x[k];
+        if (THREADS > 256) __builtin_amdgcn_sched_barrier(0);     // row by row where registers are short
+      }
     }
     __syncthreads();
-    V zp[RT];
+    const int back = R.shift * lanes;
+    // rows whose messages are read from LDS together: all of them, or two at a time where registers are short
+    constexpr int KB = (THREADS > 256 && RT > 2) ? 2 : RT;
 #pragma unroll
-    for (int k = 0; k < RT; ++k) {
-      const int i = min(rg + k * M.row_lanes, M.n - 1);
-      int p;
-      if (M.port == 2) {
-        p = i - R.shift; if (p < 0) p += M.n;
-      } else {
-        p = (i & 1) ? i - R.shift : i + R.shift;
-        if (p < 0) p += M.n;
-        if (p >= M.n) p -= M.n;
+    for (int k0 = 0; k0 < RT; k0 += KB) {
+      V zp[KB];
+#pragma unroll
+      for (int j = 0; j < KB; ++j) {
+        const int k = k0 + j;
+        if (k < RT) {
+          const int s = (k == L) ? slot_last : tid + k * THREADS;
+          int q;
+          if (M.port == 2) {
+            q = s - back;
+            if (q < 0) q += wrap;
+          } else {
+            const bool odd = alternate ? ((k & 1) != 0) : rg_odd;   // even rows look ahead, odd rows back (Eq. (7))
+            q = odd ? s - back : s + back;
+            if (q < 0) q += wrap;
+            if (q >= wrap) q -= wrap;
+          }
+          zp[j] = zs[q];
+        }
       }
-      zp[k] = zs[p * lanes + cg];
-    }
 #pragma unroll
-    for (int k = 0; k < RT; ++k) x[k] = combine(R.a, x[k] - ge[k], R.ap, zp[k]);
-    if (R.read_y) {
+      for (int j = 0; j < KB; ++j)
+        if (k0 + j < RT) x[k0 + j] = combine(R.a, x[k0 + j], R.ap, zp[j]);
+      if (R.read_y) {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) y[k] = combine(R.b, y[k] - ge[k], R.bp, zp[k]);
-    } else {
+        for (int j = 0; j < KB; ++j)
+          if (k0 + j < RT) y[k0 + j] = combine(R.b, y[k0 + j], R.bp, zp[j]);
+      } else {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) y[k] = R.bp * zp[k];
+        for (int j = 0; j < KB; ++j)
+          if (k0 + j < RT) y[k0 + j] = R.bp * zp[j];
+      }
+      if (KB < RT) __builtin_amdgcn_sched_barrier(0);    // keep the batches apart
     }
     __syncthreads();
   }
   if (!on) return;
+  // the row addresses are worked out here, after the iterations: nothing of them occupies registers meanwhile
+  int rg_out = rg;
+  asm volatile("" : "+v"(rg_out));
 #pragma unroll
   for (int k = 0; k < RT; ++k) {
-    const int i = rg + k * M.row_lanes;
+    const int i = rg_out + k * M.row_lanes;
     if (i < M.n) {
       st_stream<V>(M.xout + (int64_t)i * M.ld + col, x[k]);
       st_stream<V>(M.yout + (int64_t)i * M.ld + col, y[k]);
@@ -236,31 +276,64 @@ __global__ __launch_bounds__(kBlock) void multi_step_kernel(const StepsArgs S) {
   }
 }
 
+template <int VEC, int RT, int THREADS>
+static hipError_t launch_steps(const StepsArgs& ss, unsigned blocks, size_t lds, hipStream_t st) {
+  if (lds > 64 * 1024) {
+    // more than 64 KB of LDS per workgroup has to be asked for
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&multi_step_kernel<VEC, RT, THREADS>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  multi_step_kernel<VEC, RT, THREADS><<<dim3(blocks), dim3(THREADS), lds, st>>>(ss);
+  return hipGetLastError();
+}
+
+// 256-thread workgroups: up to 16 rows per thread
+template <int VEC>
+static hipError_t launch_steps_256(const StepsArgs& ss, unsigned blocks, size_t lds, hipStream_t st) {
+  switch (ss.m.rows_per_thread) {
+#define CECA_RT(RT) case RT: return launch_steps<VEC, RT, 256>(ss, blocks, lds, st)
+    CECA_RT(1); CECA_RT(2); CECA_RT(3); CECA_RT(4); CECA_RT(5); CECA_RT(6); CECA_RT(7); CECA_RT(8);
+    CECA_RT(9); CECA_RT(10); CECA_RT(11); CECA_RT(12); CECA_RT(13); CECA_RT(14); CECA_RT(15); CECA_RT(16);
+#undef CECA_RT
+  }
+  return hipErrorInvalidValue;
+}
+
+// wider workgroups (16-byte groups only): x, y and c of up to kStepsWideRows rows fit their 128 registers
+template <int THREADS>
+static hipError_t launch_steps_wide(const StepsArgs& ss, unsigned blocks, size_t lds, hipStream_t st) {
+  switch (ss.m.rows_per_thread) {
+#define CECA_RT(RT) case RT: return launch_steps<4, RT, THREADS>(ss, blocks, lds, st)
+    CECA_RT(1); CECA_RT(2); CECA_RT(3); CECA_RT(4); CECA_RT(5); CECA_RT(6); CECA_RT(7); CECA_RT(8);
+#undef CECA_RT
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st) {
   const MultiArgs& m = s.m;
   if (m.ngroups <= 0) return hipSuccess;
-  const int lanes = kBlock / m.row_lanes;
+  const int threads = m.threads > 0 ? m.threads : kBlock;
+  if (threads != 256 && threads != 512 && threads != 1024) return hipErrorInvalidValue;
+  if (!vec4 && threads != 256) return hipErrorInvalidValue;          // scalar columns: 256-thread tiles only
+  if (m.row_lanes < 1 || m.row_lanes > threads || (m.row_lanes & (m.row_lanes - 1)) != 0) return hipErrorInvalidValue;
+  // the kernel relies on rows_per_thread being the least that covers n (only a thread's last row can
+  // lie past the last agent)
+  if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows ||
+      (int64_t)m.rows_per_thread * m.row_lanes < m.n || (int64_t)(m.rows_per_thread - 1) * m.row_lanes >= m.n)
+    return hipErrorInvalidValue;
+  const int lanes = threads / m.row_lanes;
   int64_t blocks = (m.ngroups + lanes - 1) / lanes;
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
   StepsArgs ss = s;
   ss.m.xcd_tiles = xcd_run(lanes * (vec4 ? 16 : 4), &blocks);
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
-  dim3 grid((unsigned)blocks), block(kBlock);
-#define CECA_STEPS4(RT) case RT: multi_step_kernel<4, RT><<<grid, block, lds, st>>>(ss); break
-#define CECA_STEPS1(RT) multi_step_kernel<1, RT><<<grid, block, lds, st>>>(ss)
-  if (m.rows_per_thread < 1 || m.rows_per_thread > kMultiRows) return hipErrorInvalidValue;
-  if (vec4) {
-    switch (m.rows_per_thread) {
-      CECA_STEPS4(1); CECA_STEPS4(2); CECA_STEPS4(3); CECA_STEPS4(4); CECA_STEPS4(5); CECA_STEPS4(6);
-      CECA_STEPS4(7); CECA_STEPS4(8); CECA_STEPS4(9); CECA_STEPS4(10); CECA_STEPS4(11); CECA_STEPS4(12);
-      CECA_STEPS4(13); CECA_STEPS4(14); CECA_STEPS4(15); CECA_STEPS4(16);
-    }
-  } else if (m.rows_per_thread <= 4) CECA_STEPS1(4);
-  else if (m.rows_per_thread <= 8) CECA_STEPS1(8);
-  else CECA_STEPS1(16);
-#undef CECA_STEPS4
-#undef CECA_STEPS1
-  return hipGetLastError();
+  if (lds > kMultiMaxLds) return hipErrorInvalidValue;
+  if (!vec4) return launch_steps_256<1>(ss, (unsigned)blocks, lds, st);
+  if (threads == 256) return launch_steps_256<4>(ss, (unsigned)blocks, lds, st);
+  if (threads == 512) return launch_steps_wide<512>(ss, (unsigned)blocks, lds, st);
+  return launch_steps_wide<1024>(ss, (unsigned)blocks, lds, st);
 }
 
 template <int VEC, int RT, int THREADS>

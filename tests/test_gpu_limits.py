@@ -48,18 +48,30 @@ def test_fused_rounds_around_the_agent_limit(env, n, port):
 
 @pytest.mark.parametrize("n,port", [(4096, 1), (4097, 2)])
 def test_fused_iterations_around_the_agent_limit(env, n, port):
+    """4096 agents still fit one workgroup's registers, 4097 do not.  With tile rows this narrow the library
+    fuses only long runs (15 iterations here) and takes short ones (5) step by step; setting the rows
+    option makes it fuse those too.  All give the same bits, and the oracle's values."""
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
-    d, seed, lr, std, steps = 21, 9, 0.1, 0.01, 5
+    d, seed, lr, std = 21, 9, 0.1, 0.01
     c = WL.quad_centers(n, d, seed)
     cdev = torch.from_numpy(c).cuda()
     x0 = WL.initial_state(n, d, seed)
-    A = make_state(torch, x0)
-    B = make_state(torch, np.zeros_like(x0))
-    P.dsgd_ceca_steps(A, B, n, d, Bn.make_quad_center_loss(cdev, std, seed, 2), lr, 2, steps, port)
-    gx, gy = split_state(B, n, d)
-    x, y = OC.run(x0, port, lr, OL.make_quad_center_grad(c, std, seed), steps, store32=True, k0=2)
-    assert max(rel_err(gx, x)) <= 1e-4 and max(rel_err(gy, y)) <= 1e-4
+    for steps in (5, 15):
+        outs = []
+        try:
+            for rows in (0, 16):
+                P.ceca_set_option(Bn.OPT_ROWS, rows)
+                A = make_state(torch, x0)
+                B = make_state(torch, np.zeros_like(x0))
+                P.dsgd_ceca_steps(A, B, n, d, Bn.make_quad_center_loss(cdev, std, seed, 2), lr, 2, steps, port)
+                outs.append(B)
+        finally:
+            P.ceca_set_option(Bn.OPT_ROWS, 0)
+        assert torch.equal(outs[0], outs[1])
+        gx, gy = split_state(outs[0], n, d)
+        x, y = OC.run(x0, port, lr, OL.make_quad_center_grad(c, std, seed), steps, store32=True, k0=2)
+        assert max(rel_err(gx, x)) <= 1e-4 and max(rel_err(gy, y)) <= 1e-4
 
 
 def test_mixing_rounds_at_the_agent_limit(env):
@@ -206,8 +218,8 @@ def test_more_rounds_than_one_kernel_takes(env):
 def test_workgroup_widths_of_the_fused_rounds_give_the_same_bits(env, n, port):
     """256-, 512- and 1024-thread workgroups of the fused-rounds kernel (tile rows of different widths, up
     to 144 KB of LDS), with the library's rows per thread and with fewer: same bits as single rounds, for
-    16-byte column groups with a scalar tail and for an unaligned layout; exact averaging and the mixing
-    rounds of the comparison topologies likewise (those against the oracle too)."""
+    16-byte column groups with a scalar tail and for an unaligned layout; exact averaging, fused iterations
+    and the mixing rounds of the comparison topologies likewise (those against the oracle too)."""
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
     tau = OS.num_rounds(n)
@@ -228,6 +240,13 @@ def test_workgroup_widths_of_the_fused_rounds_give_the_same_bits(env, n, port):
     topos = {"ring": [P.ceca_topology_round(Bn.TOPO_RING, n)], "static": [P.ceca_topology_round(Bn.TOPO_STATIC_EXP, n)],
              "one_peer": [P.ceca_topology_round(Bn.TOPO_ONE_PEER_EXP, n, k) for k in range(max(tau, 1))]}
     mixed = {}
+    # four iterations from round 1 with a state whose y matters, step by step
+    y0 = WL.initial_state(n, d, seed=n + 77)
+    cdev = torch.from_numpy(WL.quad_centers(n, d, 6)).cuda()
+    steps_ref = make_state(torch, x0, y0=y0)
+    for t in range(4):
+        P.dsgd_ceca_step(steps_ref, steps_ref, n, d, Bn.make_quad_center_loss(cdev, 0.01, 5, 3 + t), None, 0.1,
+                         (1 + t) % max(tau, 1), port)
     try:
         for threads in (256, 512, 1024):
             for rows in (0, 5):
@@ -244,6 +263,10 @@ def test_workgroup_widths_of_the_fused_rounds_give_the_same_bits(env, n, port):
                 X = torch.from_numpy(x0).cuda()
                 P.ceca_average(X, X, n, d, port)
                 assert torch.equal(X, avg_ref[:n]), (threads, rows, "average")
+                A = make_state(torch, x0, y0=y0)
+                B = torch.full_like(A, float("nan"))
+                P.dsgd_ceca_steps(A, B, n, d, Bn.make_quad_center_loss(cdev, 0.01, 5, 3), 0.1, 1 % max(tau, 1), 4, port)
+                assert torch.equal(B, steps_ref), (threads, rows, "steps")
                 for name, specs in topos.items():
                     X = torch.from_numpy(x0).cuda()
                     Y = torch.full_like(X, float("nan"))
