@@ -260,27 +260,20 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
 }
 
 
-// Tile of the fused gossip-rounds kernel: threads per workgroup, threads that share a column group
-// (a power of two) and rows of (x, y) per thread (the least that covers n); ok = false when no tile
-// holds n agents.
+// Tile of the register-tile kernels (fused rounds, fused iterations, mixing): threads per workgroup,
+// threads that share a column group (a power of two) and rows per thread (the least that covers n);
+// ok = false when no such tile holds n agents.
 struct TileShape {
   int32_t threads, row_lanes, rows_per_thread;
   bool ok;
+  // bytes of one agent's row inside the tile
+  int32_t row_bytes(bool vec4) const { return (threads / std::max(row_lanes, 1)) * (vec4 ? 16 : 4); }
 };
 
-TileShape rounds_tile_for(int32_t n, bool vec4, bool knobs) {
+// The tile with at most `cap` rows per thread: the fewest row lanes that cover n give the widest rows.
+TileShape shape_tile(int32_t n, bool vec4, int32_t threads, int32_t cap) {
   TileShape t{};
-  int32_t cap = knobs ? g_opt_rows.load() : 0;
-  const bool cap_given = cap >= 4 && cap <= ceca::kMultiRows;
-  t.threads = vec4 ? (knobs ? g_opt_tile_threads.load() : 0) : ceca::kBlock;
-  // Measured on MI355X (n = 31 ... 4096): 512-thread workgroups with up to 9 rows per thread (128
-  // registers: two workgroups per compute unit) make the rows of the tile two to four times wider than
-  // 256-thread ones and run 1.1x (n = 31) to 3x (n = 1026) faster; beyond 9 x 128 agents only a
-  // 1024-thread workgroup keeps the rows at 64 bytes (4.6x at n = 2050).
-  if (t.threads == 0) t.threads = n > 9 * 128 ? 1024 : 512;
-  // 256-thread tiles: 8 rows leave room for twice as many workgroups per CU as 16 (1.5x faster at
-  // n = 100) as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
-  if (!cap_given) cap = t.threads == ceca::kBlock ? (n <= 256 ? 8 : ceca::kMultiRows) : 9;
+  t.threads = threads;
   t.row_lanes = 1;
   while ((int64_t)t.row_lanes * cap < n) t.row_lanes *= 2;
   t.rows_per_thread = (n + t.row_lanes - 1) / t.row_lanes;
@@ -289,11 +282,68 @@ TileShape rounds_tile_for(int32_t n, bool vec4, bool knobs) {
   return t;
 }
 
-// The tile the option knobs ask for when it holds n agents, else the library's own choice (which holds
-// up to 4096).
+// A kernel's tile policy: threads per workgroup for n agents, and the most rows per thread for that
+// width.  The option knobs override it when the tile they ask for holds n agents (scalar columns always
+// run 256-thread workgroups).
+template <typename Threads, typename Cap>
+TileShape pick_tile(int32_t n, bool vec4, int32_t cap_lo, int32_t cap_hi_256, int32_t cap_hi_wide, Threads threads_for, Cap cap_for) {
+  const int32_t dflt_threads = vec4 ? threads_for(n) : ceca::kBlock;
+  const TileShape dflt = shape_tile(n, vec4, dflt_threads, cap_for(dflt_threads));
+  int32_t threads = vec4 ? g_opt_tile_threads.load() : ceca::kBlock;
+  if (threads == 0) threads = dflt_threads;
+  int32_t cap = g_opt_rows.load();
+  if (cap < cap_lo || cap > (threads == ceca::kBlock ? cap_hi_256 : cap_hi_wide)) cap = cap_for(threads);
+  const TileShape t = shape_tile(n, vec4, threads, cap);
+  return t.ok ? t : dflt;
+}
+
+// Fused gossip rounds (x and y of every row in registers).
 TileShape rounds_tile(int32_t n, bool vec4) {
-  const TileShape t = rounds_tile_for(n, vec4, true);
-  return t.ok ? t : rounds_tile_for(n, vec4, false);
+  // Measured on MI355X (n = 31 ... 4096): 512-thread workgroups with up to 9 rows per thread (128
+  // registers: two workgroups per compute unit) make the rows of the tile two to four times wider than
+  // 256-thread ones and run 1.1x (n = 31) to 3x (n = 1026) faster; beyond 9 x 128 agents only a
+  // 1024-thread workgroup keeps the rows at 64 bytes (4.6x at n = 2050).
+  // 256-thread tiles: 8 rows leave room for twice as many workgroups per CU as 16 (1.5x faster at
+  // n = 100) as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
+  return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows,
+                   [](int32_t m) { return m > 9 * 128 ? 1024 : 512; },
+                   [n](int32_t threads) { return threads == ceca::kBlock ? (n <= 256 ? 8 : ceca::kMultiRows) : 9; });
+}
+
+// Fused iterations (x, y and c of every row in registers).
+TileShape steps_tile(int32_t n, bool vec4, int32_t steps) {
+  // With noise the kernel is bound by the generator's arithmetic: few rows per thread (small register
+  // footprint, many resident wavefronts) measured best on MI355X.  More agents need wider workgroups
+  // to keep a row of the tile 64 bytes wide: x, y and c of 5 rows fit the 128 registers of a 512-thread
+  // (two per compute unit) or 1024-thread workgroup.  Measured against 256-thread tiles, 4 iterations,
+  // 2^26 elements: n = 258 0.19 -> 0.13 ms, n = 640 0.27 -> 0.23, n = 1026 0.72 -> 0.26, n = 2050
+  // 1.39 -> 0.62.
+  return pick_tile(n, vec4, 1, ceca::kMultiRows, 8,
+                   [](int32_t m) { return m <= 128 ? ceca::kBlock : (m <= 5 * 128 ? 512 : 1024); },
+                   [n, steps](int32_t threads) {
+                     if (threads != ceca::kBlock) return 5;
+                     if (n <= 128) return 4;
+                     if (n <= 512) return 8;
+                     return (steps <= 16 || n > 8 * ceca::kBlock) ? 16 : 8;     // 8 rows x 256 row lanes hold 2048 agents
+                   });
+}
+
+// Mixing rounds of the comparison topologies (x of every row in registers); heavy = four or more
+// peers in some round.
+TileShape mix_tile(int32_t n, bool vec4, bool heavy) {
+  // Measured on MI355X (n = 31 ... 4096, all three topologies): 256-thread workgroups are best up to
+  // about 512 agents; 512-thread ones (13 rows per thread in 128 registers, two per compute unit) gain
+  // 1.2x at n = 1026, and beyond 13 x 128 agents a 1024-thread workgroup keeps the rows of the tile at
+  // 64 bytes (1.7x at n = 2050, 2.5x at n = 4096).
+  // 256 threads (n = 31, 130, 258, 1026): one or two peers per round want wide row segments, many
+  // peers per round (LDS-read bound) want more resident workgroups
+  return pick_tile(n, vec4, 4, 32, 16,
+                   [](int32_t m) { return m <= 512 ? ceca::kBlock : (m <= 13 * 128 ? 512 : 1024); },
+                   [n, heavy](int32_t threads) {
+                     return threads != ceca::kBlock
+                                ? 13
+                                : n <= 32 ? 12 : (n <= 192 ? (heavy ? 8 : 16) : (n <= 512 ? 16 : (heavy ? 16 : 24)));
+                   });
 }
 
 }  // namespace
@@ -391,7 +441,7 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
   // A single round is the streaming kernel's job, and tiles with rows narrower than a 128-byte line pay
   // off only over a few rounds (measured: the fused pass costs about 1.5, 2.5 and 4.7 single rounds at
   // n = 1026, 2050 and 4096).
-  const int32_t row_bytes = can_vec ? (tv.threads / std::max(tv.row_lanes, 1)) * 16 : (ts.threads / std::max(ts.row_lanes, 1)) * 4;
+  const int32_t row_bytes = can_vec ? tv.row_bytes(true) : ts.row_bytes(false);
   const int32_t worth = row_bytes >= 64 ? (tv.threads == 1024 && can_vec ? 3 : 2) : 5;
   const bool knobs = g_opt_rows.load() != 0 || g_opt_tile_threads.load() != 0;
   // (rounds after the first run in place on S_out: with two ports those walk whole cycles, which needs
@@ -689,35 +739,12 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
   if (overlaps(loss->c, cbytes, S_out, sbytes)) return fail(CECA_EINVAL, "centres overlap S_out");
   hipStream_t st = (hipStream_t)hip_stream;
   const int32_t tau = ceca::tau_of(n);
-  // The tile holds x, y and c, and with noise the kernel is bound by the generator's arithmetic: few rows
-  // per thread (small register footprint, many resident wavefronts) measured best on MI355X.  More
-  // agents need wider workgroups to keep a row of the tile 64 bytes wide: x, y and c of 5 rows fit the
-  // 128 registers of a 512-thread (two per compute unit) or 1024-thread workgroup.  Measured against
-  // 256-thread tiles, 4 iterations, 2^26 elements: n = 258 0.19 -> 0.13 ms, n = 640 0.27 -> 0.23,
-  // n = 1026 0.72 -> 0.26, n = 2050 1.39 -> 0.62.
-  auto tile = [&](bool vec4, bool knobs) {
-    TileShape t{};
-    int32_t cap = knobs ? g_opt_rows.load() : 0;
-    t.threads = vec4 ? (knobs ? g_opt_tile_threads.load() : 0) : ceca::kBlock;
-    if (t.threads == 0) t.threads = n <= 128 ? ceca::kBlock : (n <= 5 * 128 ? 512 : 1024);
-    const int32_t cap_max = t.threads == ceca::kBlock ? ceca::kMultiRows : 8;
-    if (cap < 1 || cap > cap_max)
-      cap = t.threads != ceca::kBlock ? 5 : (n <= 128 ? 4 : (n <= 512 ? 8 : (steps <= 16 ? 16 : 8)));
-    t.row_lanes = 1;
-    while ((int64_t)t.row_lanes * cap < n) t.row_lanes *= 2;
-    t.rows_per_thread = (n + t.row_lanes - 1) / t.row_lanes;
-    const int64_t lds = t.row_lanes <= t.threads ? (int64_t)n * (t.threads / t.row_lanes) * (vec4 ? 16 : 4) : 0;
-    t.ok = t.row_lanes <= t.threads && lds <= (int64_t)ceca::kMultiMaxLds;
-    return t;
-  };
-  TileShape tv = tile(true, true), ts = tile(false, true);
-  if (!tv.ok) tv = tile(true, false);
-  if (!ts.ok) ts = tile(false, false);
+  const TileShape tv = steps_tile(n, true, steps), ts = steps_tile(n, false, steps);
   const bool can_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0 && aligned16(loss->c) && loss->ldc % 4 == 0;
   // A tile row narrower than a 128-byte line reads and writes HBM several times less efficiently than
   // the streaming single-step kernel, which only pays off over enough iterations (measured at n = 1026,
   // 2050, 4096: the fused pass costs about 2, 6 and 11 single steps at 64, 32 and 16 bytes).
-  const int32_t row_bytes = can_vec ? (tv.threads / std::max(tv.row_lanes, 1)) * 16 : (ts.threads / std::max(ts.row_lanes, 1)) * 4;
+  const int32_t row_bytes = can_vec ? tv.row_bytes(true) : ts.row_bytes(false);
   const int32_t worth = row_bytes >= 128 ? 1 : (row_bytes >= 64 ? 3 : (row_bytes >= 32 ? 8 : 14));
   // (the steps after the first run in place on S_out: with two ports those walk whole cycles, which
   // needs many column tiles to fill the device)
@@ -805,37 +832,9 @@ int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, i
   m.start[period] = total;
   m.xin = X_in;  m.xout = X_out;  m.ld = ld;
   m.n = n;  m.rounds = rounds;  m.period = period;  m.k0 = k0 % period;
-  // Tile shape: a thread keeps up to `cap` rows; the fewest row lanes (a power of two) that cover n
-  // rows give the widest row segments, and the row count is then trimmed to what n needs.
   int32_t most = 0;
   for (int32_t q = 0; q < period; ++q) most = std::max(most, specs[q].m);
-  const bool heavy = most >= 4;
-  auto tile = [&](bool vec4, bool knobs) {
-    TileShape t{};
-    int32_t cap = knobs ? g_opt_rows.load() : 0;
-    t.threads = vec4 ? (knobs ? g_opt_tile_threads.load() : 0) : ceca::kBlock;
-    // measured on MI355X (n = 31 ... 4096, all three topologies): 256-thread workgroups are best up to
-    // about 512 agents; 512-thread ones (13 rows per thread in 128 registers, two per compute unit) gain
-    // 1.2x at n = 1026, and beyond 13 x 128 agents a 1024-thread workgroup keeps the rows of the tile at
-    // 64 bytes (1.7x at n = 2050, 2.5x at n = 4096)
-    if (t.threads == 0) t.threads = n <= 512 ? ceca::kBlock : (n <= 13 * 128 ? 512 : 1024);
-    const int32_t cap_max = t.threads == ceca::kBlock ? 32 : 16;
-    if (cap < 4 || cap > cap_max) {
-      // 256 threads (n = 31, 130, 258, 1026): one or two peers per round want wide row segments, many
-      // peers per round (LDS-read bound) want more resident workgroups
-      cap = t.threads != ceca::kBlock ? 13
-                                      : n <= 32 ? 12 : (n <= 192 ? (heavy ? 8 : 16) : (n <= 512 ? 16 : (heavy ? 16 : 24)));
-    }
-    t.row_lanes = 1;
-    while ((int64_t)t.row_lanes * cap < n) t.row_lanes *= 2;
-    t.rows_per_thread = (n + t.row_lanes - 1) / t.row_lanes;
-    const int64_t lds = t.row_lanes <= t.threads ? (int64_t)n * (t.threads / t.row_lanes) * (vec4 ? 16 : 4) : 0;
-    t.ok = t.row_lanes <= t.threads && lds <= (int64_t)ceca::kMultiMaxLds;
-    return t;
-  };
-  TileShape tv = tile(true, true), ts = tile(false, true);
-  if (!tv.ok) tv = tile(true, false);
-  if (!ts.ok) ts = tile(false, false);
+  const TileShape tv = mix_tile(n, true, most >= 4), ts = mix_tile(n, false, most >= 4);
   if (!tv.ok || !ts.ok) return fail(CECA_EINVAL, "internal: no tile holds n = %d agents", n);
   hipStream_t st = (hipStream_t)hip_stream;
   const bool can_vec = aligned16(X_in) && aligned16(X_out) && ld % 4 == 0;

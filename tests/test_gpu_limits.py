@@ -282,3 +282,20 @@ def test_workgroup_widths_of_the_fused_rounds_give_the_same_bits(env, n, port):
     for name, specs in otop.items():
         want = OT.run(x0, specs, 3, k0=1)
         assert max(rel_err(mixed[name].cpu().numpy(), want)) <= 1e-5, name
+
+
+def test_long_fused_runs_on_many_agents_with_an_unaligned_layout(env):
+    """More than 2048 agents, more than 16 iterations, rows that are not 16-byte aligned (scalar column
+    groups, 256-thread tiles of 16 rows): same bits as single steps."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, port, steps = 3000, 9, 1, 20
+    tau = OS.num_rounds(n)
+    x0 = WL.initial_state(n, d, seed=12)
+    cdev = torch.from_numpy(WL.quad_centers(n, d, 13)).cuda()
+    A = make_state(torch, x0, ld=d + 2, offset=1)
+    B = make_state(torch, x0, ld=d + 2, offset=1)
+    P.dsgd_ceca_steps(A, A, n, d, Bn.make_quad_center_loss(cdev, 0.01, 2, 0), 0.1, 0, steps, port, ld=d + 2)
+    for t in range(steps):
+        P.dsgd_ceca_step(B, B, n, d, Bn.make_quad_center_loss(cdev, 0.01, 2, t), None, 0.1, t % tau, port, ld=d + 2)
+    assert torch.equal(A[:, :d], B[:, :d])
