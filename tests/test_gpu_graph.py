@@ -128,3 +128,48 @@ def test_graph_of_the_multi_iteration_calls(env):
         assert np.isfinite(torch.randn(1024, device="cuda").sum().item())      # unrelated eager work in between
         assert np.array_equal(S2.cpu().numpy(), eager[rep][0]), rep
         assert np.array_equal(out2.cpu().numpy(), eager[rep][1]), rep
+
+
+def test_graph_of_the_wide_workgroup_kernels(env):
+    """More than 1000 agents: the fused rounds, fused iterations and mixing kernels run 512- and 1024-thread
+    workgroups with more than 64 KB of LDS each (asked for per launch); captured in a graph, every replay
+    equals the eager run."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, port = 1026, 132, 2
+    tau = OS.num_rounds(n)
+    c = torch.from_numpy(WL.quad_centers(n, d, 4)).cuda()
+    qloss = Bn.make_quad_center_loss(c, 0.01, 5, 0)
+    one_peer = [P.ceca_topology_round(Bn.TOPO_ONE_PEER_EXP, n, k) for k in range(tau)]
+    x0 = WL.initial_state(n, d, 8)
+
+    def window(S):
+        P.dsgd_ceca_steps(S, S, n, d, qloss, 0.05, 0, 4, port)
+        P.ceca_mix_rounds(S[:n], S[:n], n, d, one_peer, 3)
+        P.ceca_gossip_rounds(S, S, n, d, tau - 1, port)
+        P.ceca_average(S[n:], S[n:], n, d, port)
+
+    replays = 3
+    S = make_state(torch, x0)
+    eager = []
+    for _ in range(replays):
+        window(S)
+        torch.cuda.synchronize()
+        eager.append(S.cpu().numpy().copy())
+    S2 = make_state(torch, x0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        window(S2)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    S2.copy_(make_state(torch, x0))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        window(S2)
+    S2.copy_(make_state(torch, x0))
+    for rep in range(replays):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.isfinite(torch.randn(1024, device="cuda").sum().item())      # unrelated eager work in between
+        assert np.array_equal(S2.cpu().numpy(), eager[rep]), rep
