@@ -16,6 +16,7 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
+EAGER_ONLY = False      # --eager-only: minibatch workloads skip the HIP-graph and multi-iteration legs
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -219,6 +220,11 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
         for k in range(warmup, warmup + steps):
             step(k)
     tm.final = consensus_report(torch, P, S[:n], n, d, ld)      # after warmup + steps iterations from x(0) = 0
+    one_kernel_gradient = (d % 4 == 0 and ((n >= 128 and 1024 < d <= 16384) or (B <= 32 and d <= 1024) or (B <= 16 and d <= 4096)
+                                           or (B <= 8 and d <= 8192) or (B <= 4 and d <= 16384))) or (d % 4 != 0 and d <= 1024)
+    launches = 2 if one_kernel_gradient else 3
+    if EAGER_ONLY:
+        return tm, launches, minibatch_bytes(B)
     # launch-bound loops: the same iterations captured once as a HIP graph and replayed
     window = 2 * tau * max(1, 16 // tau)          # even number of steps: two-port buffers end where they began
     side = torch.cuda.Stream()
@@ -258,10 +264,6 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
             run_windows()
         tm.run_ms_per_step = tr.event_ms / (calls * K)
         tm.run_iterations_per_call = K
-    # one-pass gradient + combine when the sampled rows fit the register tile, else margins + half step + combine
-    one_kernel_gradient = (d % 4 == 0 and ((n >= 128 and 1024 < d <= 16384) or (B <= 32 and d <= 1024) or (B <= 16 and d <= 4096)
-                                           or (B <= 8 and d <= 8192) or (B <= 4 and d <= 16384))) or (d % 4 != 0 and d <= 1024)
-    launches = 2 if one_kernel_gradient else 3
     return tm, launches, minibatch_bytes(B)
 
 
@@ -412,9 +414,14 @@ def main():
     ap.add_argument("--mix-only", action="store_true",
                     help="time only the comparison-topology gossip rounds (n = 130 and n = 1026) and exit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--eager-only", action="store_true",
+                    help="minibatch workloads: time the eager steps only (no HIP-graph replay, no multi-iteration calls); "
+                         "for hardware-counter passes")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run one plain 1 GiB device copy (calibrates rocprofv3 byte counters)")
     args = ap.parse_args()
+    global EAGER_ONLY
+    EAGER_ONLY = args.eager_only
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all agents are simulated on one device); "
               "--gpus must be 1", file=sys.stderr)
