@@ -83,6 +83,24 @@ def test_noise_distribution():
     assert np.isfinite(e).all() and np.abs(e).max() < 6.0          # u1 >= 2^-24 bounds the radius
 
 
+def test_noise_follows_the_normal_law():
+    """Kolmogorov-Smirnov distance to the standard normal CDF (scipy's), for one stream and for a column
+    taken across many agents and iterations; the integer mix is a bijection of 32-bit words (invertible
+    steps: xor-shift, odd multiplier), so distinct counters of one stream give distinct words."""
+    from scipy import stats
+    e = noise.normals(5, 3, 1, np.arange(200_000))
+    assert stats.kstest(e, "norm").statistic < 4e-3                 # 1.36 / sqrt(2e5) = 3.0e-3 at the 5 % level
+    across = np.array([noise.normals(5, k, i, np.array([17]))[0] for k in range(60) for i in range(60)])
+    assert stats.kstest(across, "norm").statistic < 3.5e-2          # 3600 samples: 2.3e-2 at the 5 % level
+    k0, k1 = noise.stream_keys(5, 3, 1)
+    words = noise._word(np.arange(1 << 20, dtype=np.uint32), k0, k1)
+    assert np.unique(words).size == 1 << 20
+    assert np.unique(noise._mix(np.arange(1 << 20, dtype=np.uint32))).size == 1 << 20
+    # both halves of the word feed the uniforms: high 24 bits, uniformly spread over 256 buckets
+    hist = np.bincount((words >> np.uint32(24)).astype(np.int64), minlength=256)
+    assert abs(hist - 4096).max() < 6 * 64                          # binomial sd = 64
+
+
 def test_noise_is_a_pure_function_of_its_counter():
     cols = np.array([0, 1, 5, 4, 1000001, 1000000, 25_557_031])
     a = noise.normals(11, 49, 30, cols)
