@@ -299,15 +299,20 @@ TileShape pick_tile(int32_t n, bool vec4, int32_t cap_lo, int32_t cap_hi_256, in
 
 // Fused gossip rounds (x and y of every row in registers).
 TileShape rounds_tile(int32_t n, bool vec4) {
-  // Measured on MI355X (n = 16 ... 4096): up to 256 agents 256-thread workgroups already have rows of
-  // 128 bytes and are 0-10 % ahead; beyond, 512-thread workgroups with up to 9 rows per thread (128
-  // registers: two workgroups per compute unit) make the rows of the tile two to four times wider and
-  // run 1.25x (n = 258) to 3x (n = 1026) faster; beyond 9 x 128 agents only a 1024-thread workgroup
-  // keeps the rows at 64 bytes (4.6x at n = 2050).
+  // Measured on MI355X (n = 16 ... 4096): 512-thread workgroups with up to 9 rows per thread (128
+  // registers: two workgroups per compute unit) make the rows of the tile two to four times wider than
+  // 256-thread ones and run 1.25x (n = 130, 258) to 3x (n = 1026) faster; beyond 9 x 128 agents only a
+  // 1024-thread workgroup keeps the rows at 64 bytes (4.6x at n = 2050).  Up to 256 agents, when 9 rows
+  // per thread need as many row lanes as 8 do, the 256-thread tile has the same rows per thread at
+  // half the width (still >= 128 bytes) and measured 0-10 % ahead (n = 16 ... 200).
   // 256-thread tiles: 8 rows leave room for twice as many workgroups per CU as 16 (1.5x faster at
   // n = 100) as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
   return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows,
-                   [](int32_t m) { return m <= 256 ? ceca::kBlock : (m <= 9 * 128 ? 512 : 1024); },
+                   [](int32_t m) {
+                     if (m > 9 * 128) return 1024;
+                     const bool same_lanes = shape_tile(m, true, 512, 9).row_lanes == shape_tile(m, true, ceca::kBlock, 8).row_lanes;
+                     return (m <= 256 && same_lanes) ? ceca::kBlock : 512;
+                   },
                    [n](int32_t threads) { return threads == ceca::kBlock ? (n <= 256 ? 8 : ceca::kMultiRows) : 9; });
 }
 
