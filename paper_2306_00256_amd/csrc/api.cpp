@@ -297,8 +297,9 @@ TileShape pick_tile(int32_t n, bool vec4, int32_t cap_lo, int32_t cap_hi_256, in
   return t.ok ? t : dflt;
 }
 
-// Fused gossip rounds (x and y of every row in registers).
-TileShape rounds_tile(int32_t n, bool vec4) {
+// Fused gossip rounds (x and y of every row in registers); with_y = false: exact averaging, which
+// stores no y.
+TileShape rounds_tile(int32_t n, bool vec4, bool with_y = true) {
   // Measured on MI355X (n = 16 ... 4096): 512-thread workgroups with up to 9 rows per thread (128
   // registers: two workgroups per compute unit) make the rows of the tile two to four times wider than
   // 256-thread ones and run 1.25x (n = 130, 258) to 3x (n = 1026) faster; beyond 9 x 128 agents only a
@@ -307,6 +308,11 @@ TileShape rounds_tile(int32_t n, bool vec4) {
   // half the width (still >= 128 bytes) and measured 0-10 % ahead (n = 16 ... 200).
   // 256-thread tiles: 8 rows leave room for twice as many workgroups per CU as 16 (1.5x faster at
   // n = 100) as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
+  // Exact averaging writes a third of the bytes: up to 128 agents 5 rows per thread (rows of the tile
+  // still >= 128 bytes, twice the resident workgroups) measured 5-10 % ahead (n = 31, 64, 100).
+  if (!with_y && n <= 128)
+    return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows, [](int32_t) { return ceca::kBlock; },
+                     [](int32_t threads) { return threads == ceca::kBlock ? 5 : 9; });
   return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows,
                    [](int32_t m) {
                      if (m > 9 * 128) return 1024;
@@ -507,7 +513,7 @@ int32_t ceca_average(const float* X_in, float* X_out, int32_t n, int64_t d, int6
     return fail(CECA_EINVAL, "X_out partially overlaps X_in");
   hipStream_t st = (hipStream_t)hip_stream;
   const int32_t tau = ceca::tau_of(n);
-  const TileShape tv = rounds_tile(n, true), ts = rounds_tile(n, false);
+  const TileShape tv = rounds_tile(n, true, false), ts = rounds_tile(n, false, false);
   if (!tv.ok || !ts.ok) return fail(CECA_EINVAL, "internal: no tile holds n = %d agents", n);
   ceca::MultiArgs m{};
   m.xin = X_in;
