@@ -123,6 +123,16 @@ def run_quad(torch, P, Bn, sp, steps, warmup):
         for _ in range(10):
             P.ceca_stream_probe(pa, pb, c.reshape(-1), po1, po2, cnt)
     tm.probe = {"stream_probe_ms": tp.event_ms / 10, "stream_probe_GBs": 20.0 * cnt / (tp.event_ms / 10 * 1e-3) / 1e9}
+    # the same step with gradients the caller supplies (any loss, e.g. from autograd): same traffic, no noise
+    # arithmetic; c stands in for the gradient rows
+    gl = Bn.make_gradient_loss(c)
+    tc = Timer(torch)
+    with tc:
+        for k in range(2 * tau):
+            P.dsgd_ceca_step(S, T, n, d, gl, None, sp.lr, k % tau, port, ld=ld)
+            if port == 2:
+                S, T = T, S
+    tm.probe["caller_gradient_step_ms"] = tc.event_ms / (2 * tau)
     S.zero_()
     # the same iterations fused: up to 50 per dsgd_ceca_steps call (same bits as the calls above), 20 bytes
     # per agent-parameter per call; bound by the noise generator's arithmetic, not by HBM
@@ -480,7 +490,7 @@ def main():
         },
     }
     details = {k: main_res[k] for k in ("graph_replay_ms_per_step", "run_call_ms_per_step", "run_iterations_per_call",
-                                        "fused_rounds", "fused_ms", "fused_GBs_on_12B",
+                                        "fused_rounds", "fused_ms", "fused_GBs_on_12B", "caller_gradient_step_ms",
                                         "max_dev_over_mean_norm_after_round", "consensus_after_timed_steps")
                if k in main_res}
     if details:

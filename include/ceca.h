@@ -40,7 +40,7 @@ enum {
   CECA_EHIP = -4        /* a HIP runtime call failed; see ceca_last_hip_error() */
 };
 
-enum { CECA_LOSS_LSQ = 0, CECA_LOSS_LOGISTIC = 1, CECA_LOSS_QUAD_CENTER = 2 };
+enum { CECA_LOSS_LSQ = 0, CECA_LOSS_LOGISTIC = 1, CECA_LOSS_QUAD_CENTER = 2, CECA_LOSS_GRADIENT = 3 };
 
 /* One CECA round, as Algorithm 1 uses it (Sec. 3.1 Eqs. (2), (3); Sec. 4.1). */
 typedef struct {
@@ -63,6 +63,9 @@ typedef struct {
  *               experiment of Sec. 5: full gradient of 1/2 ||A_i x - b_i||^2 plus N(0, sigma_n^2 I))
  *   LOGISTIC    e_i = -s sum_j t_ij sigma(-t_ij a_ij . z_i) a_ij + noise_std * eps_i,  labels t_ij = +-1
  *   QUAD_CENTER e_i = z_i - c_i + noise_std * eps_i
+ *   GRADIENT    e_i = row i of c: the caller evaluated the stochastic gradient of any loss at z_i (the x
+ *               row when ceca_schedule's exchange_y is 0, the y row when it is 1) and passes it in;
+ *               N, B, seed, k, noise_std, grad_scale, A, t are ignored
  * eps_i ~ N(0, I) comes from the counter-based generator below, keyed by (seed, k, agent, column).
  *
  * Noise generator (uint32 arithmetic, wrapping; agent and column 0-based):
@@ -84,7 +87,7 @@ typedef struct {
   const float* A;       /* device, n*N rows of lda floats: row i*N + j is sample j of agent i */
   int64_t lda;          /* >= d */
   const float* t;       /* device, n*N floats: targets (LSQ) or labels +-1 (LOGISTIC) */
-  const float* c;       /* device, n rows of ldc floats: centres (QUAD_CENTER) */
+  const float* c;       /* device, n rows of ldc floats: centres (QUAD_CENTER) or gradients (GRADIENT) */
   int64_t ldc;          /* >= d */
 } ceca_loss_t;
 

@@ -9,7 +9,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libceca.so")
 
 CECA_OK, CECA_EINVAL, CECA_EODD1P, CECA_EWORKSPACE, CECA_EHIP = 0, -1, -2, -3, -4
-LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER = 0, 1, 2
+LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER, LOSS_GRADIENT = 0, 1, 2, 3
 OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS, OPT_AGENTS_PER_WG, OPT_CONS_SINGLE_PASS, OPT_XCD_TILE_ORDER, OPT_TILE_THREADS = 1, 2, 3, 4, 5, 7, 8, 9, 10
 TOPO_RING, TOPO_STATIC_EXP, TOPO_ONE_PEER_EXP = 0, 1, 2
 MIX_MAX = 16
@@ -243,3 +243,10 @@ def make_quad_center_loss(c, noise_std: float, seed: int, k: int = 0) -> Loss:
     """c: device (n, ldc) float32 centres."""
     return Loss(kind=LOSS_QUAD_CENTER, N=0, B=0, seed=seed & 0xFFFFFFFF, k=k & 0xFFFFFFFF, noise_std=noise_std,
                 grad_scale=0.0, A=None, lda=0, t=None, c=_ptr(c), ldc=int(c.stride(0)))
+
+
+def make_gradient_loss(e) -> Loss:
+    """e: device (n, ldc) float32, row i = agent i's stochastic gradient evaluated by the caller at z_i (the x
+    row when the round's exchange_y is 0, the y row when it is 1)."""
+    return Loss(kind=LOSS_GRADIENT, N=0, B=0, seed=0, k=0, noise_std=0.0, grad_scale=0.0, A=None, lda=0, t=None,
+                c=_ptr(e), ldc=int(e.stride(0)))

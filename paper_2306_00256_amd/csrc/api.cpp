@@ -112,7 +112,8 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   // variant (it also runs fewer workgroups per CU); one-row stretches want more, lighter workgroups
   // round 0 of the fused step (y not read: half the traffic is writes) measured best with the lightest
   // variant, two-row stretches, wider bands and at most 4 workgroups per CU
-  const bool quad_round0 = mode == ceca::MODE_QUAD && !a.read_y && !(pairs || in_place);
+  const bool fused_step = mode == ceca::MODE_QUAD || mode == ceca::MODE_GRAD;     // x, y and one more array stream in
+  const bool quad_round0 = fused_step && !a.read_y && !(pairs || in_place);
   // a state that stays in the last-level cache (minibatch losses on many small agents) is not a
   // streaming problem: measured on MI355X at n = 1023, d = 4096, 16-row stretches with two rows in
   // flight beat one-row stretches (fewer, longer workgroups; 18.5 -> 14 us for the combine)
@@ -122,7 +123,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
                       2 * (int64_t)a.n * a.ld * (int64_t)sizeof(float) <= (64LL << 20) &&
                       (int64_t)a.n * ((d + 4 * ceca::kBlock - 1) / (4 * ceca::kBlock)) >= 2048;
   const int32_t default_seg = quad_round0 ? 2 : (cached ? 16 : 1);
-  if (rows == 0) rows = quad_round0 ? 1 : cached ? 2 : (mode == ceca::MODE_QUAD && (pairs || in_place)) ? 8 : 4;
+  if (rows == 0) rows = quad_round0 ? 1 : cached ? 2 : (fused_step && (pairs || in_place)) ? 8 : 4;
   if (cached && a.band == 0) a.band = 2;
   if (quad_round0) {
     if (a.band == 0) a.band = 512;
@@ -132,7 +133,7 @@ int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ce
   // re-read hits L2 (32 MB over 8 XCDs; a tile and its successor land on the same XCD when the band
   // is a multiple of 8)
   // closed stretches re-read nothing: they sweep whole rows, one pair or cycle after the other
-  if (a.band == 0 && !(pairs || in_place)) a.band = (mode == ceca::MODE_QUAD) ? 256 : 512;
+  if (a.band == 0 && !(pairs || in_place)) a.band = fused_step ? 256 : 512;
   const int64_t d4 = can_vec ? d / 4 : 0;
   if (d4 > 0) {
     a.col0 = 0;
@@ -195,6 +196,9 @@ int32_t check_loss(const ceca_loss_t* loss, int64_t d, bool need_batch, const in
     case CECA_LOSS_QUAD_CENTER:
       if (!loss->c || loss->ldc < d) return fail(CECA_EINVAL, "quadratic-centre loss needs c and ldc >= d");
       if (!(loss->noise_std >= 0.0f)) return fail(CECA_EINVAL, "noise_std must be >= 0");
+      return CECA_OK;
+    case CECA_LOSS_GRADIENT:
+      if (!loss->c || loss->ldc < d) return fail(CECA_EINVAL, "caller-supplied gradients need c and ldc >= d");
       return CECA_OK;
     default:
       return fail(CECA_EINVAL, "unknown loss kind %d", loss->kind);
@@ -548,7 +552,7 @@ int64_t dsgd_ceca_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* loss)
   if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
   const int32_t rc = check_loss(loss, d, false, nullptr);
   if (rc != CECA_OK) return rc;
-  if (loss->kind == CECA_LOSS_QUAD_CENTER) return 0;
+  if (loss->kind == CECA_LOSS_QUAD_CENTER || loss->kind == CECA_LOSS_GRADIENT) return 0;
   const GemvPlan p = gemv_plan(n, d, loss->B);
   return p.v_bytes + p.partial_bytes;
 }
@@ -572,15 +576,16 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   set_weights(rd, n, /*gossip_only=*/false, &a);
   const bool state_vec = aligned16(S_in) && aligned16(S_out) && ld % 4 == 0;
 
-  if (loss->kind == CECA_LOSS_QUAD_CENTER) {
+  if (loss->kind == CECA_LOSS_QUAD_CENTER || loss->kind == CECA_LOSS_GRADIENT) {
     const int64_t sbytes = 2 * (int64_t)n * ld * 4, cbytes = (int64_t)n * loss->ldc * 4;
-    if (overlaps(loss->c, cbytes, S_out, sbytes)) return fail(CECA_EINVAL, "centres overlap S_out");
+    if (overlaps(loss->c, cbytes, S_out, sbytes)) return fail(CECA_EINVAL, "centres or gradients overlap S_out");
     a.aux = loss->c;
     a.ldaux = loss->ldc;
+    const bool can_vec = state_vec && aligned16(loss->c) && loss->ldc % 4 == 0;
+    if (loss->kind == CECA_LOSS_GRADIENT) return run_chain(a, ceca::MODE_GRAD, d, can_vec, rd, port, st);
     a.noise_std = loss->noise_std;
     a.seed = loss->seed;
     a.k = loss->k;
-    const bool can_vec = state_vec && aligned16(loss->c) && loss->ldc % 4 == 0;
     return run_chain(a, ceca::MODE_QUAD, d, can_vec, rd, port, st);
   }
 
@@ -634,7 +639,8 @@ int64_t dsgd_ceca_run_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* l
   if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
   const int32_t rc = check_loss(loss, d, false, nullptr);
   if (rc != CECA_OK) return rc;
-  if (loss->kind == CECA_LOSS_QUAD_CENTER) return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (use dsgd_ceca_steps)");
+  if (loss->kind != CECA_LOSS_LSQ && loss->kind != CECA_LOSS_LOGISTIC)
+    return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (LSQ, LOGISTIC)");
   const GemvPlan p = gemv_plan(n, d, loss->B);
   return 2 * p.v_bytes + p.partial_bytes;     // two message buffers (iterations alternate) + partial margins
 }
@@ -647,7 +653,8 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
   if (rc != CECA_OK) return rc;
   rc = check_loss(loss, d, true, batch_idx);
   if (rc != CECA_OK) return rc;
-  if (loss->kind == CECA_LOSS_QUAD_CENTER) return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (use dsgd_ceca_steps)");
+  if (loss->kind != CECA_LOSS_LSQ && loss->kind != CECA_LOSS_LOGISTIC)
+    return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (LSQ, LOGISTIC)");
   if (iters < 1) return fail(CECA_EINVAL, "iters = %d: need at least one", iters);
   const GemvPlan p = gemv_plan(n, d, loss->B);
   const int64_t need = 2 * p.v_bytes + p.partial_bytes;

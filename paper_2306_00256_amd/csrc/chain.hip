@@ -50,6 +50,9 @@ __device__ __forceinline__ void agent_terms(const ChainArgs& A, const Raw<V, MOD
     if (A.noise_std != 0.0f) e += A.noise_std * noise_group<V>(col, noise_keys(A.seed, A.k, (uint32_t)agent));
     const V ge = A.lr * e;
     xs = r.x - ge; ys = r.y - ge; v = z - ge;
+  } else if (MODE == MODE_GRAD) {
+    const V ge = A.lr * r.aux;
+    xs = r.x - ge; ys = r.y - ge; v = z - ge;
   } else {  // MODE_FROMV: aux = v, so -lr e = v - z
     v = r.aux;
     const V dz = v - z;
@@ -66,6 +69,7 @@ __device__ __forceinline__ V message_only(const ChainArgs& A, int agent, int64_t
   if (MODE == MODE_FROMV) return ld_plain<V>(A.aux + (int64_t)agent * A.ldaux + col);
   const V z = ld_plain<V>((EXCH_Y ? A.yin : A.xin) + off);
   if (MODE == MODE_GOSSIP) return z;
+  if (MODE == MODE_GRAD) return z - A.lr * ld_plain<V>(A.aux + (int64_t)agent * A.ldaux + col);
   V e = z - ld_plain<V>(A.aux + (int64_t)agent * A.ldaux + col);
   if (A.noise_std != 0.0f) e += A.noise_std * noise_group<V>(col, noise_keys(A.seed, A.k, (uint32_t)agent));
   const V ge = A.lr * e;
@@ -211,6 +215,7 @@ hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipSt
     case MODE_GOSSIP: CECA_CHAIN(MODE_GOSSIP);
     case MODE_QUAD: CECA_CHAIN(MODE_QUAD);
     case MODE_FROMV: CECA_CHAIN(MODE_FROMV);
+    case MODE_GRAD: CECA_CHAIN(MODE_GRAD);
   }
 #undef CECA_CHAIN
   return hipErrorInvalidValue;

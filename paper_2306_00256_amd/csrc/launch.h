@@ -13,7 +13,8 @@ namespace ceca {
 enum ChainMode : int {
   MODE_GOSSIP = 0,  // e = 0: self terms are x, y and the message is z             (Sec. 3 recursions)
   MODE_QUAD = 1,    // e = z - c + noise, generated in the kernel                  (fused step)
-  MODE_FROMV = 2    // message v was written by the half-step kernel; x - lr e = x + (v - z)
+  MODE_FROMV = 2,   // message v was written by the half-step kernel; x - lr e = x + (v - z)
+  MODE_GRAD = 3     // e is read from memory (the caller's gradients)
 };
 
 struct ChainArgs {
@@ -22,7 +23,7 @@ struct ChainArgs {
   float* xout;
   float* yout;
   int64_t ld;
-  const float* aux;   // MODE_QUAD: centres c;  MODE_FROMV: messages v
+  const float* aux;   // MODE_QUAD: centres c;  MODE_FROMV: messages v;  MODE_GRAD: gradients e
   int64_t ldaux;
   int64_t col0;       // first column of this launch
   int64_t ngroups;    // VEC-wide column groups in this launch

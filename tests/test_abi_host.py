@@ -91,6 +91,14 @@ def test_host_side_errors(api):
     assert L.dsgd_ceca_steps(p, p, 4, 8, 8, None, 0.1, 0, 3, 1, None) == Bn.CECA_EINVAL
     q.ldc = 4
     assert L.dsgd_ceca_steps(p, p, 4, 8, 8, ctypes.byref(q), 0.1, 0, 3, 1, None) == Bn.CECA_EINVAL     # ldc < d
+    g = Bn.Loss(); g.kind = Bn.LOSS_GRADIENT; g.c = None; g.ldc = 8
+    assert L.dsgd_ceca_step(p, p, 4, 8, 8, ctypes.byref(g), None, 0.1, 0, 1, None, 0, None) == Bn.CECA_EINVAL   # no gradients
+    g.c = p; g.ldc = 4
+    assert L.dsgd_ceca_step(p, p, 4, 8, 8, ctypes.byref(g), None, 0.1, 0, 1, None, 0, None) == Bn.CECA_EINVAL   # ldc < d
+    g.ldc = 8
+    assert L.dsgd_ceca_step(p, p, 4, 8, 8, ctypes.byref(g), None, 0.1, 0, 1, None, 0, None) == Bn.CECA_EINVAL   # gradients overlap S_out
+    assert L.dsgd_ceca_steps(p, p, 4, 8, 8, ctypes.byref(g), 0.1, 0, 3, 1, None) == Bn.CECA_EINVAL
+    assert api.dsgd_ceca_workspace_bytes(4, 8, g) == 0
     assert api.consensus_error_workspace_bytes(31, 25_557_032) > 0
     assert L.ceca_state_consensus(None, 4, 8, 8, p, p, 1 << 20, None) == Bn.CECA_EINVAL
     assert L.ceca_state_consensus(p, 4, 8, 4, p, p, 1 << 20, None) == Bn.CECA_EINVAL   # ld < d
