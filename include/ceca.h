@@ -106,6 +106,9 @@ int32_t ceca_schedule(int32_t n, int32_t r, int32_t port, ceca_round_t* out, int
  * itself.  In place, a thread reads every row of a pair (port 1) or of a whole shift cycle (port 2)
  * before it writes it; out of place, two-port rounds are cut into one-row stretches that sweep the
  * state band by band, which is the faster form on MI355X.  Partial overlap is CECA_EINVAL.
+ * In place with two ports, one workgroup per 1024 columns walks a whole cycle of up to n rows in turn:
+ * fine with many columns (within 10-20 % of out of place from d = 2^17), but with few columns and many
+ * agents it is latency-bound (n = 4097, d = 1024: 1 ms against 15 us) -- alternate two buffers there.
  * n = 1 copies (r must be 0).
  * In round 0 (b = 0) the y rows of S_in are not read. */
 int32_t ceca_gossip_round(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,
