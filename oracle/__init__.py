@@ -28,4 +28,8 @@ Pin status (see tests/test_oracle_*.py):
       the paper cites, not by the paper: pinned by stochasticity, three codings agreeing
       (per agent, dense, circular convolution), one-hot direction checks, the power-of-two
       exact-averaging property and its equality with CECA; *parity unpinned by the paper*
+  gossip over arbitrary graphs (Metropolis weights; hypercube, torus, grid of Table 1) ... textbook
+      definitions, not the paper's: pinned by hand-made weight matrices, closed-form spectra, exact
+      averaging of the one-peer hypercube, equality with the circulant oracle on a ring;
+      *parity unpinned by the paper*
 """
