@@ -300,6 +300,20 @@ def run_mix(torch, P, Bn, n, d, steps, warmup):
         ms = tm.event_ms / steps
         out[kind] = {"ms_per_call": ms, "GBs": 8.0 * n * d / (ms * 1e-3) / 1e9,
                      "agent_param_rounds_per_s": tau * n * d / (ms * 1e-3)}
+    # graphs that are not shift-invariant go through neighbour tables (ceca_graph_rounds): a 2-D torus of
+    # the same n with Metropolis weights, and the ring again as a table (same bits as the circulant kernel)
+    rows = {130: 10, 1026: 27}.get(n, 1)
+    for kind, edges in (("torus_graph", WL.edges_of("torus", n, rows)), ("ring_graph", WL.edges_of("ring", n))):
+        tn, tw, ts = (torch.from_numpy(a[None]).cuda().contiguous() for a in WL.graph_table(n, edges))
+        for _ in range(warmup):
+            P.ceca_graph_rounds(X, Y, n, d, tn, tw, ts, tau, ld=ld)
+        tm = Timer(torch)
+        with tm:
+            for _ in range(steps):
+                P.ceca_graph_rounds(X, Y, n, d, tn, tw, ts, tau, ld=ld)
+        ms = tm.event_ms / steps
+        out[kind] = {"ms_per_call": ms, "GBs": 8.0 * n * d / (ms * 1e-3) / 1e9,
+                     "agent_param_rounds_per_s": tau * n * d / (ms * 1e-3)}
     # CECA beside them: the same tau rounds on the same x reach the exact mean (ceca_average keeps the
     # auxiliary y in registers, so it also moves 8 bytes per agent-parameter)
     for port in (2, 1) if n % 2 == 0 else (2,):

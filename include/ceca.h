@@ -244,6 +244,19 @@ int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, i
                         const ceca_mix_t* specs, int32_t period, int32_t k0, int32_t rounds,
                         void* hip_stream);
 
+/* Gossip averaging over an arbitrary graph (the non-circulant topologies of Table 1 -- grid, torus,
+ * hypercube -- and any graph or weight rule the caller brings; their definitions are not the paper's):
+ *   x_i+ = w_self[i] x_i + sum_{j < m} w[i*m + j] x_{nbr[i*m + j]}
+ * for `rounds` rounds in one pass over X (8 bytes per agent-parameter); round t uses the tables at index
+ * (k0 + t) mod period.  nbr: device, period*n*m int32 (0-based vertices; rows with fewer than m neighbours
+ * are padded with any valid vertex at weight 0; values outside [0, n) are clamped into it rather than
+ * followed); w: device, period*n*m floats; w_self: device, period*n floats.  The tables must not overlap
+ * X_out.  Evaluated as t = w_0 z_0, t = fma(w_j, z_j, t), x+ = fma(w_self, x, t): a circulant graph gives
+ * the bits of ceca_mix_rounds.  X_out may be X_in or disjoint from it.  Limits: n <= 4096, 1 <= m <= 64. */
+int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, int64_t ld,
+                          const int32_t* nbr, const float* w, const float* w_self, int32_t m,
+                          int32_t period, int32_t k0, int32_t rounds, void* hip_stream);
+
 /* Measurement aid, not part of the method: an elementwise kernel with the traffic mix of the fused
  * quadratic-centre step (three streaming reads a, b, c and two streaming writes o1, o2 per element;
  * o1, o2 may be a, b), so that a benchmark can report, from the same run, the bandwidth the device gives

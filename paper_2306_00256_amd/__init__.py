@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     ceca_average,
     ceca_gossip_round,
     ceca_gossip_rounds,
+    ceca_graph_rounds,
     ceca_mix_rounds,
     ceca_schedule,
     ceca_set_option,

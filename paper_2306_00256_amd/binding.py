@@ -16,7 +16,7 @@ MIX_MAX = 16
 
 EXPORTS = (
     "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "ceca_average", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps", "dsgd_ceca_run_workspace_bytes", "dsgd_ceca_run",
-    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_stream_probe", "ceca_last_error", "ceca_last_hip_error",
+    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_graph_rounds", "ceca_stream_probe", "ceca_last_error", "ceca_last_hip_error",
     "ceca_set_option",
 )
 
@@ -99,6 +99,9 @@ def lib():
         L.ceca_mix_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.POINTER(Mix), C.c_int32,
                                       C.c_int32, C.c_int32, C.c_void_p]
         L.ceca_mix_rounds.restype = C.c_int32
+        L.ceca_graph_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.ceca_graph_rounds.restype = C.c_int32
         L.ceca_stream_probe.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_void_p]
         L.ceca_stream_probe.restype = C.c_int32
         L.ceca_last_error.restype = C.c_char_p
@@ -164,6 +167,16 @@ def ceca_mix_rounds(X_in, X_out, n: int, d: int, specs: Sequence[Mix], rounds: i
     ld = int(X_in.stride(0)) if ld is None else ld
     arr = (Mix * len(specs))(*specs)
     _check(lib().ceca_mix_rounds(_ptr(X_in), _ptr(X_out), n, d, ld, arr, len(specs), k0, rounds, _stream(stream)))
+
+
+def ceca_graph_rounds(X_in, X_out, n: int, d: int, nbr, w, w_self, rounds: int, k0: int = 0,
+                      ld: Optional[int] = None, stream=None) -> None:
+    """`rounds` gossip rounds over a graph given as device tables: nbr (period, n, m) int32, w (period, n, m)
+    float32, w_self (period, n) float32, all contiguous; round t uses tables[(k0 + t) % period]."""
+    ld = int(X_in.stride(0)) if ld is None else ld
+    period, _, m = nbr.shape
+    _check(lib().ceca_graph_rounds(_ptr(X_in), _ptr(X_out), n, d, ld, _ptr(nbr), _ptr(w), _ptr(w_self), m, period, k0,
+                                   rounds, _stream(stream)))
 
 
 def ceca_average(X_in, X_out, n: int, d: int, port: int, ld: Optional[int] = None, stream=None) -> None:

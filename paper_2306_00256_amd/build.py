@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libceca.so")
-SOURCES = ["api.cpp", "schedule.cpp", "chain.hip", "multi_round.hip", "mix.hip", "gemv.hip", "consensus.hip", "probe.hip"]
+SOURCES = ["api.cpp", "schedule.cpp", "chain.hip", "multi_round.hip", "mix.hip", "graph.hip", "gemv.hip", "consensus.hip", "probe.hip"]
 
 
 def hipcc_path() -> str:
@@ -20,7 +20,7 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build_library(verbose: bool = True, out: str = LIB, extra=(), jobs: int = 7) -> str:
+def build_library(verbose: bool = True, out: str = LIB, extra=(), jobs: int = 8) -> str:
     """Compiles every source for gfx950 (one hipcc per source, side by side) and links the shared
     library; always recompiles.  Objects go to a scratch folder next to the output and are removed."""
     import tempfile

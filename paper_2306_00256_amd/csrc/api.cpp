@@ -362,6 +362,17 @@ TileShape mix_tile(int32_t n, bool vec4, bool heavy) {
                    });
 }
 
+// Gossip over an arbitrary graph (x of every row in registers, plus a neighbour index and weight per row
+// in flight): 256-thread workgroups up to 512 agents, then the wider ones of the mixing kernel.
+TileShape graph_tile(int32_t n, bool vec4) {
+  return pick_tile(n, vec4, 4, ceca::kGraphRows, 8,
+                   [](int32_t m) { return m <= 512 ? ceca::kBlock : (m <= 6 * 128 ? 512 : 1024); },
+                   [n](int32_t threads) {
+                     if (threads == ceca::kBlock) return n <= 192 ? 8 : ceca::kGraphRows;
+                     return n <= 6 * 512 ? 6 : 8;      // 6 rows fit 128 registers; 8 keep 4096 agents at 32-byte rows
+                   });
+}
+
 }  // namespace
 
 extern "C" {
@@ -869,6 +880,45 @@ int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, i
     m.threads = ts.threads;  m.row_lanes = ts.row_lanes;  m.rows_per_thread = ts.rows_per_thread;
     const hipError_t e = ceca::launch_mix_rounds(m, false, st);
     if (e != hipSuccess) return hip_fail(e, "mixing kernel launch (scalar columns)");
+  }
+  return CECA_OK;
+}
+
+int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, int64_t ld, const int32_t* nbr,
+                          const float* w, const float* w_self, int32_t m, int32_t period, int32_t k0, int32_t rounds,
+                          void* hip_stream) {
+  if (!X_in || !X_out || !nbr || !w || !w_self) return fail(CECA_EINVAL, "null pointer");
+  if (n < 1 || n > 4096) return fail(CECA_EINVAL, "n = %d: graph gossip rounds take 1 to 4096 agents", n);
+  if (d < 1 || ld < d) return fail(CECA_EINVAL, "need 1 <= d <= ld (d = %lld, ld = %lld)", (long long)d, (long long)ld);
+  if (m < 1 || m > ceca::kGraphMaxDegree) return fail(CECA_EINVAL, "m = %d outside [1, %d]", m, ceca::kGraphMaxDegree);
+  if (period < 1 || k0 < 0 || rounds < 1) return fail(CECA_EINVAL, "need period >= 1, k0 >= 0 and rounds >= 1");
+  const int64_t bytes = (int64_t)n * ld * (int64_t)sizeof(float);
+  if (overlaps(X_in, bytes, X_out, bytes) && (const void*)X_in != (const void*)X_out)
+    return fail(CECA_EINVAL, "X_out partially overlaps X_in");
+  const int64_t entries = (int64_t)period * n * m;
+  if (overlaps(nbr, entries * 4, X_out, bytes) || overlaps(w, entries * 4, X_out, bytes) ||
+      overlaps(w_self, (int64_t)period * n * 4, X_out, bytes))
+    return fail(CECA_EINVAL, "the graph tables overlap X_out");
+  const TileShape tv = graph_tile(n, true), ts = graph_tile(n, false);
+  if (!tv.ok || !ts.ok) return fail(CECA_EINVAL, "internal: no tile holds n = %d agents", n);
+  ceca::GraphArgs g{};
+  g.xin = X_in;  g.xout = X_out;  g.ld = ld;
+  g.nbr = nbr;  g.w = w;  g.w_self = w_self;
+  g.n = n;  g.m = m;  g.rounds = rounds;  g.period = period;  g.k0 = k0 % period;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const bool can_vec = aligned16(X_in) && aligned16(X_out) && ld % 4 == 0;
+  const int64_t d4 = can_vec ? d / 4 : 0;
+  if (d4 > 0) {
+    g.col0 = 0;  g.ngroups = d4;
+    g.threads = tv.threads;  g.row_lanes = tv.row_lanes;  g.rows_per_thread = tv.rows_per_thread;
+    const hipError_t e = ceca::launch_graph_rounds(g, true, st);
+    if (e != hipSuccess) return hip_fail(e, "graph gossip kernel launch");
+  }
+  if (d - 4 * d4 > 0) {
+    g.col0 = 4 * d4;  g.ngroups = d - 4 * d4;
+    g.threads = ts.threads;  g.row_lanes = ts.row_lanes;  g.rows_per_thread = ts.rows_per_thread;
+    const hipError_t e = ceca::launch_graph_rounds(g, false, st);
+    if (e != hipSuccess) return hip_fail(e, "graph gossip kernel launch (scalar columns)");
   }
   return CECA_OK;
 }

@@ -153,6 +153,25 @@ struct MixArgs {
   float w[kMixMaxPeers];
 };
 
+constexpr int kGraphRows = 16;      // most rows of x a thread of the graph-gossip kernel keeps in registers
+constexpr int kGraphMaxDegree = 64; // most neighbours per vertex and round
+
+struct GraphArgs {
+  const float* xin;
+  float* xout;
+  int64_t ld;
+  int64_t col0;
+  int64_t ngroups;
+  const int32_t* nbr;       // device, [period][n][m]: neighbour j of vertex i in the round's graph
+  const float* w;           // device, [period][n][m]: its weight
+  const float* w_self;      // device, [period][n]
+  int32_t n, m, rounds, period, k0;
+  int32_t rows_per_thread;  // 1 to kGraphRows, the least that covers n
+  int32_t row_lanes;        // power of two, row_lanes * rows_per_thread >= n
+  int32_t threads;          // threads per workgroup: 0 = 256, or 512 / 1024 (16-byte groups only)
+  int32_t xcd_tiles;        // set by the launcher
+};
+
 // rows: state rows whose loads a thread keeps in flight together (1, 2, 4 or 8)
 hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
 // one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
@@ -167,6 +186,7 @@ hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
 extern std::atomic<int> g_mix_xcd;   // measurement knob: 0 = plain tile order in the mixing kernel
 hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
+hipError_t launch_graph_rounds(const GraphArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);

@@ -212,3 +212,49 @@ def sample_columns(d: int, count: int, seed: int, tile: int = 1024, tail: Option
         for c in g.integers(0, d, size=need):
             cols.add(int(c))
     return np.array(sorted(cols), dtype=np.int64)
+
+
+# ---------------------------------------------------------------------------------------------
+# Graph tables for ceca_graph_rounds: neighbour lists of standard graphs with Metropolis weights
+# (inputs only: which vertices are adjacent and the textbook weight 1 / (1 + max degree of the two ends))
+# ---------------------------------------------------------------------------------------------
+def graph_table(n: int, edges, m: int = 0):
+    """(nbr (n, m) int32, w (n, m) float32, w_self (n,) float32) of the undirected graph with Metropolis
+    weights; rows with fewer neighbours are padded with the vertex itself at weight 0."""
+    adj = [[] for _ in range(n)]
+    for a, b in edges:
+        if a != b and b not in adj[a]:
+            adj[a].append(b)
+            adj[b].append(a)
+    width = max(m, max(len(r) for r in adj), 1)
+    nbr = np.tile(np.arange(n, dtype=np.int32)[:, None], (1, width))
+    w = np.zeros((n, width), dtype=np.float32)
+    for i in range(n):
+        for j, v in enumerate(sorted(adj[i])):
+            nbr[i, j] = v
+            w[i, j] = np.float32(1.0 / (1.0 + max(len(adj[i]), len(adj[v]))))
+    w_self = (1.0 - w.astype(np.float64).sum(axis=1)).astype(np.float32)
+    return nbr, w, w_self
+
+
+def edges_of(kind: str, n: int, rows: int = 0):
+    """Edge lists: 'ring', 'hypercube' (n a power of two), 'torus' / 'grid' (rows x n/rows), 'random' (ring plus n chords)."""
+    if kind == "ring":
+        return [(i, (i + 1) % n) for i in range(n)]
+    if kind == "hypercube":
+        return [(i, i ^ (1 << b)) for i in range(n) for b in range(max(n - 1, 1).bit_length()) if (i ^ (1 << b)) < n and i < (i ^ (1 << b))]
+    if kind in ("torus", "grid"):
+        cols = n // rows
+        e = []
+        for a in range(rows):
+            for b in range(cols):
+                if kind == "torus" or a + 1 < rows:
+                    e.append((a * cols + b, ((a + 1) % rows) * cols + b))
+                if kind == "torus" or b + 1 < cols:
+                    e.append((a * cols + b, a * cols + (b + 1) % cols))
+        return e
+    if kind == "random":
+        rng = np.random.default_rng(n)
+        chords = [(int(a), int(b)) for a, b in rng.integers(0, n, size=(n, 2)) if a != b]
+        return [(i, (i + 1) % n) for i in range(n)] + chords
+    raise ValueError(kind)
