@@ -279,7 +279,8 @@ int32_t ceca_last_hip_error(void);
  *   CECA_OPT_BAND     column tiles (of 1024 columns) per band of the launch order (0 = library default)
  *   CECA_OPT_WG_PER_CU  cap on workgroups resident per compute unit, 2..8 (0 = library default)
  *   CECA_OPT_ONEPASS  1 (default): minibatch gradients keep the sampled rows in registers and read A once when
- *                     (B, d) fits; 0: always the two-pass margins / half-step kernels
+ *                     (B, d) fits; 0: always the two-pass margins / half-step kernels.  Also: 0 makes
+ *                     ceca_graph_rounds read its tables from memory at every look-up (no staging in LDS)
  *   CECA_OPT_AGENTS_PER_WG  agents one workgroup of the looping one-pass gradient kernel takes in turn
  *                     (0 = library default); 1000: never use the chunked gradient kernel
  *   CECA_OPT_CONS_SINGLE_PASS  1 (default): consensus observables read x once when a workgroup's registers can

@@ -363,10 +363,11 @@ TileShape mix_tile(int32_t n, bool vec4, bool heavy) {
 }
 
 // Gossip over an arbitrary graph (x of every row in registers, plus a neighbour index and weight per row
-// in flight): 256-thread workgroups up to 512 agents, then the wider ones of the mixing kernel.
+// in flight).  Measured on MI355X (ring, torus, hypercube; n = 130 ... 2048): 256-thread workgroups are
+// best up to about 258 agents, 1024-thread ones from 512 on (1.6-3.3x there: wider rows of the tile).
 TileShape graph_tile(int32_t n, bool vec4) {
   return pick_tile(n, vec4, 4, ceca::kGraphRows, 8,
-                   [](int32_t m) { return m <= 512 ? ceca::kBlock : (m <= 6 * 128 ? 512 : 1024); },
+                   [](int32_t m) { return m <= 384 ? ceca::kBlock : 1024; },
                    [n](int32_t threads) {
                      if (threads == ceca::kBlock) return n <= 192 ? 8 : ceca::kGraphRows;
                      return n <= 6 * 512 ? 6 : 8;      // 6 rows fit 128 registers; 8 keep 4096 agents at 32-byte rows
@@ -905,6 +906,7 @@ int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d,
   g.xin = X_in;  g.xout = X_out;  g.ld = ld;
   g.nbr = nbr;  g.w = w;  g.w_self = w_self;
   g.n = n;  g.m = m;  g.rounds = rounds;  g.period = period;  g.k0 = k0 % period;
+  g.stage = g_opt_onepass.load() != 0;      // (CECA_OPT_ONEPASS doubles as the switch of the staged tables)
   hipStream_t st = (hipStream_t)hip_stream;
   const bool can_vec = aligned16(X_in) && aligned16(X_out) && ld % 4 == 0;
   const int64_t d4 = can_vec ? d / 4 : 0;

@@ -26,12 +26,16 @@ constexpr int graph_waves() { return THREADS > 256 ? 4 : 1; }
 // neighbour for all of a thread's rows at once.  Per row the order of operations is t = w_0 z_0,
 // t = fma(w_j, z_j, t), x+ = fma(w_self, x, t) -- that of the shift-invariant kernel, so a circulant
 // graph gives the same bits there and here.
-template <int VEC, int RT, int THREADS>
+// STAGE: the round's table (n * m entries of index and weight) is copied into LDS behind the tile --
+// once for a static graph, every round for a time-varying one (each thread requests its share of the
+// next round's entries right after the barrier) -- and the look-ups read it there instead of from
+// memory.  Used when the table is small (kGraphStageEntries entries per thread at most).
+template <int VEC, int RT, int THREADS, bool STAGE>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(graph_waves<THREADS>())))
 void graph_rounds_kernel(const GraphArgs M) {
 #pragma clang fp contract(off)
   using V = typename VecOf<VEC>::T;
-  extern __shared__ float lds_x[];                 // [n][lanes] groups of VEC floats
+  extern __shared__ float lds_x[];                 // [n][lanes] groups of VEC floats, then (STAGE) [n * m] entries
   const int lanes = THREADS / M.row_lanes;
   const int tid = threadIdx.x;
   const int cg = tid % lanes;
@@ -50,44 +54,73 @@ void graph_rounds_kernel(const GraphArgs M) {
     x[k] = ld_stream<V>(M.xin + (int64_t)row[k] * M.ld + col);
   }
   V* xs = reinterpret_cast<V*>(lds_x);
+  int2* tab = reinterpret_cast<int2*>(xs + (size_t)M.n * lanes);   // (clamped index, weight bits) of entry i * m + j
+  const int entries = M.n * M.m;
   constexpr int L = RT - 1;                        // rows_per_thread is the least that covers n: only row L can be a shadow
   const bool last_mine = rg + L * M.row_lanes < M.n;
   int spec = M.k0 % M.period;
+  // my share of a round's table: entries tid, tid + THREADS, ...
+  int2 share[STAGE ? kGraphStageEntries : 1];
+  auto request_share = [&](int sp) {
+    const int64_t base = (int64_t)sp * entries;
+#pragma unroll
+    for (int e = 0; e < kGraphStageEntries; ++e) {
+      const int q = tid + e * THREADS;
+      if (q < entries) {
+        share[STAGE ? e : 0].x = min(max(M.nbr[base + q], 0), M.n - 1);     // indices outside [0, n) are clamped, not followed
+        share[STAGE ? e : 0].y = __float_as_int(M.w[base + q]);
+      }
+    }
+  };
+  if (STAGE) request_share(spec);
   for (int t = 0; t < M.rounds; ++t) {
     const int64_t base = (int64_t)spec * M.n;
     const int32_t* nbr = M.nbr + base * M.m;
     const float* w = M.w + base * M.m;
+    const int next_spec = (spec + 1 == M.period) ? 0 : spec + 1;
+    float ws[RT];                                  // requested before the barrier, used after the neighbours
+#pragma unroll
+    for (int k = 0; k < RT; ++k) ws[k] = M.w_self[base + row[k]];
 #pragma unroll
     for (int k = 0; k < L; ++k) xs[tid + k * THREADS] = x[k];      // row i, group c sits in slot i * lanes + c = tid + k * THREADS
     if (last_mine) xs[tid + L * THREADS] = x[L];
+    const bool restage = STAGE && (t == 0 || M.period > 1);        // the same for every thread
+    if (restage) {
+#pragma unroll
+      for (int e = 0; e < kGraphStageEntries; ++e) {
+        const int q = tid + e * THREADS;
+        if (q < entries) tab[q] = share[STAGE ? e : 0];
+      }
+    }
     __syncthreads();
+    if (STAGE && M.period > 1 && t + 1 < M.rounds) request_share(next_spec);
     V acc[RT];
-    {
+    for (int j = 0; j < M.m; ++j) {
       int idx[RT];
       float wt[RT];
 #pragma unroll
       for (int k = 0; k < RT; ++k) {
-        idx[k] = nbr[(int64_t)row[k] * M.m];
-        wt[k] = w[(int64_t)row[k] * M.m];
+        if (STAGE) {
+          const int2 en = tab[row[k] * M.m + j];
+          idx[k] = en.x;
+          wt[k] = __int_as_float(en.y);
+        } else {
+          idx[k] = min(max(nbr[(int64_t)row[k] * M.m + j], 0), M.n - 1);   // indices outside [0, n) are clamped, not followed
+          wt[k] = w[(int64_t)row[k] * M.m + j];
+        }
       }
+      if (j == 0) {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) acc[k] = wt[k] * xs[min(max(idx[k], 0), M.n - 1) * lanes + cg];   // indices outside [0, n) are clamped, not followed
-    }
-    for (int j = 1; j < M.m; ++j) {
-      int idx[RT];
-      float wt[RT];
+        for (int k = 0; k < RT; ++k) acc[k] = wt[k] * xs[idx[k] * lanes + cg];
+      } else {
 #pragma unroll
-      for (int k = 0; k < RT; ++k) {
-        idx[k] = nbr[(int64_t)row[k] * M.m + j];
-        wt[k] = w[(int64_t)row[k] * M.m + j];
+        for (int k = 0; k < RT; ++k) acc[k] = fma_rows(wt[k], xs[idx[k] * lanes + cg], acc[k]);
       }
-#pragma unroll
-      for (int k = 0; k < RT; ++k) acc[k] = fma_rows(wt[k], xs[min(max(idx[k], 0), M.n - 1) * lanes + cg], acc[k]);
     }
 #pragma unroll
-    for (int k = 0; k < RT; ++k) x[k] = fma_rows(M.w_self[base + row[k]], x[k], acc[k]);
+    for (int k = 0; k < RT; ++k) x[k] = fma_rows(ws[k], x[k], acc[k]);
     __syncthreads();
-    if (++spec == M.period) spec = 0;
+    spec = next_spec;
   }
   if (!on) return;
 #pragma unroll
@@ -99,13 +132,21 @@ void graph_rounds_kernel(const GraphArgs M) {
 
 template <int VEC, int RT, int THREADS>
 static hipError_t launch_graph(const GraphArgs& mm, unsigned blocks, size_t lds, hipStream_t st) {
+  // small tables are staged in LDS behind the tile
+  const int64_t entries = (int64_t)mm.n * mm.m;
+  const size_t staged = lds + (size_t)entries * sizeof(int2);
+  const bool stage = mm.stage && entries <= (int64_t)kGraphStageEntries * THREADS && staged <= kMultiMaxLds &&
+                     (staged <= 64 * 1024 || lds > 32 * 1024);     // do not halve the resident workgroups of a small tile
+  if (stage) lds = staged;
+  const void* fn = stage ? reinterpret_cast<const void*>(&graph_rounds_kernel<VEC, RT, THREADS, true>)
+                         : reinterpret_cast<const void*>(&graph_rounds_kernel<VEC, RT, THREADS, false>);
   if (lds > 64 * 1024) {
     // more than 64 KB of LDS per workgroup has to be asked for
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&graph_rounds_kernel<VEC, RT, THREADS>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  graph_rounds_kernel<VEC, RT, THREADS><<<dim3(blocks), dim3(THREADS), lds, st>>>(mm);
+  if (stage) graph_rounds_kernel<VEC, RT, THREADS, true><<<dim3(blocks), dim3(THREADS), lds, st>>>(mm);
+  else graph_rounds_kernel<VEC, RT, THREADS, false><<<dim3(blocks), dim3(THREADS), lds, st>>>(mm);
   return hipGetLastError();
 }
 

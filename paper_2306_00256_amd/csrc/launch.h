@@ -155,6 +155,7 @@ struct MixArgs {
 
 constexpr int kGraphRows = 16;      // most rows of x a thread of the graph-gossip kernel keeps in registers
 constexpr int kGraphMaxDegree = 64; // most neighbours per vertex and round
+constexpr int kGraphStageEntries = 12;   // a round's table is staged in LDS when each thread copies at most this many entries
 
 struct GraphArgs {
   const float* xin;
@@ -169,6 +170,7 @@ struct GraphArgs {
   int32_t rows_per_thread;  // 1 to kGraphRows, the least that covers n
   int32_t row_lanes;        // power of two, row_lanes * rows_per_thread >= n
   int32_t threads;          // threads per workgroup: 0 = 256, or 512 / 1024 (16-byte groups only)
+  int32_t stage;            // 1: stage small tables in LDS (0: always read them from memory)
   int32_t xcd_tiles;        // set by the launcher
 };
 
