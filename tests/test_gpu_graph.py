@@ -173,3 +173,45 @@ def test_graph_of_the_wide_workgroup_kernels(env):
         torch.cuda.synchronize()
         assert np.isfinite(torch.randn(1024, device="cuda").sum().item())      # unrelated eager work in between
         assert np.array_equal(S2.cpu().numpy(), eager[rep]), rep
+
+
+def test_concurrent_calls_on_two_streams_from_two_threads(env):
+    """The library keeps no per-call state (no global scratch): two host threads driving different problems
+    on their own streams at the same time get the results of running them one after the other."""
+    import threading
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    jobs = []
+    for n, d, port, seed in [(100, 4096 + 4, 2, 1), (30, 8192, 1, 2)]:
+        x0 = WL.initial_state(n, d, seed)
+        c = torch.from_numpy(WL.quad_centers(n, d, seed)).cuda()
+        jobs.append((n, d, port, x0, c))
+
+    def work(job, stream, out):
+        n, d, port, x0, c = job
+        tau = OS.num_rounds(n)
+        with torch.cuda.stream(stream):
+            S = make_state(torch, x0)
+            T = S if port == 1 else torch.empty_like(S)
+            for k in range(3 * tau):
+                P.dsgd_ceca_step(S, T, n, d, Bn.make_quad_center_loss(c, 0.01, 7, k), None, 0.1, k % tau, port, stream=stream)
+                S, T = T, S
+            P.ceca_gossip_rounds(S, S, n, d, tau + 1, port, stream=stream)
+            stream.synchronize()
+            out.append(S.cpu().numpy().copy())
+
+    serial = []
+    for job in jobs:
+        out = []
+        work(job, torch.cuda.current_stream(), out)
+        serial.append(out[0])
+    torch.cuda.synchronize()
+    for _ in range(3):
+        outs = [[], []]
+        threads = [threading.Thread(target=work, args=(jobs[i], torch.cuda.Stream(), outs[i])) for i in range(2)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+        for i in range(2):
+            assert np.array_equal(outs[i][0], serial[i]), i
