@@ -54,7 +54,8 @@ void graph_rounds_kernel(const GraphArgs M) {
     x[k] = ld_stream<V>(M.xin + (int64_t)row[k] * M.ld + col);
   }
   V* xs = reinterpret_cast<V*>(lds_x);
-  int2* tab = reinterpret_cast<int2*>(xs + (size_t)M.n * lanes);   // (clamped index, weight bits) of entry i * m + j
+  // (clamped index, weight bits) of entry i * m + j, on the next 8-byte boundary behind the tile
+  int2* tab = reinterpret_cast<int2*>(reinterpret_cast<char*>(lds_x) + (((size_t)M.n * lanes * sizeof(V) + 7) & ~(size_t)7));
   const int entries = M.n * M.m;
   constexpr int L = RT - 1;                        // rows_per_thread is the least that covers n: only row L can be a shadow
   const bool last_mine = rg + L * M.row_lanes < M.n;
@@ -134,7 +135,7 @@ template <int VEC, int RT, int THREADS>
 static hipError_t launch_graph(const GraphArgs& mm, unsigned blocks, size_t lds, hipStream_t st) {
   // small tables are staged in LDS behind the tile
   const int64_t entries = (int64_t)mm.n * mm.m;
-  const size_t staged = lds + (size_t)entries * sizeof(int2);
+  const size_t staged = ((lds + 7) & ~(size_t)7) + (size_t)entries * sizeof(int2);
   const bool stage = mm.stage && entries <= (int64_t)kGraphStageEntries * THREADS && staged <= kMultiMaxLds &&
                      (staged <= 64 * 1024 || lds > 32 * 1024);     // do not halve the resident workgroups of a small tile
   if (stage) lds = staged;

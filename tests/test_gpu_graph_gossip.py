@@ -29,7 +29,8 @@ def _dev(torch, tables):
 
 
 CASES = [("hypercube", 64, 0), ("hypercube", 1024, 0), ("torus", 15, 3), ("torus", 130, 10), ("grid", 12, 4),
-         ("grid", 1026, 27), ("random", 50, 0), ("random", 700, 0), ("random", 2050, 0), ("ring", 31, 0)]
+         ("grid", 1026, 27), ("random", 50, 0), ("random", 700, 0), ("random", 2050, 0), ("random", 2049, 0),
+         ("ring", 31, 0), ("ring", 3001, 0)]
 
 
 @pytest.mark.parametrize("kind,n,rows", CASES)
