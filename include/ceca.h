@@ -177,9 +177,13 @@ int64_t dsgd_ceca_run_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* l
  * same bits as `iters` calls of dsgd_ceca_step.  Where a workgroup can take an agent's whole rows
  * (16-byte aligned layouts with d <= 16384 and either n >= 128 with d > 1024 or a batch that fits a
  * register tile: B <= 32 at d <= 1024, 16 at 4096, 8 at 8192, 4 at 16384; any other layout with
- * d <= 1024) each iteration after the first is ONE kernel: the workgroup that takes agent i's gradient first finishes the iteration before
- * for that agent (Eqs. (8), (9)) from its own and its peer's message; otherwise the call loops over
- * dsgd_ceca_step.
+ * d <= 1024) each iteration after the first is ONE kernel: the workgroup that takes agent i's gradient
+ * first finishes the iteration before for that agent (Eqs. (8), (9)) from its own and its peer's
+ * message.  Other shapes take the gradient in two passes (margins, then half step); there the margins
+ * kernel finishes the iteration before, TWO kernels per iteration instead of three, with the state
+ * alternating between S_out and a copy in the workspace (used when ld <= d rounded up to a multiple of
+ * 64; beyond that, and when S_in and S_out differ in 16-byte alignment, the call loops over
+ * dsgd_ceca_step).
  * S_out may be S_in or disjoint from it; when disjoint, S_in is left unchanged.
  * workspace: device, 256-byte aligned, at least dsgd_ceca_run_workspace_bytes(); contents are scratch. */
 int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld,

@@ -166,6 +166,9 @@ void set_weights(const ceca_round_t& rd, int32_t n, bool gossip_only, ceca::Chai
   a->read_y = (rd.b_num != 0) ? 1 : 0;
 }
 
+// dsgd_ceca_run's copy of the state: 2n rows at the caller's pitch, for pitches up to round_up(d, 64)
+int64_t run_state_bytes(int32_t n, int64_t d) { return round_up(2 * (int64_t)n * round_up(d, 64) * (int64_t)sizeof(float), 256); }
+
 struct GemvPlan {
   int64_t ldv, v_bytes, partial_bytes;
   int32_t nchunks_max;
@@ -654,7 +657,9 @@ int64_t dsgd_ceca_run_workspace_bytes(int32_t n, int64_t d, const ceca_loss_t* l
   if (loss->kind != CECA_LOSS_LSQ && loss->kind != CECA_LOSS_LOGISTIC)
     return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (LSQ, LOGISTIC)");
   const GemvPlan p = gemv_plan(n, d, loss->B);
-  return 2 * p.v_bytes + p.partial_bytes;     // two message buffers (iterations alternate) + partial margins
+  // two message buffers (iterations alternate) + partial margins + a copy of the state (iterations on the
+  // two-pass gradient kernels alternate between it and S_out)
+  return 2 * p.v_bytes + p.partial_bytes + run_state_bytes(n, d);
 }
 
 int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int64_t ld, const ceca_loss_t* loss,
@@ -669,7 +674,7 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
     return fail(CECA_EINVAL, "dsgd_ceca_run takes minibatch losses (LSQ, LOGISTIC)");
   if (iters < 1) return fail(CECA_EINVAL, "iters = %d: need at least one", iters);
   const GemvPlan p = gemv_plan(n, d, loss->B);
-  const int64_t need = 2 * p.v_bytes + p.partial_bytes;
+  const int64_t need = 2 * p.v_bytes + p.partial_bytes + run_state_bytes(n, d);
   if (!workspace || workspace_bytes < need)
     return fail(CECA_EWORKSPACE, "workspace of %lld bytes needed, %lld given", (long long)need,
                 (long long)(workspace ? workspace_bytes : 0));
@@ -688,6 +693,70 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
   const bool same_layout = vec == (lay && aligned16(S_out));
   const bool fused = same_layout && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg.load() != 1000 &&
                      ceca::grad_fused_covers(n, d, loss->B, vec);
+  // Shapes whose single step takes the two-pass gradient (margins, then half step): the combine of the
+  // iteration before becomes the prologue of the margins kernel -- two launches per iteration instead of
+  // three, same bits.  The row groups of that kernel all read the old rows while one of them stores the
+  // new ones, so the state alternates between S_out and a copy in the workspace.
+  const bool two_pass = g_opt_onepass.load() == 0 || !(vec ? ceca::grad_fused_covers(n, d, loss->B, true) : d <= 1024);
+  const bool copy_fits = 2 * (int64_t)n * ld * (int64_t)sizeof(float) <= run_state_bytes(n, d);     // the copy keeps the caller's pitch
+  if (!fused && two_pass && same_layout && copy_fits && n > 1 && iters > 1 && n <= 65535) {
+    float* V2[2] = {reinterpret_cast<float*>(w), reinterpret_cast<float*>(w + p.v_bytes)};
+    float* W = reinterpret_cast<float*>(w + 2 * p.v_bytes + p.partial_bytes);
+    ceca::GemvArgs g{};
+    g.A = loss->A;  g.lda = loss->lda;  g.t = loss->t;
+    g.ldv = p.ldv;
+    g.partial = reinterpret_cast<float*>(w + 2 * p.v_bytes);
+    g.d = d;
+    g.n = n;  g.N = loss->N;  g.B = loss->B;  g.kind = loss->kind;
+    g.lr = lr;
+    g.scale = loss->grad_scale > 0.0f ? loss->grad_scale : 1.0f / (float)loss->B;
+    g.noise_std = loss->noise_std;
+    g.seed = loss->seed;
+    g.chunk_cols = ceca::kBlock * ceca::kChunkGroups * (vec ? 4 : 1);
+    g.nchunks = (int32_t)((d + g.chunk_cols - 1) / g.chunk_cols);
+    // where the state lives before iteration t's prologue: S_in, then the copy and S_out in turn
+    const float* cur = S_in;
+    ceca_round_t prev{};
+    g.ld = ld;  g.ldo = ld;
+    for (int32_t t = 0; t < iters; ++t) {
+      ceca::fill_round(n, (r0 + t) % tau, port, &rd);
+      g.batch_idx = batch_idx + (int64_t)t * nb;
+      g.k = loss->k + (uint32_t)t;
+      g.v = V2[t & 1];
+      hipError_t e;
+      if (t == 0) {
+        g.zin = rd.exchange_y ? S_in + (int64_t)n * ld : S_in;
+        e = ceca::launch_margins(g, vec, st);
+      } else {
+        float* dst = (cur == W) ? S_out : W;
+        g.px = cur;  g.py = cur + (int64_t)n * ld;
+        g.ox = dst;  g.oy = dst + (int64_t)n * ld;
+        g.pv = V2[(t - 1) & 1];
+        g.p_shift = prev.shift;  g.p_port = port;
+        g.p_exch_y = prev.exchange_y;  g.p_read_y = prev.b_num != 0;
+        g.pa = prev.a;  g.pap = prev.a_peer;  g.pb = prev.b;  g.pbp = prev.b_peer;
+        g.new_exch_y = rd.exchange_y;
+        e = ceca::launch_margins_fused(g, vec, st);
+        cur = dst;
+        g.zin = rd.exchange_y ? cur + (int64_t)n * ld : cur;          // the half step reads z where the prologue put it
+      }
+      if (e != hipSuccess) return hip_fail(e, "margins kernel launch");
+      e = ceca::launch_halfstep(g, vec, st);
+      if (e != hipSuccess) return hip_fail(e, "half-step kernel launch");
+      prev = rd;
+    }
+    // the last iteration's combine, from wherever the state lives into S_out
+    ceca::ChainArgs a{};
+    a.xin = cur;  a.yin = cur + (int64_t)n * ld;
+    a.xout = S_out;  a.yout = S_out + (int64_t)n * ld;
+    a.ld = ld;
+    a.n = n;
+    a.lr = lr;
+    set_weights(prev, n, /*gossip_only=*/false, &a);
+    a.aux = V2[(iters - 1) & 1];
+    a.ldaux = p.ldv;
+    return run_chain(a, ceca::MODE_FROMV, d, vec && aligned16(S_out) && ld % 4 == 0, prev, port, st);
+  }
   ceca_loss_t one = *loss;
   if (!fused) {
     // one dsgd_ceca_step per iteration: the first from S_in to S_out, the rest in place on S_out

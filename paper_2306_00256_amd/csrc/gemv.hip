@@ -16,7 +16,12 @@ __device__ __forceinline__ int32_t uniform_i32(int32_t v) { return __builtin_amd
 // partial[(agent * nchunks + chunk) * B + j] = sum over the chunk's columns of A[row_j][col] * z[agent][col].
 // A workgroup takes one column chunk of kRowGroup sampled rows of one agent (grid: chunks x agents x row groups),
 // so few agents still spread over many workgroups.
-template <int VEC>
+// FUSE: the workgroup first finishes the iteration before for its agent and columns -- x+, y+ from x, y,
+// its own message and its peer's (Eqs. (8), (9), with the arithmetic of the combine kernel, operation
+// for operation) -- and takes the margins at the new z.  Every row group of an (agent, chunk) pair
+// computes the same x+, y+; the first one stores them, into a buffer other than the one they are read
+// from (the row groups run at the same time).
+template <int VEC, bool FUSE>
 __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
   using V = typename VecOf<VEC>::T;
   __shared__ float red[kBlock / 64][kRowGroup];
@@ -29,7 +34,36 @@ __global__ __launch_bounds__(kBlock) void margins_kernel(const GemvArgs G) {
   const int64_t c = (int64_t)chunk * G.chunk_cols + (int64_t)threadIdx.x * VEC;
   const bool on = c + VEC <= G.d;
   const int64_t col = on ? c : 0;
-  const V zv = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
+  V zv;
+  if (FUSE) {
+#pragma clang fp contract(off)
+    int p;
+    if (G.p_port == 2) {
+      p = agent - G.p_shift; if (p < 0) p += G.n;
+    } else {
+      p = (agent & 1) ? agent - G.p_shift : agent + G.p_shift;
+      if (p < 0) p += G.n;
+      if (p >= G.n) p -= G.n;
+    }
+    const int64_t off = (int64_t)agent * G.ld + col;
+    const V x = ld_plain<V>(G.px + off);
+    const V y = G.p_read_y || G.p_exch_y ? ld_plain<V>(G.py + off) : V(0.0f);
+    const V v = ld_plain<V>(G.pv + (int64_t)agent * G.ldv + col);
+    const V msg = ld_plain<V>(G.pv + (int64_t)p * G.ldv + col);
+    const V dz = v - (G.p_exch_y ? y : x);          // -lr e of the iteration before
+    const V xs = G.p_exch_y ? x + dz : v;
+    const V ys = G.p_exch_y ? v : y + dz;
+    const V xn = combine(G.pa, xs, G.pap, msg);
+    const V yn = G.p_read_y ? combine(G.pb, ys, G.pbp, msg) : G.pbp * msg;
+    if (on && blockIdx.z == 0) {
+      const int64_t oo = (int64_t)agent * G.ldo + col;
+      *reinterpret_cast<V*>(G.ox + oo) = xn;
+      *reinterpret_cast<V*>(G.oy + oo) = yn;
+    }
+    zv = G.new_exch_y ? yn : xn;
+  } else {
+    zv = ld_plain<V>(G.zin + (int64_t)agent * G.ld + col);
+  }
   const V z = on ? zv : V(0.0f);
   const int32_t* idx = G.batch_idx + (int64_t)agent * G.B;
   const float* Abase = G.A + (int64_t)agent * G.N * G.lda + col;
@@ -409,8 +443,18 @@ bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st) {
   if (g.nchunks < 1 || g.n > 65535) return hipErrorInvalidConfiguration;
   dim3 grid((unsigned)g.nchunks, (unsigned)g.n, (unsigned)((g.B + kRowGroup - 1) / kRowGroup)), block(kBlock);
-  if (vec4) margins_kernel<4><<<grid, block, 0, st>>>(g);
-  else margins_kernel<1><<<grid, block, 0, st>>>(g);
+  if (vec4) margins_kernel<4, false><<<grid, block, 0, st>>>(g);
+  else margins_kernel<1, false><<<grid, block, 0, st>>>(g);
+  return hipGetLastError();
+}
+
+hipError_t launch_margins_fused(const GemvArgs& g, bool vec4, hipStream_t st) {
+  if (g.nchunks < 1 || g.n > 65535) return hipErrorInvalidConfiguration;
+  // the row groups of an (agent, chunk) pair all read the old rows while the first one stores the new ones
+  if (g.px == g.ox || g.py == g.oy) return hipErrorInvalidValue;
+  dim3 grid((unsigned)g.nchunks, (unsigned)g.n, (unsigned)((g.B + kRowGroup - 1) / kRowGroup)), block(kBlock);
+  if (vec4) margins_kernel<4, true><<<grid, block, 0, st>>>(g);
+  else margins_kernel<1, true><<<grid, block, 0, st>>>(g);
   return hipGetLastError();
 }
 

@@ -92,8 +92,9 @@ struct GemvArgs {
   // z is then the x or y row (new_exch_y) of the state this prologue produces.
   const float* px;        // row 0 of x, y before that combine
   const float* py;
-  float* ox;              // row 0 of x, y after it (may be px, py: a workgroup touches only its agent's rows)
-  float* oy;
+  float* ox;              // row 0 of x, y after it (launch_grad_fused: may be px, py, a workgroup touches only its
+  float* oy;              // agent's rows, pitch ld; launch_margins_fused: another buffer, pitch ldo)
+  int64_t ldo;
   const float* pv;        // messages of the iteration before, [n][ldv]
   int32_t p_shift, p_port, p_exch_y, p_read_y;
   float pa, pap, pb, pbp; // its weights
@@ -190,6 +191,8 @@ extern std::atomic<int> g_mix_xcd;   // measurement knob: 0 = plain tile order i
 hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
 hipError_t launch_graph_rounds(const GraphArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
+// margins with the previous iteration's combine as prologue: reads px, py (pitch ld), stores ox, oy (pitch ldo)
+hipError_t launch_margins_fused(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);
 // measurement aid: o1, o2 <- elementwise functions of a, b, c (ngroups groups of 4 floats, 16-byte aligned)

@@ -1,6 +1,7 @@
-"""GPU parity: dsgd_ceca_run (several minibatch iterations per call; with many agents each iteration
-after the first is one kernel that also finishes the iteration before) against single dsgd_ceca_step
-calls (bit for bit) and against the fp64 oracle (1e-4 over the run)."""
+"""GPU parity: dsgd_ceca_run (several minibatch iterations per call; each iteration after the first finishes
+the iteration before inside its gradient kernel: one kernel per iteration where the one-pass gradient
+applies, two where the gradient takes two passes) against single dsgd_ceca_step calls (bit for bit) and
+against the fp64 oracle (1e-4 over the run)."""
 import numpy as np
 import pytest
 
@@ -43,7 +44,9 @@ def _problem(torch, Bn, kind, n, N, d, B, iters, seed, noise=0.0):
                                            (130, 1, 16384, 3, None), (131, 2, 1100, 40, None),
                                            (6, 1, 1000, 8, None), (5, 2, 4100, 7, None), (130, 2, 515, 4, None),
                                            (258, 1, 10, 50, None), (12, 2, 63, 9, None), (9, 2, 255, 20, 258),
-                                           (6, 1, 1023, 12, None), (6, 2, 1027, 5, None), (4, 2, 1000, 40, None)])
+                                           (6, 1, 1023, 12, None), (6, 2, 1027, 5, None), (4, 2, 1000, 40, None),
+                                           (6, 2, 10000, 32, None), (30, 1, 8192, 16, 8192 + 64), (7, 2, 2000, 33, 2064),
+                                           (6, 1, 1500, 6, 1501)])
 def test_run_equals_single_steps_and_oracle(env, kind, n, port, d, B, ld):
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
@@ -100,3 +103,27 @@ def test_single_iteration_and_argument_errors(env):
     with pytest.raises(P.CecaError) as e:
         P.dsgd_ceca_run(S2, T2, n, d, Bn.make_quad_center_loss(c, 0.0, 0, 0), idxd, 0.01, 0, 2, 2, workspace=ws)
     assert e.value.code == Bn.CECA_EINVAL
+
+
+@pytest.mark.parametrize("iters", [2, 3, 4, 5])
+@pytest.mark.parametrize("n,port,d,B", [(6, 2, 10000, 32), (6, 1, 2051, 9)])
+def test_two_pass_shapes_for_every_parity_of_the_iteration_count(env, iters, n, port, d, B):
+    """Shapes on the two-pass gradient alternate the state between S_out and a copy in the workspace: the
+    result must land in S_out for odd and even iteration counts, in place and out of place."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    N, lr = 12, 0.003
+    A, t, idx, Ad, td, idxd, code = _problem(torch, Bn, "logistic", n, N, d, B, iters, seed=iters)
+    tau = OS.num_rounds(n)
+    x0 = 0.05 * WL.initial_state(n, d, seed=3)
+    loss = Bn.make_minibatch_loss(code, Ad, td, N, B)
+    ws1 = _aligned(torch, P.dsgd_ceca_workspace_bytes(n, d, loss))
+    S = make_state(torch, x0)
+    for t_ in range(iters):
+        P.dsgd_ceca_step(S, S, n, d, loss, idxd[t_], lr, (1 + t_) % tau, port, workspace=ws1)
+    ws = _aligned(torch, P.dsgd_ceca_run_workspace_bytes(n, d, loss))
+    for inplace in (False, True):
+        A_ = make_state(torch, x0)
+        B_ = A_ if inplace else torch.full_like(A_, float("nan"))
+        P.dsgd_ceca_run(A_, B_, n, d, loss, idxd, lr, 1 % tau, iters, port, workspace=ws)
+        assert torch.equal(B_, S), (iters, inplace)
