@@ -215,3 +215,42 @@ def test_concurrent_calls_on_two_streams_from_two_threads(env):
             t.join()
         for i in range(2):
             assert np.array_equal(outs[i][0], serial[i]), i
+
+
+def test_graph_of_a_run_on_the_two_pass_gradient(env):
+    """dsgd_ceca_run on a shape whose gradient takes two passes (the state alternates between S_out and a copy
+    in the workspace): captured once, every replay continues the eager trajectory."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    n, d, N, B, iters, port = 6, 10000, 20, 32, 5, 2
+    A, t, _ = WL.logistic_data_sparse(n, N, d, seed=5, density=0.5)
+    idx = torch.from_numpy(WL.batch_indices(n, N, B, iters, seed=5)).cuda()
+    Ad, td = torch.from_numpy(A).cuda(), torch.from_numpy(t).cuda()
+    loss = Bn.make_minibatch_loss(Bn.LOSS_LOGISTIC, Ad, td, N, B)
+    ws = torch.empty(P.dsgd_ceca_run_workspace_bytes(n, d, loss) + 256, dtype=torch.uint8, device="cuda")
+    ws = ws[(-ws.data_ptr()) % 256:]
+    x0 = 0.1 * WL.initial_state(n, d, 6)
+    replays = 3
+    S = make_state(torch, x0)
+    eager = []
+    for _ in range(replays):
+        P.dsgd_ceca_run(S, S, n, d, loss, idx, 0.01, 0, iters, port, workspace=ws)
+        torch.cuda.synchronize()
+        eager.append(S.cpu().numpy().copy())
+    S2 = make_state(torch, x0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        P.dsgd_ceca_run(S2, S2, n, d, loss, idx, 0.01, 0, iters, port, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    S2.copy_(make_state(torch, x0))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        P.dsgd_ceca_run(S2, S2, n, d, loss, idx, 0.01, 0, iters, port, workspace=ws)
+    S2.copy_(make_state(torch, x0))
+    for rep in range(replays):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.isfinite(torch.randn(1024, device="cuda").sum().item())      # unrelated eager work in between
+        assert np.array_equal(S2.cpu().numpy(), eager[rep]), rep
