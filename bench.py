@@ -514,6 +514,13 @@ def main():
         out["fused_iterations"] = {k: main_res[k] for k in ("fused_iterations_per_call", "fused_ms_per_iteration",
                                                              "fused_agent_param_updates_per_s")}
         out["fused_iterations"]["speedup_over_value"] = main_res["fused_agent_param_updates_per_s"] / out["value"]
+    if args.workload == "quad31_2p" and not args.others:
+        # the configuration names one-port CECA, which needs an even number of agents: the same workload at
+        # n = 30 with one port (in place, closed pairs) beside the two-port run at the stated n = 31
+        comp = measure(torch, P, Bn, "quad30_1p", args.steps, args.warmup)
+        out["companion_1p"] = {"workload": "quad30_1p", "n_agents": 30, "port": 1, "ms_per_step": comp["ms_per_step"],
+                               "value": comp["agent_param_updates_per_s"], "achieved_GBs": comp["achieved_GBs"],
+                               "frac": comp["achieved_GBs"] / HBM_PEAK_GBS}
     if args.others:
         out["others"] = []
         for name in sorted(WL.SPECS):
