@@ -236,15 +236,16 @@ def test_gradient_kernels_agree_bit_for_bit(env):
     x0 = 0.05 * WL.initial_state(n, d, seed=4)
     outs = []
     try:
-        for knob in (0, 1000, 1, 3):
-            P.ceca_set_option(Bn.OPT_AGENTS_PER_WG, knob)
+        for chunked, per_wg in ((1, 0), (0, 0), (0, 1), (0, 3)):
+            P.ceca_set_option(Bn.OPT_CHUNKED_GRADIENT, chunked)
+            P.ceca_set_option(Bn.OPT_AGENTS_PER_WG, per_wg)
             S, T = make_state(torch, x0), make_state(torch, np.zeros_like(x0))
             for k in range(5):
                 P.dsgd_ceca_step(S, T, n, d, loss, idxd[k], 0.01, k % OS.num_rounds(n), port, workspace=ws)
                 S, T = T, S
             outs.append(S.clone())
     finally:
-        P.ceca_set_option(Bn.OPT_AGENTS_PER_WG, 0)
+        P.ceca_reset_options()
     assert all(torch.equal(outs[0], o) for o in outs[1:])
 
 
@@ -310,6 +311,95 @@ def test_many_agent_logistic(env):
     x0 = WL.initial_state(63, sp.d, sp.seed, kind="zero")
     (gx, gy), (x, y), _ = _run_minibatch(torch, P, "logistic", A, lab, idx, x0, 2, sp.lr, sp.iters)
     assert max(rel_err(gx, x)) <= TOL_RUN and max(rel_err(gy, y)) <= TOL_RUN
+
+
+@pytest.mark.timeout(1500)
+def test_many_agent_logistic_full_length(env, capsys):
+    """n = 1023, d = 4096, N = 512, B = 16, lr = 0.02 for ALL 2000 iterations, free-running, at full size:
+    once through dsgd_ceca_step (one call per iteration) and once through dsgd_ceca_run (windows of up to
+    200 iterations, the size bench.py uses; each iteration after a window's first is one kernel that also
+    finishes the iteration before), against the fp64 oracle in mirror mode on the host copy of the
+    device-drawn data.  Gates: max-norm and Frobenius relative error of x and of y at most 1e-4 at
+    iterations 40, 500 and 2000; the two device paths agree bit for bit.  Reports the consensus error and
+    the mean distance to the averaged model, as the configuration asks.  The oracle's 2000 iterations
+    take a few minutes of host time; progress lines go to the terminal so that the run is seen to be alive."""
+    import time
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    from oracle import consensus as OCN
+    sp = WL.SPECS["logistic1023_2p"]
+    n, d, N, B, iters = sp.n, sp.d, sp.N, sp.B, sp.iters
+    checkpoints = (40, 500, iters)
+    Ad, labd, _ = WL.device_logistic_sparse(n, N, d, sp.seed)
+    idx = WL.batch_indices(n, N, B, iters, sp.seed)
+    idxd = torch.from_numpy(idx).cuda()
+    loss = Bn.make_minibatch_loss(Bn.LOSS_LOGISTIC, Ad, labd, N, B)
+    ld = (d + 63) // 64 * 64
+    tau = OS.num_rounds(n)
+
+    # device path 1: one dsgd_ceca_step per iteration, two buffers alternating
+    ws = _workspace(torch, P, n, d, loss)
+    S = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
+    T = torch.empty_like(S)
+    snap_step = {}
+    for k in range(iters):
+        P.dsgd_ceca_step(S, T, n, d, loss, idxd[k], sp.lr, k % tau, 2, workspace=ws, ld=ld)
+        S, T = T, S
+        if k + 1 in checkpoints:
+            snap_step[k + 1] = S.clone()
+    # consensus observables of the final x rows, from the library
+    cws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+    cws = cws[(-cws.data_ptr()) % 256:]
+    cout = torch.zeros(5, dtype=torch.float64, device="cuda")
+    P.consensus_error(S[:n], n, d, cout, workspace=cws, ld=ld)
+    g_frob2, g_resid, g_max, g_norm, _ = cout.tolist()
+
+    # device path 2: dsgd_ceca_run in windows (none longer than 200 iterations, several starting rounds)
+    wsr = torch.empty(P.dsgd_ceca_run_workspace_bytes(n, d, loss) + 256, dtype=torch.uint8, device="cuda")
+    wsr = wsr[(-wsr.data_ptr()) % 256:]
+    R = torch.zeros((2 * n, ld), dtype=torch.float32, device="cuda")
+    windows = [37, 3, 160, 200, 100] + [200] * 7 + [100]
+    assert sum(windows) == iters
+    k0 = 0
+    for w in windows:
+        P.dsgd_ceca_run(R, R, n, d, loss, idxd[k0:k0 + w], sp.lr, k0 % tau, w, 2, workspace=wsr, ld=ld)
+        k0 += w
+        if k0 in checkpoints:
+            assert torch.equal(R, snap_step[k0]), f"dsgd_ceca_run and dsgd_ceca_step differ at iteration {k0}"
+    torch.cuda.synchronize()
+
+    # the oracle on the host copy of the same data
+    A, lab = Ad.cpu().numpy(), labd.cpu().numpy()
+    del Ad, labd, loss
+    torch.cuda.empty_cache()
+    grad = OL.make_minibatch_grad("logistic", A, lab, idx)
+    x = y = np.zeros((n, d))
+    t0 = time.perf_counter()
+    report = []
+    for k in range(iters):
+        x, y = OC.dsgd_ceca_step(x, y, k, 2, sp.lr, grad, store32=True)
+        if (k + 1) % 100 == 0:
+            with capsys.disabled():
+                print(f"\n  [logistic1023_2p full length] oracle iteration {k + 1}/{iters}, "
+                      f"{time.perf_counter() - t0:.0f} s", end="", flush=True)
+        if k + 1 in checkpoints:
+            gx, gy = split_state(snap_step[k + 1], n, d)
+            ex, ey = rel_err(gx, x), rel_err(gy, y)
+            report.append((k + 1, ex, ey))
+            assert max(ex) <= TOL_RUN and max(ey) <= TOL_RUN, (k + 1, ex, ey)
+            diff_f = float(np.sqrt(((gx - x) ** 2).sum()))      # the last checkpoint's value is used below
+    want = OCN.consensus_error(x)
+    with capsys.disabled():
+        for it, ex, ey in report:
+            print(f"\n  iteration {it}: rel. error of x (max-norm, Frobenius) = ({ex[0]:.2e}, {ex[1]:.2e}), "
+                  f"of y = ({ey[0]:.2e}, {ey[1]:.2e})", end="")
+        print(f"\n  after {iters} iterations: consensus error max_i ||x_i - xbar|| / ||xbar|| = {g_max / g_norm:.3e} "
+              f"(oracle {want['max_dev'] / want['mean_norm']:.3e}); mean distance to the averaged model "
+              f"(1/n) sum_i ||x_i - xbar|| = {g_resid / n:.4e} (oracle {want['residue'] / n:.4e})", flush=True)
+    # the device's observables of its own final state against the oracle's of its own: two states that differ
+    # by D in Frobenius norm have residues within 2 sqrt(n) D and mean norms within D / sqrt(n) of each other
+    assert abs(g_resid - want["residue"]) <= 2.0 * np.sqrt(n) * diff_f + 1e-9 * want["residue"]
+    assert abs(g_norm - want["mean_norm"]) <= diff_f / np.sqrt(n) + 1e-9 * want["mean_norm"]
 
 
 @pytest.mark.parametrize("name", ["paperlsq258_1p", "paperlsq258_2p"])
