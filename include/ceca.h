@@ -22,6 +22,11 @@
  *   - Any base pointer / leading dimension is accepted; 16-byte aligned bases with
  *     leading dimensions that are multiples of 4 take the vectorized kernels, other
  *     layouts silently take a scalar kernel with identical results.
+ *   - The functions declared here keep no mutable state between calls beyond the calling
+ *     thread's last error (ceca_last_error, ceca_last_hip_error) and may be called from
+ *     several threads at once.  Launch shapes are the library's own; the per-thread
+ *     overrides that tests and measurement sweeps use live in ceca_test.h, which is not
+ *     part of this interface.
  */
 #ifndef CECA_H
 #define CECA_H
@@ -261,44 +266,10 @@ int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d,
                           const int32_t* nbr, const float* w, const float* w_self, int32_t m,
                           int32_t period, int32_t k0, int32_t rounds, void* hip_stream);
 
-/* Measurement aid, not part of the method: an elementwise kernel with the traffic mix of the fused
- * quadratic-centre step (three streaming reads a, b, c and two streaming writes o1, o2 per element;
- * o1, o2 may be a, b), so that a benchmark can report, from the same run, the bandwidth the device gives
- * the simplest kernel with that mix.  All pointers device, 16-byte aligned, count floats (a multiple of 4). */
-int32_t ceca_stream_probe(const float* a, const float* b, const float* c, float* o1, float* o2, int64_t count,
-                          void* hip_stream);
-
 /* Message for the calling thread's most recent error ("" if none); valid until its next failing call. */
 const char* ceca_last_error(void);
 /* hipError_t value behind the calling thread's most recent CECA_EHIP (0 if none). */
 int32_t ceca_last_hip_error(void);
-
-/* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe against running calls):
- *   CECA_OPT_SEGMENT  agents a 2-port chain walks before it starts a new one (0 = library default)
- *   CECA_OPT_ROWS     0..32 (0 = library default).  Single rounds and steps: state rows whose loads one
- *                     thread keeps in flight, 1, 2, 4 or 8 (other values: 4).  Register-tile kernels: most
- *                     rows of the tile a thread holds -- 4..16 for ceca_gossip_rounds / ceca_average,
- *                     1..16 for dsgd_ceca_steps, 4..32 for ceca_mix_rounds and the single-pass consensus
- *                     (values outside a kernel's range leave that kernel at its default)
- *   CECA_OPT_BAND     column tiles (of 1024 columns) per band of the launch order (0 = library default)
- *   CECA_OPT_WG_PER_CU  cap on workgroups resident per compute unit, 2..8 (0 = library default)
- *   CECA_OPT_ONEPASS  1 (default): minibatch gradients keep the sampled rows in registers and read A once when
- *                     (B, d) fits; 0: always the two-pass margins / half-step kernels.  Also: 0 makes
- *                     ceca_graph_rounds read its tables from memory at every look-up (no staging in LDS)
- *   CECA_OPT_AGENTS_PER_WG  agents one workgroup of the looping one-pass gradient kernel takes in turn
- *                     (0 = library default); 1000: never use the chunked gradient kernel
- *   CECA_OPT_CONS_SINGLE_PASS  1 (default): consensus observables read x once when a workgroup's registers can
- *                     hold a column tile of every agent; 0: always the two-pass kernels
- *   CECA_OPT_XCD_TILE_ORDER  1 (default): register-tile kernels whose tile rows are narrower than 128 bytes give
- *                     each of the 8 XCDs a contiguous run of tiles; 0: plain order
- *   CECA_OPT_TILE_THREADS  threads per workgroup of the fused rounds, fused iterations and mixing kernels:
- *                     256, 512 or 1024 (0 = library default); more threads make the rows of a tile
- *                     wider.  A tile shape that cannot hold n agents is replaced by the library's own
- * Returns CECA_EINVAL for an unknown option or value. */
-enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5,
-       CECA_OPT_AGENTS_PER_WG = 7, CECA_OPT_CONS_SINGLE_PASS = 8, CECA_OPT_XCD_TILE_ORDER = 9,
-       CECA_OPT_TILE_THREADS = 10 };
-int32_t ceca_set_option(int32_t option, int32_t value);
 
 #ifdef __cplusplus
 }

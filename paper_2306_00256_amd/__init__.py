@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     ceca_gossip_rounds,
     ceca_graph_rounds,
     ceca_mix_rounds,
+    ceca_reset_options,
     ceca_schedule,
     ceca_set_option,
     ceca_stream_probe,

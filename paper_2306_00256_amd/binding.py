@@ -10,15 +10,18 @@ _LIB_PATH = os.path.join(_HERE, "libceca.so")
 
 CECA_OK, CECA_EINVAL, CECA_EODD1P, CECA_EWORKSPACE, CECA_EHIP = 0, -1, -2, -3, -4
 LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER, LOSS_GRADIENT = 0, 1, 2, 3
+# options of the test and measurement interface (include/ceca_test.h)
 OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS, OPT_AGENTS_PER_WG, OPT_CONS_SINGLE_PASS, OPT_XCD_TILE_ORDER, OPT_TILE_THREADS = 1, 2, 3, 4, 5, 7, 8, 9, 10
+OPT_GRAPH_STAGE, OPT_CHUNKED_GRADIENT, OPT_CONS_STRIPS, OPT_PROBE_WAVES = 11, 12, 13, 14
 TOPO_RING, TOPO_STATIC_EXP, TOPO_ONE_PEER_EXP = 0, 1, 2
 MIX_MAX = 16
 
 EXPORTS = (
     "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "ceca_average", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps", "dsgd_ceca_run_workspace_bytes", "dsgd_ceca_run",
-    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_graph_rounds", "ceca_stream_probe", "ceca_last_error", "ceca_last_hip_error",
-    "ceca_set_option",
+    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_graph_rounds", "ceca_last_error", "ceca_last_hip_error",
 )
+# include/ceca_test.h: launch-shape overrides and probe kernels for tests and measurement, not the product ABI
+TEST_EXPORTS = ("ceca_set_option", "ceca_reset_options", "ceca_stream_probe")
 
 
 class CecaError(RuntimeError):
@@ -102,8 +105,10 @@ def lib():
         L.ceca_graph_rounds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         L.ceca_graph_rounds.restype = C.c_int32
-        L.ceca_stream_probe.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_void_p]
+        L.ceca_stream_probe.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
         L.ceca_stream_probe.restype = C.c_int32
+        L.ceca_reset_options.argtypes = []
+        L.ceca_reset_options.restype = C.c_int32
         L.ceca_last_error.restype = C.c_char_p
         L.ceca_last_hip_error.restype = C.c_int32
         L.ceca_set_option.argtypes = [C.c_int32, C.c_int32]
@@ -236,13 +241,20 @@ def ceca_state_consensus(S, n: int, d: int, out, workspace=None, ld: Optional[in
     _check(lib().ceca_state_consensus(_ptr(S), n, d, ld, _ptr(out), _ptr(workspace), wbytes, _stream(stream)))
 
 
-def ceca_stream_probe(a, b, c, o1, o2, count: int, stream=None) -> None:
-    """Measurement aid: elementwise kernel with three streaming reads and two streaming writes per element."""
-    _check(lib().ceca_stream_probe(_ptr(a), _ptr(b), _ptr(c), _ptr(o1), _ptr(o2), count, _stream(stream)))
+def ceca_stream_probe(a, b, c, o1, o2, count: int, reads: int = 3, writes: int = 2, stream=None) -> None:
+    """Measurement aid (ceca_test.h): elementwise kernel with `reads` streaming reads (of a, b, c) and `writes`
+    streaming writes (of o1, o2) per element."""
+    _check(lib().ceca_stream_probe(_ptr(a), _ptr(b), _ptr(c), _ptr(o1), _ptr(o2), count, reads, writes, _stream(stream)))
 
 
 def ceca_set_option(option: int, value: int) -> None:
+    """Launch-shape override of the calling thread (ceca_test.h)."""
     _check(lib().ceca_set_option(option, value))
+
+
+def ceca_reset_options() -> None:
+    """Every launch-shape override of the calling thread back to the library default (ceca_test.h)."""
+    _check(lib().ceca_reset_options())
 
 
 def make_minibatch_loss(kind: int, A, t, N: int, B: int, grad_scale: float = 0.0, noise_std: float = 0.0,

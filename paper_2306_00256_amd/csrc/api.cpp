@@ -2,27 +2,26 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
 #include <numeric>
 
 #include "ceca.h"
+#include "ceca_test.h"
 #include "launch.h"
 #include "schedule.h"
 
+namespace ceca {
+thread_local Tuning g_tuning{};     // all zero: the library's own launch shapes
+}
+
 namespace {
+
+using ceca::g_tuning;
 
 thread_local char g_msg[256] = "";
 thread_local int32_t g_hip = 0;
-std::atomic<int32_t> g_opt_segment{0};
-std::atomic<int32_t> g_opt_rows{0};
-std::atomic<int32_t> g_opt_band{0};
-std::atomic<int32_t> g_opt_wgs{0};
-std::atomic<int32_t> g_opt_onepass{1};
-std::atomic<int32_t> g_opt_cons_tile{1};
-std::atomic<int32_t> g_opt_tile_threads{0};
 
 int32_t fail(int32_t code, const char* fmt, ...) {
   va_list ap;
@@ -88,7 +87,7 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place,
   // In place only whole cycles are safe.  Out of place, measurements on MI355X favour one-row
   // stretches: the device then sweeps the rows of a column band one at a time (few concurrent DRAM
   // streams), and the message a stretch re-reads is still in L2 from the stretch before it.
-  int32_t seg_len = in_place ? len : g_opt_segment.load();
+  int32_t seg_len = in_place ? len : g_tuning.segment;
   if (seg_len <= 0) seg_len = default_seg;
   if (seg_len > len) seg_len = len;
   // a launch addresses fewer than 2^24 workgroups: huge problems walk longer stretches
@@ -101,9 +100,9 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place,
 
 int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ceca_round_t& rd, int32_t port,
                   hipStream_t st) {
-  int rows = g_opt_rows.load();
-  a.band = (uint32_t)g_opt_band.load();
-  a.wg_per_cu = g_opt_wgs.load();
+  int rows = g_tuning.rows;
+  a.band = (uint32_t)g_tuning.band;
+  a.wg_per_cu = g_tuning.wg_per_cu;
   // combining from stored messages reads no other agent's state rows, so it can overwrite the state
   // row by row with any stretch length; the other modes may only run whole cycles in place
   const bool in_place = a.xin == a.xout && mode != ceca::MODE_FROMV;
@@ -208,15 +207,53 @@ int32_t check_loss(const ceca_loss_t* loss, int64_t d, bool need_batch, const in
   }
 }
 
+// Consensus observables come in three forms (all deterministic, fp64 accumulation):
+//   WAVE      one pass, a wavefront holds a column strip of every agent (no LDS): up to 64 x 32 agents
+//   TILE      one pass, a workgroup holds a column tile of every agent and reduces through LDS
+//   TWO_PASS  column sums, mean, then per-agent squared deviations (x read twice)
+enum ConsForm { CONS_TWO_PASS = 1, CONS_TILE = 2, CONS_WAVE = 3 };
+
+// Partial sums of the WAVE form are capped at this many bytes whatever the launch shape, so that the
+// workspace bound does not depend on the calling thread's tuning.
+constexpr int64_t kConsWavePartialBytes = 12LL << 20;
+constexpr int64_t kConsWaves = 1024;     // wavefronts of the WAVE form: one per SIMD of an MI355X
+
 struct ConsPlan {
+  // two-pass form
   int64_t ntiles;
   int32_t agent_groups, agents_per_group, dev_agents;
-  int64_t off_norm, off_devpart, off_dev2, total;
-  // single-pass form: rows per thread (0 = not available for this n), row lanes, tiles for 16-byte / scalar groups
+  int64_t off_norm, off_devpart, off_dev2, off_counter, two_pass_total;
+  // TILE form: rows per thread (0 = not available for this n), row lanes, tiles for 16-byte / scalar groups
   int32_t rows_per_thread, row_lanes;
   int64_t tile_ntiles_vec, tile_ntiles_scalar;
-  int64_t tile_off_devpart, tile_off_dev2;     // (normpart sits at offset 0)
+  int64_t tile_total;          // workspace of the TILE form on a layout without 16-byte alignment (the larger one)
+  // WAVE form: column groups per strip (0 = not available), rows per lane, most wavefronts
+  int32_t wave_cgs, wave_shift, wave_rows;
+  int64_t wave_cap;            // most wavefronts (bounds the partial sums)
+  bool wave_default;           // the library's own choice for this n
+  int64_t bound;               // workspace that covers every form and launch shape
 };
+
+struct ConsWave { int64_t strips, nwaves, off_dev2, off_counter, total; };
+
+// The WAVE form's launch for this layout: strips of wave_cgs column groups, strips per wavefront.
+ConsWave cons_wave(const ConsPlan& p, int32_t n, int64_t d, bool vec4) {
+  ConsWave w;
+  const int64_t ngroups = vec4 ? (d + 3) / 4 : d;
+  w.strips = (ngroups + p.wave_cgs - 1) / p.wave_cgs;
+  // Measured on MI355X (n = 16 ... 130, 0.3 to 3 GB): the pass is fastest with exactly one wavefront per SIMD
+  // (256 compute units x 4), each holding many rows in flight and walking its share of the strips; at
+  // n = 31, d = 25.6 M that streams 7.0 TB/s, what a plain read-only kernel reaches, against 5.4 TB/s with
+  // 50,000 short-lived wavefronts.  More wavefronts only add row streams that compete for DRAM pages.
+  int64_t per = g_tuning.cons_strips;
+  if (per <= 0) per = std::max<int64_t>((w.strips + kConsWaves - 1) / kConsWaves, 1);
+  per = std::max(per, (w.strips + p.wave_cap - 1) / p.wave_cap);
+  w.nwaves = (w.strips + per - 1) / per;
+  w.off_dev2 = round_up(((int64_t)n + 1) * w.nwaves * 8, 256);
+  w.off_counter = w.off_dev2 + round_up(((int64_t)n + 1) * 8, 256);
+  w.total = w.off_counter + 256;
+  return w;
+}
 
 ConsPlan cons_plan(int32_t n, int64_t d) {
   ConsPlan p;
@@ -239,30 +276,65 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
   p.off_norm = off;     off += round_up(p.ntiles * 8, 256);
   p.off_devpart = off;  off += round_up((int64_t)n * p.ntiles * 8, 256);
   p.off_dev2 = off;     off += round_up((int64_t)n * 8, 256);
-  p.total = off;
-  // single pass: every agent's column tile in one workgroup (x-only tiling of the fused-round kernels)
+  p.off_counter = off;  off += 256;
+  p.two_pass_total = off;
+  p.bound = off;
+  // TILE form: every agent's column tile in one workgroup (x-only tiling of the fused-round kernels)
   p.rows_per_thread = 0;
   p.row_lanes = 0;
-  int32_t cap = g_opt_rows.load();
-  if (cap < 4 || cap > 32) cap = n <= 32 ? 16 : 32;     // wide tiles measured best on MI355X (n = 31, 100, 1023)
-  int32_t row_lanes = 1;
-  while (row_lanes * cap < n) row_lanes *= 2;
-  while (row_lanes <= ceca::kBlock && ((int64_t)n + 1) * (ceca::kBlock / row_lanes) * 8 > 65536) row_lanes *= 2;
-  // rows of the tile narrower than 128 bytes read poorly: with that many agents the single pass is kept
-  // only for small problems, where the two-pass form is bound by its five launches
-  const bool wide_enough = ceca::kBlock / (row_lanes < ceca::kBlock ? row_lanes : ceca::kBlock) >= 8 ||
-                           (int64_t)n * d * 4 <= (64LL << 20);
-  if (row_lanes <= ceca::kBlock && (n + row_lanes - 1) / row_lanes <= 32 && wide_enough) {
-    p.row_lanes = row_lanes;
-    p.rows_per_thread = (n + row_lanes - 1) / row_lanes;
-    const int64_t lanes = ceca::kBlock / row_lanes;
-    p.tile_ntiles_vec = ((d + 3) / 4 + lanes - 1) / lanes;
-    p.tile_ntiles_scalar = (d + lanes - 1) / lanes;
-    int64_t o = round_up(p.tile_ntiles_scalar * 8, 256);
-    p.tile_off_devpart = o;  o += round_up((int64_t)n * p.tile_ntiles_scalar * 8, 256);
-    p.tile_off_dev2 = o;     o += round_up((int64_t)n * 8, 256);
-    if (o > p.total) p.total = o;
+  p.tile_total = 0;
+  {
+    // the widest tile (32 rows per thread) bounds the workspace of every tuned shape: fewer rows per thread
+    // mean more row lanes, narrower tiles and more of them
+    int32_t cap = g_tuning.rows;
+    if (cap < 4 || cap > 32) cap = n <= 32 ? 16 : 32;     // wide tiles measured best on MI355X (n = 31, 100, 1023)
+    int32_t row_lanes = 1;
+    while (row_lanes * cap < n) row_lanes *= 2;
+    while (row_lanes <= ceca::kBlock && ((int64_t)n + 1) * (ceca::kBlock / row_lanes) * 8 > 65536) row_lanes *= 2;
+    // rows of the tile narrower than 128 bytes read poorly: with that many agents the single pass is kept
+    // only for small problems, where the two-pass form is bound by its five launches
+    const bool wide_enough = ceca::kBlock / (row_lanes < ceca::kBlock ? row_lanes : ceca::kBlock) >= 8 ||
+                             (int64_t)n * d * 4 <= (64LL << 20);
+    if (row_lanes <= ceca::kBlock && (n + row_lanes - 1) / row_lanes <= 32 && wide_enough) {
+      p.row_lanes = row_lanes;
+      p.rows_per_thread = (n + row_lanes - 1) / row_lanes;
+      const int64_t lanes = ceca::kBlock / row_lanes;
+      p.tile_ntiles_vec = ((d + 3) / 4 + lanes - 1) / lanes;
+      p.tile_ntiles_scalar = (d + lanes - 1) / lanes;
+    }
+    if (p.rows_per_thread > 0) {
+      p.tile_total = round_up(p.tile_ntiles_scalar * 8, 256) + round_up((int64_t)n * p.tile_ntiles_scalar * 8, 256) +
+                     round_up((int64_t)n * 8, 256) + 256;
+    }
   }
+  // WAVE form
+  p.wave_cgs = 0;
+  p.wave_default = false;
+  {
+    // Rows per lane, measured on MI355X with one wavefront per SIMD: 16 up to 64 agents (n = 31: two row lanes
+    // beat one lane with 31 rows, n = 64: four beat two), 32 beyond (n = 100, 128: four row lanes with 25 / 32
+    // rows beat eight with 13 / 16: a strip is 256 bytes per agent instead of 128)
+    int32_t cap = g_tuning.rows;
+    if (cap < 1 || cap > 32) cap = n <= 64 ? 16 : 32;
+    int32_t row_lanes = 1;
+    while (row_lanes * cap < n) row_lanes *= 2;
+    if (row_lanes <= 64) {
+      p.wave_cgs = 64 / row_lanes;
+      p.wave_shift = 0;
+      while ((1 << p.wave_shift) < p.wave_cgs) ++p.wave_shift;
+      p.wave_rows = (n + row_lanes - 1) / row_lanes;
+      p.wave_cap = std::max<int64_t>(kConsWavePartialBytes / (((int64_t)n + 1) * 8), 64);
+      // strips of 128 bytes per agent still win (n = 130: 0.072 against 0.077 ms for the workgroup tiles on
+      // 273 MB); at 64 bytes (n = 258) the tiles do
+      p.wave_default = p.wave_cgs >= 8;
+    }
+  }
+  // the WAVE form never exceeds its cap whatever its launch shape; the TILE form's share follows the
+  // calling thread's tuning (ask for the size after setting the options)
+  const int64_t wave_bound = round_up(((int64_t)n + 1) * std::max<int64_t>(kConsWavePartialBytes / (((int64_t)n + 1) * 8), 64) * 8, 256) +
+                             round_up(((int64_t)n + 1) * 8, 256) + 256;
+  p.bound = std::max(p.bound, wave_bound);
+  p.bound = std::max(p.bound, p.tile_total);
   return p;
 }
 
@@ -296,9 +368,9 @@ template <typename Threads, typename Cap>
 TileShape pick_tile(int32_t n, bool vec4, int32_t cap_lo, int32_t cap_hi_256, int32_t cap_hi_wide, Threads threads_for, Cap cap_for) {
   const int32_t dflt_threads = vec4 ? threads_for(n) : ceca::kBlock;
   const TileShape dflt = shape_tile(n, vec4, dflt_threads, cap_for(dflt_threads));
-  int32_t threads = vec4 ? g_opt_tile_threads.load() : ceca::kBlock;
+  int32_t threads = vec4 ? g_tuning.tile_threads : ceca::kBlock;
   if (threads == 0) threads = dflt_threads;
-  int32_t cap = g_opt_rows.load();
+  int32_t cap = g_tuning.rows;
   if (cap < cap_lo || cap > (threads == ceca::kBlock ? cap_hi_256 : cap_hi_wide)) cap = cap_for(threads);
   const TileShape t = shape_tile(n, vec4, threads, cap);
   return t.ok ? t : dflt;
@@ -385,44 +457,65 @@ const char* ceca_last_error(void) { return g_msg; }
 int32_t ceca_last_hip_error(void) { return g_hip; }
 
 int32_t ceca_set_option(int32_t option, int32_t value) {
+  ceca::Tuning& t = ceca::g_tuning;
   switch (option) {
     case CECA_OPT_SEGMENT:
       if (value < 0) return fail(CECA_EINVAL, "segment length must be >= 0");
-      g_opt_segment.store(value);
+      t.segment = value;
       return CECA_OK;
     case CECA_OPT_ROWS:
       if (value < 0 || value > 32) return fail(CECA_EINVAL, "rows must be 0..32");
-      g_opt_rows.store(value);
+      t.rows = value;
       return CECA_OK;
     case CECA_OPT_WG_PER_CU:
       if (value < 0 || value > 8) return fail(CECA_EINVAL, "workgroups per CU must be 0..8");
-      g_opt_wgs.store(value);
+      t.wg_per_cu = value;
       return CECA_OK;
     case CECA_OPT_ONEPASS:
-      g_opt_onepass.store(value != 0);
+      t.two_pass_gradient = value == 0;
       return CECA_OK;
     case CECA_OPT_CONS_SINGLE_PASS:
-      g_opt_cons_tile.store(value != 0);
+      if (value < 0 || value > 3) return fail(CECA_EINVAL, "consensus form must be 0..3");
+      t.cons_form = value == 1 ? 0 : (value == 0 ? 1 : value);
       return CECA_OK;
     case CECA_OPT_TILE_THREADS:
       if (value != 0 && value != 256 && value != 512 && value != 1024)
         return fail(CECA_EINVAL, "tile threads must be 0, 256, 512 or 1024");
-      g_opt_tile_threads.store(value);
+      t.tile_threads = value;
       return CECA_OK;
     case CECA_OPT_XCD_TILE_ORDER:
-      ceca::g_mix_xcd.store(value != 0);
+      t.plain_tile_order = value == 0;
       return CECA_OK;
     case CECA_OPT_AGENTS_PER_WG:
       if (value < 0) return fail(CECA_EINVAL, "agents per workgroup must be >= 0");
-      ceca::g_agents_per_wg.store(value);
+      t.agents_per_wg = value;
       return CECA_OK;
     case CECA_OPT_BAND:
       if (value < 0) return fail(CECA_EINVAL, "band width must be >= 0");
-      g_opt_band.store(value);
+      t.band = value;
+      return CECA_OK;
+    case CECA_OPT_GRAPH_STAGE:
+      t.graph_tables_in_memory = value == 0;
+      return CECA_OK;
+    case CECA_OPT_CHUNKED_GRADIENT:
+      t.never_chunked = value == 0;
+      return CECA_OK;
+    case CECA_OPT_PROBE_WAVES:
+      if (value < 0 || value > (1 << 20)) return fail(CECA_EINVAL, "probe wavefronts must be 0..2^20");
+      t.probe_waves = value;
+      return CECA_OK;
+    case CECA_OPT_CONS_STRIPS:
+      if (value < 0 || value > 4096) return fail(CECA_EINVAL, "strips per wavefront must be 0..4096");
+      t.cons_strips = value;
       return CECA_OK;
     default:
       return fail(CECA_EINVAL, "unknown option %d", option);
   }
+}
+
+int32_t ceca_reset_options(void) {
+  ceca::g_tuning = ceca::Tuning{};
+  return CECA_OK;
 }
 
 int32_t ceca_tau(int32_t n) {
@@ -474,7 +567,7 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
   // n = 1026, 2050 and 4096).
   const int32_t row_bytes = can_vec ? tv.row_bytes(true) : ts.row_bytes(false);
   const int32_t worth = row_bytes >= 64 ? (tv.threads == 1024 && can_vec ? 3 : 2) : 5;
-  const bool knobs = g_opt_rows.load() != 0 || g_opt_tile_threads.load() != 0;
+  const bool knobs = g_tuning.rows != 0 || g_tuning.tile_threads != 0;
   // (rounds after the first run in place on S_out: with two ports those walk whole cycles, which needs
   // many column tiles to fill the device)
   const bool rounds_fill = port == 1 || d >= 1024 * 1024 || rounds == 1;
@@ -634,7 +727,7 @@ int32_t dsgd_ceca_step(const float* S_in, float* S_out, int32_t n, int64_t d, in
   g.chunk_cols = ceca::kBlock * ceca::kChunkGroups * (gemv_vec ? 4 : 1);
   g.nchunks = (int32_t)((d + g.chunk_cols - 1) / g.chunk_cols);
   hipError_t e = hipSuccess;
-  const bool onepass = g_opt_onepass.load() != 0 &&
+  const bool onepass = !g_tuning.two_pass_gradient &&
                        (gemv_vec ? ceca::launch_grad_onepass(g, st, &e) : ceca::launch_grad_scalar(g, st, &e));
   if (onepass) {
     if (e != hipSuccess) return hip_fail(e, "one-pass gradient kernel launch");
@@ -691,13 +784,13 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
   const bool lay = ld % 4 == 0 && aligned16(loss->A) && loss->lda % 4 == 0 && d % 4 == 0;
   const bool vec = lay && aligned16(S_in);
   const bool same_layout = vec == (lay && aligned16(S_out));
-  const bool fused = same_layout && n > 1 && iters > 1 && g_opt_onepass.load() != 0 && ceca::g_agents_per_wg.load() != 1000 &&
+  const bool fused = same_layout && n > 1 && iters > 1 && !g_tuning.two_pass_gradient && !g_tuning.never_chunked &&
                      ceca::grad_fused_covers(n, d, loss->B, vec);
   // Shapes whose single step takes the two-pass gradient (margins, then half step): the combine of the
   // iteration before becomes the prologue of the margins kernel -- two launches per iteration instead of
   // three, same bits.  The row groups of that kernel all read the old rows while one of them stores the
   // new ones, so the state alternates between S_out and a copy in the workspace.
-  const bool two_pass = g_opt_onepass.load() == 0 || !(vec ? ceca::grad_fused_covers(n, d, loss->B, true) : d <= 1024);
+  const bool two_pass = g_tuning.two_pass_gradient || !(vec ? ceca::grad_fused_covers(n, d, loss->B, true) : d <= 1024);
   const bool copy_fits = 2 * (int64_t)n * ld * (int64_t)sizeof(float) <= run_state_bytes(n, d);     // the copy keeps the caller's pitch
   if (!fused && two_pass && same_layout && copy_fits && n > 1 && iters > 1 && n <= 65535) {
     float* V2[2] = {reinterpret_cast<float*>(w), reinterpret_cast<float*>(w + p.v_bytes)};
@@ -849,7 +942,7 @@ int32_t dsgd_ceca_steps(const float* S_in, float* S_out, int32_t n, int64_t d, i
   // (the steps after the first run in place on S_out: with two ports those walk whole cycles, which
   // needs many column tiles to fill the device)
   const bool steps_fill = port == 1 || d >= 1024 * 1024;
-  const bool knobs = g_opt_rows.load() != 0 || g_opt_tile_threads.load() != 0;
+  const bool knobs = g_tuning.rows != 0 || g_tuning.tile_threads != 0;
   if (n == 1 || !tv.ok || !ts.ok || (steps < worth && steps_fill && !knobs)) {
     ceca_loss_t one = *loss;
     for (int32_t t = 0; t < steps; ++t) {
@@ -975,7 +1068,7 @@ int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d,
   g.xin = X_in;  g.xout = X_out;  g.ld = ld;
   g.nbr = nbr;  g.w = w;  g.w_self = w_self;
   g.n = n;  g.m = m;  g.rounds = rounds;  g.period = period;  g.k0 = k0 % period;
-  g.stage = g_opt_onepass.load() != 0;      // (CECA_OPT_ONEPASS doubles as the switch of the staged tables)
+  g.stage = !g_tuning.graph_tables_in_memory;
   hipStream_t st = (hipStream_t)hip_stream;
   const bool can_vec = aligned16(X_in) && aligned16(X_out) && ld % 4 == 0;
   const int64_t d4 = can_vec ? d / 4 : 0;
@@ -995,57 +1088,97 @@ int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d,
 }
 
 int32_t ceca_stream_probe(const float* a, const float* b, const float* c, float* o1, float* o2, int64_t count,
-                          void* hip_stream) {
-  if (!a || !b || !c || !o1 || !o2) return fail(CECA_EINVAL, "null pointer");
+                          int32_t reads, int32_t writes, void* hip_stream) {
+  if (reads < 1 || reads > 3 || writes < 0 || writes > 2) return fail(CECA_EINVAL, "the probe takes 1..3 reads and 0..2 writes");
+  if (!a || (reads >= 2 && !b) || (reads >= 3 && !c) || !o1 || (writes >= 2 && !o2)) return fail(CECA_EINVAL, "null pointer");
   if (count < 4 || count % 4 != 0) return fail(CECA_EINVAL, "count must be a positive multiple of 4");
   if (!aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(o1) || !aligned16(o2))
     return fail(CECA_EINVAL, "the probe takes 16-byte aligned arrays");
-  const hipError_t e = ceca::launch_stream_probe(a, b, c, o1, o2, count / 4, (hipStream_t)hip_stream);
+  const hipError_t e = ceca::launch_stream_probe(a, b, c, o1, o2, count / 4, reads, writes, (hipStream_t)hip_stream);
   if (e != hipSuccess) return hip_fail(e, "probe kernel launch");
   return CECA_OK;
 }
 
 int64_t consensus_error_workspace_bytes(int32_t n, int64_t d) {
   if (n < 1 || d < 1) return fail(CECA_EINVAL, "need n >= 1 and d >= 1");
-  return cons_plan(n, d).total;
+  return cons_plan(n, d).bound;
 }
+
+namespace {
+
+// The consensus kernels on `workspace` (checked by the caller to be 256-byte aligned); *need receives the
+// bytes this problem's form uses, and nothing is launched when `have` is smaller.
+int32_t run_consensus(const float* X, int32_t n, int64_t d, int64_t ld, double* out, float* xbar_or_null,
+                      char* w, int64_t have, int64_t* need, hipStream_t st) {
+  const ConsPlan p = cons_plan(n, d);
+  ceca::ConsensusArgs c{};
+  c.X = X;  c.ld = ld;  c.d = d;  c.n = n;
+  c.out = out;
+  c.xbar = xbar_or_null;
+  const bool vec = aligned16(X) && ld % 4 == 0 && d % 4 == 0;
+  const int32_t forced = g_tuning.cons_form;
+  int form = CONS_TWO_PASS;
+  if (forced == CONS_WAVE ? p.wave_cgs > 0 : (forced == 0 && p.wave_cgs > 0 && p.wave_default)) form = CONS_WAVE;
+  else if (forced != CONS_TWO_PASS && p.rows_per_thread > 0) form = CONS_TILE;
+  if (form == CONS_WAVE) {
+    const ConsWave cw = cons_wave(p, n, d, vec);
+    *need = cw.total;
+    if (have < cw.total) return CECA_EWORKSPACE;
+    c.wave_cgs = p.wave_cgs;  c.cg_shift = p.wave_shift;  c.rows_per_thread = p.wave_rows;
+    c.strips = cw.strips;  c.nwaves = cw.nwaves;
+    c.devpart = reinterpret_cast<double*>(w);
+    c.dev2 = reinterpret_cast<double*>(w + cw.off_dev2);
+    c.counter = reinterpret_cast<uint32_t*>(w + cw.off_counter);
+  } else if (form == CONS_TILE) {
+    // single pass over x; the workspace then holds only the partials: normpart[ntiles], devpart[n][ntiles], dev2[n]
+    c.ntiles = vec ? p.tile_ntiles_vec : p.tile_ntiles_scalar;
+    const int64_t off_devpart = round_up(c.ntiles * 8, 256);
+    const int64_t off_dev2 = off_devpart + round_up((int64_t)n * c.ntiles * 8, 256);
+    const int64_t off_counter = off_dev2 + round_up((int64_t)n * 8, 256);
+    *need = off_counter + 256;
+    if (have < *need) return CECA_EWORKSPACE;
+    c.counter = reinterpret_cast<uint32_t*>(w + off_counter);
+    c.rows_per_thread = p.rows_per_thread;
+    c.row_lanes = p.row_lanes;
+    c.normpart = reinterpret_cast<double*>(w);
+    c.devpart = reinterpret_cast<double*>(w + off_devpart);
+    c.dev2 = reinterpret_cast<double*>(w + off_dev2);
+  } else {
+    *need = p.two_pass_total;
+    if (have < p.two_pass_total) return CECA_EWORKSPACE;
+    c.agent_groups = p.agent_groups;
+    c.agents_per_group = p.agents_per_group;
+    c.dev_agents = p.dev_agents;
+    c.ntiles = p.ntiles;
+    c.colsum = reinterpret_cast<double*>(w);
+    c.normpart = reinterpret_cast<double*>(w + p.off_norm);
+    c.devpart = reinterpret_cast<double*>(w + p.off_devpart);
+    c.dev2 = reinterpret_cast<double*>(w + p.off_dev2);
+    c.counter = reinterpret_cast<uint32_t*>(w + p.off_counter);
+  }
+  const hipError_t e = ceca::launch_consensus(c, vec, st);
+  if (e != hipSuccess) return hip_fail(e, "consensus kernels launch");
+  return CECA_OK;
+}
+
+}  // namespace
 
 int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double* out, float* xbar_or_null,
                         void* workspace, int64_t workspace_bytes, void* hip_stream) {
   if (!X || !out) return fail(CECA_EINVAL, "null pointer");
   if (n < 1 || d < 1 || ld < d) return fail(CECA_EINVAL, "need n >= 1 and 1 <= d <= ld");
-  const ConsPlan p = cons_plan(n, d);
-  if (!workspace || workspace_bytes < p.total)
-    return fail(CECA_EWORKSPACE, "workspace of %lld bytes needed, %lld given", (long long)p.total,
+  const int64_t bound = cons_plan(n, d).bound;
+  if (!workspace || workspace_bytes < bound)
+    return fail(CECA_EWORKSPACE, "workspace of %lld bytes needed, %lld given", (long long)bound,
                 (long long)(workspace ? workspace_bytes : 0));
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(CECA_EWORKSPACE, "workspace must be 256-byte aligned");
-  char* w = reinterpret_cast<char*>(workspace);
-  ceca::ConsensusArgs c{};
-  c.X = X;  c.ld = ld;  c.d = d;  c.n = n;
-  c.agent_groups = p.agent_groups;
-  c.agents_per_group = p.agents_per_group;
-  c.dev_agents = p.dev_agents;
-  c.ntiles = p.ntiles;
-  c.colsum = reinterpret_cast<double*>(w);
-  c.normpart = reinterpret_cast<double*>(w + p.off_norm);
-  c.devpart = reinterpret_cast<double*>(w + p.off_devpart);
-  c.dev2 = reinterpret_cast<double*>(w + p.off_dev2);
-  c.out = out;
-  c.xbar = xbar_or_null;
-  const bool vec = aligned16(X) && ld % 4 == 0 && d % 4 == 0;
-  if (p.rows_per_thread > 0 && g_opt_cons_tile.load() != 0) {
-    // single pass over x; the workspace then holds only the partials
-    c.rows_per_thread = p.rows_per_thread;
-    c.row_lanes = p.row_lanes;
-    c.ntiles = vec ? p.tile_ntiles_vec : p.tile_ntiles_scalar;
-    c.colsum = nullptr;
-    c.normpart = reinterpret_cast<double*>(w);
-    c.devpart = reinterpret_cast<double*>(w + p.tile_off_devpart);
-    c.dev2 = reinterpret_cast<double*>(w + p.tile_off_dev2);
-  }
-  const hipError_t e = ceca::launch_consensus(c, vec, (hipStream_t)hip_stream);
-  if (e != hipSuccess) return hip_fail(e, "consensus kernels launch");
-  return CECA_OK;
+  int64_t need = 0;
+  const int32_t rc = run_consensus(X, n, d, ld, out, xbar_or_null, reinterpret_cast<char*>(workspace), workspace_bytes, &need,
+                                   (hipStream_t)hip_stream);
+  if (rc == CECA_EWORKSPACE)
+    return fail(CECA_EWORKSPACE, "internal: this launch shape needs %lld bytes of workspace, the bound is %lld", (long long)need,
+                (long long)bound);
+  return rc;
 }
 
 int32_t ceca_state_consensus(const float* S, int32_t n, int64_t d, int64_t ld, double* out, void* workspace,

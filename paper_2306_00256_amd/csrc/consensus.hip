@@ -39,6 +39,7 @@ __global__ __launch_bounds__(kBlock) void colsum_kernel(const ConsensusArgs C) {
 // slice 0 of colsum <- mean; optional fp32 copy; per-workgroup partial of ||xbar||^2
 __global__ __launch_bounds__(kBlock) void mean_kernel(const ConsensusArgs C) {
   __shared__ double red[kBlock / 64];
+  if (blockIdx.x == 0 && threadIdx.x == 0) *C.counter = 0u;      // the closing kernel counts its workgroups from zero
   double sq = 0.0;
   const int64_t base = (int64_t)blockIdx.x * kConsTile;
   for (int q = 0; q < (int)(kConsTile / kBlock); ++q) {
@@ -119,6 +120,7 @@ __global__ __launch_bounds__(kBlock) void cons_tile_kernel(const ConsensusArgs C
   const int cg = threadIdx.x % lanes;
   const int rg = threadIdx.x / lanes;
   const int64_t tile = blockIdx.x;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *C.counter = 0u;      // the closing kernel counts its workgroups from zero
   const int64_t g = tile * lanes + cg;
   const int64_t ngroups = (C.d + VEC - 1) / VEC;   // d is a multiple of VEC on the vector path
   const bool on = g < ngroups;
@@ -168,31 +170,142 @@ __global__ __launch_bounds__(kBlock) void cons_tile_kernel(const ConsensusArgs C
   }
 }
 
-// dev2[agent] = sum over tiles of devpart[agent][tile]
-__global__ __launch_bounds__(kBlock) void devsum_kernel(const ConsensusArgs C) {
-  __shared__ double red[kBlock / 64];
-  const int i = blockIdx.x;
-  double s = 0.0;
-  for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) s += C.devpart[(int64_t)i * C.ntiles + t];
-  s = wave_sum(s);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double t = 0.0;
-    for (int w = 0; w < kBlock / 64; ++w) t += red[w];
-    C.dev2[i] = t;
+// Single pass, one wavefront per column strip: the 64 lanes of a wavefront hold a strip of every agent
+// (lane = row lane * cgs + column group: cgs adjacent 16-byte groups of RT rows each, rows
+// rg, rg + row_lanes, ...), so x is read once and nothing is shared between wavefronts: no LDS, no barrier.
+// Column sums cross the row lanes and squared deviations cross the column groups through lane exchanges
+// (fp64, fixed order).  A wavefront takes strips w, w + nwaves, ... and adds up every row's squared
+// distance to the column means over all of them before it reduces across lanes once.
+// Writes devpart[agent][wave] (row n: the wavefront's share of ||xbar||^2) and, if asked, xbar.
+template <int VEC, int RT>
+__global__ __launch_bounds__(kBlock) void cons_wave_kernel(const ConsensusArgs C) {
+  using V = typename VecOf<VEC>::T;
+  constexpr int RTP = RT <= 1 ? 1 : RT <= 2 ? 2 : RT <= 4 ? 4 : RT <= 8 ? 8 : RT <= 16 ? 16 : 32;
+  constexpr int LOG_RTP = RTP == 1 ? 0 : RTP == 2 ? 1 : RTP == 4 ? 2 : RTP == 8 ? 3 : RTP == 16 ? 4 : 5;
+  const int lane = threadIdx.x & 63;
+  const int64_t w = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (blockIdx.x == 0 && threadIdx.x == 0) *C.counter = 0u;      // the closing kernel counts its workgroups from zero
+  if (w >= C.nwaves) return;                        // the whole wavefront leaves
+  const int cgs = C.wave_cgs;                       // column groups per strip: a power of two, 1..64
+  const int cg = lane & (cgs - 1);
+  const int rg = lane >> C.cg_shift;
+  const int row_lanes = 64 >> C.cg_shift;
+  const int64_t ngroups = (C.d + VEC - 1) / VEC;    // d is a multiple of VEC on the vector path
+  double acc[RTP];
+#pragma unroll
+  for (int k = 0; k < RTP; ++k) acc[k] = 0.0;
+  double nrm = 0.0;
+  // the loads of one strip: lanes past the last column shadow column group 0, rows past the last agent
+  // shadow it (neither is ever counted), so no branch surrounds a load
+  auto request = [&](int64_t strip, V (&x)[RT], bool& on, int64_t& col) {
+    const int64_t g = strip * cgs + cg;
+    on = g < ngroups;
+    col = (on ? g : 0) * VEC;
+#pragma unroll
+    for (int k = 0; k < RT; ++k) {
+      const int i = min(rg + k * row_lanes, C.n - 1);
+      x[k] = ld_stream<V>(C.X + (int64_t)i * C.ld + col);
+    }
+  };
+  V x[RT];
+  bool on;
+  int64_t col;
+  int64_t strip = w;
+  request(strip, x, on, col);
+  while (true) {
+    const int64_t next = strip + C.nwaves;
+    const bool more = next < C.strips;              // the same for the whole wavefront
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int k = 0; k < RT; ++k)
+      if (rg + k * row_lanes < C.n) acc4(s, x[k]);
+    // the row lanes of a column group sit cgs lanes apart: sum across them (every lane ends with the total)
+#define CECA_ROWSUM(O)                                                \
+    if (cgs <= O) {                                                   \
+      _Pragma("unroll") for (int q = 0; q < VEC; ++q) s[q] += xor_lane<O>(s[q]); \
+    }
+    CECA_ROWSUM(1) CECA_ROWSUM(2) CECA_ROWSUM(4) CECA_ROWSUM(8) CECA_ROWSUM(16) CECA_ROWSUM(32)
+#undef CECA_ROWSUM
+    double m[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) m[q] = s[q] / (double)C.n;
+#pragma unroll
+    for (int k = 0; k < RT; ++k)
+      if (on && rg + k * row_lanes < C.n) acc[k] += sqdev(x[k], m);
+    if (rg == 0 && on) {
+#pragma unroll
+      for (int q = 0; q < VEC; ++q) nrm += m[q] * m[q];
+      if (C.xbar) {
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) C.xbar[col + q] = (float)m[q];
+      }
+    }
+    if (!more) break;
+    request(next, x, on, col);
+    strip = next;
   }
+  // Sum over the column groups (lane bits below cg_shift).  Level t halves the rows a lane still carries
+  // while there is more than one: afterwards the lane holds complete sums of rows off, off + 1, ...
+  if (cgs > 1) { halve_d<1, RTP / 2>(acc, (lane & 1) != 0); nrm += xor_lane<1>(nrm); }
+  if (cgs > 2) { halve_d<2, RTP / 4>(acc, (lane & 2) != 0); nrm += xor_lane<2>(nrm); }
+  if (cgs > 4) { halve_d<4, RTP / 8>(acc, (lane & 4) != 0); nrm += xor_lane<4>(nrm); }
+  if (cgs > 8) { halve_d<8, RTP / 16>(acc, (lane & 8) != 0); nrm += xor_lane<8>(nrm); }
+  if (cgs > 16) { halve_d<16, RTP / 32>(acc, (lane & 16) != 0); nrm += xor_lane<16>(nrm); }
+  if (cgs > 32) { halve_d<32, RTP / 64>(acc, (lane & 32) != 0); nrm += xor_lane<32>(nrm); }
+  const int halvings = C.cg_shift < LOG_RTP ? C.cg_shift : LOG_RTP;     // levels that dropped half of the rows
+  int off = 0;
+#pragma unroll
+  for (int t = 0; t < LOG_RTP; ++t)
+    if (t < halvings) off += ((lane >> t) & 1) * (RTP >> (t + 1));
+  const int live = RTP >> halvings;
+  // with more column groups than rows the later levels leave copies: the lane whose remaining bits are 0 writes
+  const bool writer = (cg >> halvings) == 0;
+#pragma unroll
+  for (int j = 0; j < RTP; ++j) {
+    const int k = j + off;
+    const int i = rg + k * row_lanes;
+    if (writer && j < live && k < RT && i < C.n) C.devpart[(int64_t)i * C.nwaves + w] = acc[j];
+  }
+  if (lane == 0) C.devpart[(int64_t)C.n * C.nwaves + w] = nrm;
 }
 
-__global__ __launch_bounds__(kBlock) void finish_kernel(const ConsensusArgs C) {
+// Closing kernel, a workgroup per row (or few rows) of devpart: dev2[row] = sum over tiles (or wavefronts)
+// of devpart[row][.]; the workgroup that finishes last (a counter that an earlier kernel of the same call set
+// to zero tells it) then reduces dev2 and the partials of ||xbar||^2 to the five results.  Every sum runs in
+// a fixed order, so which workgroup happens to be last does not change a bit of the result.  The grid is
+// capped (kCloseBlocks): each workgroup's device-wide fence has a cost that must not grow with n.
+constexpr int kCloseBlocks = 32;
+__global__ __launch_bounds__(kBlock) void close_kernel(const ConsensusArgs C) {
+  __shared__ double red[kBlock / 64];
+  __shared__ bool last;
+  for (int i = blockIdx.x; i < C.close_rows; i += gridDim.x) {
+    double s = 0.0;
+    for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) s += C.devpart[(int64_t)i * C.ntiles + t];
+    s = wave_sum(s);
+    __syncthreads();                                 // red[] of the previous row has been consumed
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+      C.dev2[i] = t;
+    }
+  }
+  if (threadIdx.x == 0) {
+    __threadfence();                                 // my dev2 entries are visible device-wide before the count goes up
+    last = atomicAdd(C.counter, 1u) == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (!last) return;
+  __threadfence();                                   // every other workgroup's dev2 entry is visible from here on
   __shared__ double r0[kBlock / 64], r1[kBlock / 64], r2[kBlock / 64], r3[kBlock / 64];
   double frob = 0.0, resid = 0.0, mx = 0.0, nrm = 0.0;
-  for (int i = threadIdx.x; i < C.n; i += kBlock) {
-    const double d2 = C.dev2[i];
+  for (int a = threadIdx.x; a < C.n; a += kBlock) {
+    const double d2 = C.dev2[a];
     const double dv = sqrt(d2);
     frob += d2; resid += dv; mx = fmax(mx, dv);
   }
-  for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) nrm += C.normpart[t];
+  for (int64_t t = threadIdx.x; t < C.norm_count; t += kBlock) nrm += C.normpart[t];
   frob = wave_sum(frob); resid = wave_sum(resid); mx = wave_max(mx); nrm = wave_sum(nrm);
   if ((threadIdx.x & 63) == 0) {
     const int w = threadIdx.x >> 6;
@@ -216,7 +329,7 @@ hipError_t launch_phi(double* out, hipStream_t st) {
   return hipGetLastError();
 }
 
-static hipError_t launch_cons_tile(const ConsensusArgs& c, bool vec4, hipStream_t st) {
+static hipError_t launch_cons_tile(ConsensusArgs c, bool vec4, hipStream_t st) {
   const int lanes = kBlock / c.row_lanes;
   const size_t lds = sizeof(double) * (size_t)((c.n + 1) * lanes > kBlock * (vec4 ? 4 : 1) ? (c.n + 1) * lanes : kBlock * (vec4 ? 4 : 1));
   if (c.ntiles < 1 || c.ntiles >= (1LL << 24) || lds > 65536 || c.rows_per_thread < 1 || c.rows_per_thread > 32)
@@ -237,12 +350,54 @@ static hipError_t launch_cons_tile(const ConsensusArgs& c, bool vec4, hipStream_
   else CECA_CONS1(32);
 #undef CECA_CONS4
 #undef CECA_CONS1
-  devsum_kernel<<<dim3((unsigned)c.n), block, 0, st>>>(c);
-  finish_kernel<<<dim3(1), block, 0, st>>>(c);
+  c.close_rows = c.n;
+  close_kernel<<<dim3((unsigned)(c.n < kCloseBlocks ? c.n : kCloseBlocks)), block, 0, st>>>(c);
   return hipGetLastError();
 }
 
-hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st) {
+static hipError_t launch_cons_wave(const ConsensusArgs& c0, bool vec4, hipStream_t st) {
+  ConsensusArgs c = c0;
+  const int cgs = c.wave_cgs;
+  if (cgs < 1 || cgs > 64 || (cgs & (cgs - 1)) != 0 || (1 << c.cg_shift) != cgs) return hipErrorInvalidValue;
+  const int row_lanes = 64 / cgs;
+  if (c.rows_per_thread < 1 || c.rows_per_thread > 32 || (int64_t)c.rows_per_thread * row_lanes < c.n)
+    return hipErrorInvalidValue;
+  if (c.nwaves < 1 || c.nwaves > c.strips || c.nwaves >= (1LL << 30)) return hipErrorInvalidConfiguration;
+  // few wavefronts: one per workgroup, so that they spread over the compute units
+  const int block = c.nwaves <= 2048 ? 64 : kBlock;
+  const int64_t per = block / 64;
+  dim3 grid((unsigned)((c.nwaves + per - 1) / per));
+  c.ntiles = c.nwaves;            // row length of devpart for the reduction kernels
+  c.normpart = c.dev2 + c.n;      // devsum's row n is ||xbar||^2
+  c.norm_count = 1;
+#define CECA_CW4(RT) case RT: cons_wave_kernel<4, RT><<<grid, dim3(block), 0, st>>>(c); break
+#define CECA_CW1(RT) case RT: cons_wave_kernel<1, RT><<<grid, dim3(block), 0, st>>>(c); break
+  if (vec4) {
+    switch (c.rows_per_thread) {
+      CECA_CW4(1); CECA_CW4(2); CECA_CW4(3); CECA_CW4(4); CECA_CW4(5); CECA_CW4(6); CECA_CW4(7); CECA_CW4(8);
+      CECA_CW4(9); CECA_CW4(10); CECA_CW4(11); CECA_CW4(12); CECA_CW4(13); CECA_CW4(14); CECA_CW4(15); CECA_CW4(16);
+      CECA_CW4(17); CECA_CW4(18); CECA_CW4(19); CECA_CW4(20); CECA_CW4(21); CECA_CW4(22); CECA_CW4(23); CECA_CW4(24);
+      CECA_CW4(25); CECA_CW4(26); CECA_CW4(27); CECA_CW4(28); CECA_CW4(29); CECA_CW4(30); CECA_CW4(31); CECA_CW4(32);
+    }
+  } else {
+    switch (c.rows_per_thread) {
+      CECA_CW1(1); CECA_CW1(2); CECA_CW1(3); CECA_CW1(4); CECA_CW1(5); CECA_CW1(6); CECA_CW1(7); CECA_CW1(8);
+      CECA_CW1(9); CECA_CW1(10); CECA_CW1(11); CECA_CW1(12); CECA_CW1(13); CECA_CW1(14); CECA_CW1(15); CECA_CW1(16);
+      CECA_CW1(17); CECA_CW1(18); CECA_CW1(19); CECA_CW1(20); CECA_CW1(21); CECA_CW1(22); CECA_CW1(23); CECA_CW1(24);
+      CECA_CW1(25); CECA_CW1(26); CECA_CW1(27); CECA_CW1(28); CECA_CW1(29); CECA_CW1(30); CECA_CW1(31); CECA_CW1(32);
+    }
+  }
+#undef CECA_CW4
+#undef CECA_CW1
+  c.close_rows = c.n + 1;
+  close_kernel<<<dim3((unsigned)(c.n + 1 < kCloseBlocks ? c.n + 1 : kCloseBlocks)), dim3(kBlock), 0, st>>>(c);
+  return hipGetLastError();
+}
+
+hipError_t launch_consensus(const ConsensusArgs& c0, bool vec4, hipStream_t st) {
+  if (c0.wave_cgs > 0) return launch_cons_wave(c0, vec4, st);
+  ConsensusArgs c = c0;
+  c.norm_count = c.ntiles;        // one partial of ||xbar||^2 per column tile
   if (c.rows_per_thread > 0) return launch_cons_tile(c, vec4, st);
   const int vec = vec4 ? 4 : 1;
   const int64_t groups = (c.d + vec - 1) / vec;
@@ -262,8 +417,8 @@ hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st) {
     if (vec4) dev_kernel<4><<<grid, block, 0, st>>>(c);
     else dev_kernel<1><<<grid, block, 0, st>>>(c);
   }
-  devsum_kernel<<<dim3((unsigned)c.n), block, 0, st>>>(c);
-  finish_kernel<<<dim3(1), block, 0, st>>>(c);
+  c.close_rows = c.n;
+  close_kernel<<<dim3((unsigned)(c.n < kCloseBlocks ? c.n : kCloseBlocks)), block, 0, st>>>(c);
   return hipGetLastError();
 }
 

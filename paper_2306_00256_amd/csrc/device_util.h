@@ -87,6 +87,42 @@ __device__ __forceinline__ float wave_sum_many(const float (&in)[N], int lane, i
   return xor_add<32>(xor_add<16>(m[0]));
 }
 
+// The 32-bit word of lane ^ XOR (XOR a power of two below 64): quad permutes for 1 and 2, swizzles inside
+// each half of the wavefront for 4, 8 and 16, a lane exchange for 32.
+template <int XOR>
+__device__ __forceinline__ int xor_lane(int bits) {
+  if constexpr (XOR == 1) return __builtin_amdgcn_update_dpp(0, bits, 0xB1, 0xf, 0xf, false);        // quad_perm [1, 0, 3, 2]
+  else if constexpr (XOR == 2) return __builtin_amdgcn_update_dpp(0, bits, 0x4E, 0xf, 0xf, false);   // quad_perm [2, 3, 0, 1]
+  else if constexpr (XOR == 32) return __shfl_xor(bits, 32, 64);
+  else return __builtin_amdgcn_ds_swizzle(bits, (XOR << 10) | 0x1f);                                  // xor mask, all lanes kept
+}
+// The double that lane ^ XOR holds.
+template <int XOR>
+__device__ __forceinline__ double xor_lane(double v) {
+  const int lo = xor_lane<XOR>(__double2loint(v));
+  const int hi = xor_lane<XOR>(__double2hiint(v));
+  return __hiloint2double(hi, lo);
+}
+// One level of a halving butterfly over doubles: a lane and its partner (lane ^ XOR) both carry 2H
+// values; the lane keeps H of them (the upper half if `up`, which is the lane's own XOR bit) and adds the
+// partner's copies of those.  With one value left (H = 0) both partners keep the pair sum.  The sum a
+// lane forms is its own value plus the partner's, and the partner adds the same two numbers, so partners
+// agree bit for bit.
+template <int XOR, int H, int N>
+__device__ __forceinline__ void halve_d(double (&v)[N], bool up) {
+  if constexpr (H >= 1) {
+    static_assert(2 * H <= N, "halving more values than the lane carries");
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+      const double give = up ? v[k] : v[k + H];         // the half this lane drops is the half its partner keeps
+      const double keep = up ? v[k + H] : v[k];
+      v[k] = keep + xor_lane<XOR>(give);
+    }
+  } else {
+    v[0] = v[0] + xor_lane<XOR>(v[0]);
+  }
+}
+
 __device__ __forceinline__ float dot_v(vf4 a, vf4 b) { return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w; }
 __device__ __forceinline__ float dot_v(float a, float b) { return a * b; }
 

@@ -350,9 +350,6 @@ void grad_chunked_kernel(const GemvArgs P) {
   }
 }
 
-std::atomic<int> g_agents_per_wg{0};   // measurement knob: agents per workgroup of the looping one-pass kernel (0 = default);
-                           // 1000 = never take the chunked kernel
-
 // The chunked kernel for rows of d4 16-byte groups.  Workgroup size and column groups per thread are a
 // function of d4 alone and equal those of the one-pass variant for the same d4, so either kernel (and
 // the fused form) produces the same bits.
@@ -413,10 +410,10 @@ bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err) {
 // Picks the one-pass variant whose register tile covers (B, d); false if none does.
 bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   const int64_t d4 = g.d / 4;
-  const int apw = g_agents_per_wg.load();
+  const int apw = g_tuning.agents_per_wg;
   // many agents, long rows: the chunked kernel (any B up to 64, d up to 16384), two workgroups per
   // compute unit; a handful of agents cannot fill the device that way and stays with the kernels below
-  if (chunked_by_default(g.n, d4) && apw != 1000) {
+  if (chunked_by_default(g.n, d4) && !g_tuning.never_chunked) {
     *err = launch_chunked<false>(g, st);
     return true;
   }
@@ -424,7 +421,7 @@ bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   // 256-thread workgroups leave room for several per unit
 #define CECA_ONEPASS(T, BM, GG)                                          \
   if (g.B <= BM && d4 <= (int64_t)T * GG) {                              \
-    const int per_wg = (apw > 0 && apw < 1000) ? apw : (T == 1024 ? (g.n + 255) / 256 : 1); \
+    const int per_wg = apw > 0 ? apw : (T == 1024 ? (g.n + 255) / 256 : 1); \
     dim3 grid((unsigned)((g.n + per_wg - 1) / per_wg));                  \
     grad_onepass_kernel<T, BM, GG><<<grid, dim3(T), 0, st>>>(g);         \
     *err = hipGetLastError();                                            \

@@ -3,7 +3,6 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <cstdint>
 
 namespace ceca {
@@ -119,6 +118,14 @@ struct ConsensusArgs {
   // single-pass form (every agent's column tile in one workgroup's registers); 0 rows = two-pass form
   int32_t rows_per_thread; // 1..32 rows of x per thread
   int32_t row_lanes;       // power of two, row_lanes * rows_per_thread >= n
+  // wavefront-per-strip form of the single pass (wave_cgs > 0): devpart is [n + 1][nwaves], dev2 has n + 1 entries
+  int32_t wave_cgs;        // column groups per strip: a power of two, 64 / wave_cgs row lanes share a group
+  int32_t cg_shift;        // log2(wave_cgs)
+  int64_t strips;          // column strips in all
+  int64_t nwaves;          // wavefronts launched; wavefront w takes strips w, w + nwaves, ...
+  int64_t norm_count;      // entries of normpart (set by the launcher)
+  int32_t close_rows;      // rows of devpart the closing kernel reduces (set by the launcher)
+  uint32_t* counter;       // workgroups of the closing kernel that are done (zeroed by the call's first big kernel)
 };
 
 // Fused iterations with the quadratic-centre loss: the rounds of MultiArgs plus what the gradient needs.
@@ -175,6 +182,26 @@ struct GraphArgs {
   int32_t xcd_tiles;        // set by the launcher
 };
 
+// Launch-shape overrides of the calling thread, set through the test and measurement interface
+// (ceca_test.h).  Zero everywhere = the library's own choices, which is all the product ABI ever sees on a
+// thread that never touched that interface.
+struct Tuning {
+  int32_t segment;              // agents a two-port chain walks before it starts a new one
+  int32_t rows;                 // rows in flight (streaming kernels) / most rows per thread (register-tile kernels)
+  int32_t band;                 // column tiles per band of the launch order
+  int32_t wg_per_cu;            // cap on workgroups resident per compute unit
+  int32_t tile_threads;         // threads per workgroup of the register-tile kernels: 256, 512, 1024
+  int32_t agents_per_wg;        // agents one workgroup of the looping one-pass gradient kernel takes in turn
+  int32_t two_pass_gradient;    // 1: minibatch gradients always take the margins / half-step kernels
+  int32_t never_chunked;        // 1: single steps never take the chunked gradient kernel
+  int32_t cons_form;            // consensus observables: 1 two-pass, 2 workgroup tiles, 3 wavefront strips
+  int32_t cons_strips;          // strips one wavefront of the consensus kernel takes in turn
+  int32_t plain_tile_order;     // 1: register-tile kernels never use the XCD-contiguous tile order
+  int32_t graph_tables_in_memory;  // 1: graph gossip reads its tables from memory at every look-up
+  int32_t probe_waves;          // probe kernels: that many long-lived wavefronts instead of one thread per column group
+};
+extern thread_local Tuning g_tuning;
+
 // rows: state rows whose loads a thread keeps in flight together (1, 2, 4 or 8)
 hipError_t launch_chain(const ChainArgs& a, int mode, bool vec4, int rows, hipStream_t st);
 // one-pass gradient (vector layouts only): returns false when no register tile covers (B, d)
@@ -184,10 +211,8 @@ bool launch_grad_fused(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t*
 bool grad_fused_covers(int32_t n, int64_t d, int32_t B, bool vec4);
 // single-step gradient for layouts that are not 16-byte aligned (rows up to 1024 columns); false otherwise
 bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err);
-extern std::atomic<int> g_agents_per_wg;  // measurement knob for the one-pass kernel (0 = default)
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st);
-extern std::atomic<int> g_mix_xcd;   // measurement knob: 0 = plain tile order in the mixing kernel
 hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st);
 hipError_t launch_graph_rounds(const GraphArgs& m, bool vec4, hipStream_t st);
 hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
@@ -195,9 +220,10 @@ hipError_t launch_margins(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_margins_fused(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_halfstep(const GemvArgs& g, bool vec4, hipStream_t st);
 hipError_t launch_consensus(const ConsensusArgs& c, bool vec4, hipStream_t st);
-// measurement aid: o1, o2 <- elementwise functions of a, b, c (ngroups groups of 4 floats, 16-byte aligned)
+// measurement aid: o1, o2 <- elementwise functions of a, b, c (ngroups groups of 4 floats, 16-byte aligned);
+// reads 1..3 of a, b, c and writes 0..2 of o1, o2 are touched
 hipError_t launch_stream_probe(const float* a, const float* b, const float* c, float* o1, float* o2, int64_t ngroups,
-                               hipStream_t st);
+                               int reads, int writes, hipStream_t st);
 // out[10] = out[0] + out[5] (11 doubles on the device)
 hipError_t launch_phi(double* out, hipStream_t st);
 

@@ -107,7 +107,6 @@ void mix_rounds_kernel(const MixArgs M) {
   }
 }
 
-std::atomic<int> g_mix_xcd{1};
 
 template <int VEC, int RT, int THREADS>
 static hipError_t launch_mix(const MixArgs& mm, unsigned blocks, size_t lds, hipStream_t st) {
@@ -163,7 +162,7 @@ hipError_t launch_mix_rounds(const MixArgs& m, bool vec4, hipStream_t st) {
   if (blocks < 1 || blocks >= (1LL << 24)) return hipErrorInvalidConfiguration;
   MixArgs mm = m;
   mm.xcd_tiles = 0;
-  if (lanes * (vec4 ? 16 : 4) < 128 && blocks >= 1024 && g_mix_xcd) {
+  if (lanes * (vec4 ? 16 : 4) < 128 && blocks >= 1024 && !g_tuning.plain_tile_order) {
     mm.xcd_tiles = (int32_t)((blocks + 7) / 8);
     blocks = (int64_t)mm.xcd_tiles * 8;            // tiles past the last one find no columns and leave
   }

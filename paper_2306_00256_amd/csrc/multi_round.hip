@@ -18,7 +18,7 @@ namespace ceca {
 // and enough tiles to matter), 0 for the plain order; rounds *blocks up to 8 runs of that many tiles
 // (workgroups past the last tile find no columns and leave).
 static int32_t xcd_run(int row_bytes, int64_t* blocks) {
-  if (row_bytes >= 128 || *blocks < 1024 || !g_mix_xcd) return 0;   // small launches measured better in plain order
+  if (row_bytes >= 128 || *blocks < 1024 || g_tuning.plain_tile_order) return 0;   // small launches measured better in plain order
   const int64_t per = (*blocks + 7) / 8;
   *blocks = per * 8;
   return (int32_t)per;

@@ -21,16 +21,38 @@ def api():
     return P
 
 
-def test_every_declared_symbol_is_exported(api):
-    hdr = open(os.path.join(ROOT, "include", "ceca.h")).read()
+def _declared(header):
+    hdr = open(os.path.join(ROOT, "include", header)).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(?:int32_t|int64_t|const char\*)\s+(\w+)\s*\(", hdr))
+    return set(re.findall(r"\b(?:int32_t|int64_t|const char\*)\s+(\w+)\s*\(", hdr))
+
+
+def test_every_declared_symbol_is_exported(api):
+    declared = _declared("ceca.h")
     assert {"ceca_tau", "ceca_schedule", "ceca_gossip_round", "dsgd_ceca_step", "consensus_error"} <= declared
     L = ctypes.CDLL(api.library_path())
     for name in declared:
         assert hasattr(L, name), name
     from paper_2306_00256_amd import binding
     assert declared == set(binding.EXPORTS)
+
+
+def test_test_interface_is_separate_and_exported(api):
+    """Launch-shape overrides and probe kernels live in their own header: the product header neither
+    declares nor includes them."""
+    product = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "ceca.h")).read(), flags=re.S)
+    assert "#include \"ceca_test.h\"" not in product and "ceca_set_option" not in product and "ceca_stream_probe" not in product
+    assert not (_declared("ceca.h") & _declared("ceca_test.h"))
+    declared = _declared("ceca_test.h")
+    from paper_2306_00256_amd import binding
+    assert declared == set(binding.TEST_EXPORTS)
+    L = ctypes.CDLL(api.library_path())
+    for name in declared:
+        assert hasattr(L, name), name
+    # options are validated on the host and belong to the calling thread
+    assert L.ceca_set_option(binding.OPT_ROWS, 99) == binding.CECA_EINVAL
+    assert L.ceca_set_option(12345, 0) == binding.CECA_EINVAL
+    assert L.ceca_set_option(binding.OPT_ROWS, 8) == 0 and L.ceca_reset_options() == 0
 
 
 def test_struct_sizes_match_header(api):

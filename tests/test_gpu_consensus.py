@@ -142,8 +142,10 @@ def test_state_consensus_entry_point(env, n, d, pad):
                                          (100, 3000, 8, 0), (130, 515, 0, 1), (1023, 4096, 0, 0), (1026, 37, 3, 0),
                                          (3, 70001, 3, 0), (4000, 12, 0, 0), (4096, 9, 0, 0), (5000, 8, 0, 0)])
 def test_single_pass_and_two_pass_forms(env, n, d, pad, off):
-    """Both forms of the consensus kernels (x read once with every agent's column tile in one workgroup;
-    column sums first, deviations second) against the fp64 oracle, on aligned, padded and unaligned layouts."""
+    """Every form of the consensus kernels -- the library's choice, the two passes (column sums first,
+    deviations second), the single pass with every agent's column tile in one workgroup, and the single
+    pass with one wavefront per column strip in several shapes (rows per lane, strips per wavefront) --
+    against the fp64 oracle, on aligned, padded and unaligned layouts."""
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
     ld = d + pad
@@ -153,27 +155,55 @@ def test_single_pass_and_two_pass_forms(env, n, d, pad, off):
     X[:, :d] = torch.from_numpy(x).cuda()
     X[:, d:] = 1e30                                         # padding must never be read
     want = OCONS.consensus_error(x)
-    ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
-    ws = ws[(-ws.data_ptr()) % 256:]
-    got = {}
-    try:
-        for mode in (1, 0):
-            P.ceca_set_option(Bn.OPT_CONS_SINGLE_PASS, mode)
+    shapes = [(1, 0, 0), (0, 0, 0), (2, 0, 0), (3, 0, 0), (3, 32, 1), (3, 5, 3), (3, 1, 2), (3, 16, 4096), (3, 7, 1)]
+    for mode, rows, strips in shapes:
+        P.ceca_set_option(Bn.OPT_CONS_SINGLE_PASS, mode)
+        P.ceca_set_option(Bn.OPT_ROWS, rows)
+        P.ceca_set_option(Bn.OPT_CONS_STRIPS, strips)
+        ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+        ws = ws[(-ws.data_ptr()) % 256:]
+        out = torch.full((5,), -1.0, dtype=torch.float64, device="cuda")
+        xbar = torch.zeros(d, dtype=torch.float32, device="cuda")
+        P.consensus_error(X, n, d, out, xbar=xbar, workspace=ws, ld=ld)
+        torch.cuda.synchronize()
+        g = out.cpu().numpy()
+        what = (mode, rows, strips)
+        scale = max(want["frob2"], 1e-300)
+        assert abs(g[0] - want["frob2"]) <= 1e-10 * scale, what
+        assert abs(g[1] - want["residue"]) <= 1e-9 * max(want["residue"], 1e-300), what
+        assert abs(g[2] - want["max_dev"]) <= 1e-9 * max(want["max_dev"], 1e-300), what
+        assert abs(g[3] - want["mean_norm"]) <= 1e-10 * want["mean_norm"], what
+        assert g[4] == n
+        assert np.abs(xbar.cpu().numpy() - want["mean"]).max() <= 1e-6 * max(np.abs(want["mean"]).max(), 1.0), what
+    P.ceca_reset_options()
+
+
+@pytest.mark.parametrize("n,d", [(31, 1 << 16), (100, 20_000), (6, 300_000), (512, 4100), (17, 77_777)])
+def test_wavefront_strip_form_is_deterministic_and_tight(env, n, d):
+    """The wavefront-strip form at rtol 1e-12 on the four scalars (as the default form is gated above), twice
+    with the same bits, for layouts with and without 16-byte alignment."""
+    torch, P = env
+    from paper_2306_00256_amd import binding as Bn
+    x = WL.initial_state(n, d, seed=n + d) * 3.0 + 1.5
+    want = OCONS.consensus_error(x)
+    for off in (0, 1):
+        buf = torch.zeros(n * d + 8, dtype=torch.float32, device="cuda")
+        X = buf[off: off + n * d].view(n, d)
+        X.copy_(torch.from_numpy(x))
+        P.ceca_set_option(Bn.OPT_CONS_SINGLE_PASS, 3)
+        ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+        ws = ws[(-ws.data_ptr()) % 256:]
+        outs = []
+        for _ in range(2):
+            ws.fill_(0xFF)                                   # stale workspace contents must not matter
             out = torch.full((5,), -1.0, dtype=torch.float64, device="cuda")
-            xbar = torch.zeros(d, dtype=torch.float32, device="cuda")
-            P.consensus_error(X, n, d, out, xbar=xbar, workspace=ws, ld=ld)
-            torch.cuda.synchronize()
-            g = out.cpu().numpy()
-            got[mode] = g
-            scale = max(want["frob2"], 1e-300)
-            assert abs(g[0] - want["frob2"]) <= 1e-10 * scale, mode
-            assert abs(g[1] - want["residue"]) <= 1e-9 * max(want["residue"], 1e-300), mode
-            assert abs(g[2] - want["max_dev"]) <= 1e-9 * max(want["max_dev"], 1e-300), mode
-            assert abs(g[3] - want["mean_norm"]) <= 1e-10 * want["mean_norm"], mode
-            assert g[4] == n
-            assert np.abs(xbar.cpu().numpy() - want["mean"]).max() <= 1e-6 * max(np.abs(want["mean"]).max(), 1.0), mode
-    finally:
-        P.ceca_set_option(Bn.OPT_CONS_SINGLE_PASS, 1)
+            P.consensus_error(X, n, d, out, workspace=ws)
+            outs.append(out.cpu().numpy())
+        assert np.array_equal(outs[0], outs[1])
+        g = outs[0]
+        assert np.isclose(g[0], want["frob2"], rtol=1e-12) and np.isclose(g[1], want["residue"], rtol=1e-12)
+        assert np.isclose(g[2], want["max_dev"], rtol=1e-12) and np.isclose(g[3], want["mean_norm"], rtol=1e-12)
+    P.ceca_reset_options()
 
 
 def test_stream_probe_values(env):
@@ -191,5 +221,17 @@ def test_stream_probe_values(env):
     a2, b2 = a.clone(), b.clone()
     P.ceca_stream_probe(a2, b2, c, a2, b2, 4096)
     assert torch.equal(a2, o1) and torch.equal(b2, o2)
+    # fewer reads stand in the first array for the missing ones; fewer writes leave the other output alone
+    p1, p2 = torch.full_like(a, 7.0), torch.full_like(a, 7.0)
+    P.ceca_stream_probe(a, b, None, p1, p2, 4096, reads=2, writes=2)
+    assert torch.allclose(p1, 0.5 * a + 0.5 * (b - 0.1 * (b - a)), rtol=1e-6, atol=1e-6)
+    p1.fill_(7.0); p2.fill_(7.0)
+    P.ceca_stream_probe(a, None, None, p1, None, 4096, reads=1, writes=1)
+    assert torch.allclose(p1, a, rtol=1e-6, atol=1e-6) and bool((p2 == 7.0).all())
+    p1.fill_(7.0)
+    P.ceca_stream_probe(a, b, c, p1, None, 4096, reads=3, writes=0)
+    assert bool((p1 == 7.0).all())
     with pytest.raises(P.CecaError):
         P.ceca_stream_probe(a, b, c, o1, o2, 4095)
+    with pytest.raises(P.CecaError):
+        P.ceca_stream_probe(a, b, c, o1, o2, 4096, reads=4)

@@ -58,12 +58,12 @@ def test_graph_rounds_match_the_oracle(env, kind, n, rows):
         P.ceca_set_option(Bn.OPT_TILE_THREADS, 0)
     assert all(torch.equal(outs[0], o) for o in outs[1:])
     try:
-        P.ceca_set_option(Bn.OPT_ONEPASS, 0)                                     # tables read from memory, not staged in LDS
+        P.ceca_set_option(Bn.OPT_GRAPH_STAGE, 0)                                 # tables read from memory, not staged in LDS
         X = torch.from_numpy(x0).cuda()
         P.ceca_graph_rounds(X, X, n, d, nbr, w, ws, rounds)
         assert torch.equal(X, outs[0])
     finally:
-        P.ceca_set_option(Bn.OPT_ONEPASS, 1)
+        P.ceca_set_option(Bn.OPT_GRAPH_STAGE, 1)
     assert max(rel_err(outs[0].cpu().numpy(), want)) <= 1e-5
     # the mean of every column is kept (W is doubly stochastic)
     assert np.abs(outs[0].cpu().numpy().astype(np.float64).mean(axis=0) - x0.astype(np.float64).mean(axis=0)).max() <= 1e-6
