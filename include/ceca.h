@@ -210,6 +210,21 @@ int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double
                         float* xbar_or_null, void* workspace, int64_t workspace_bytes,
                         void* hip_stream);
 
+/* consensus_error for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same kernels, same
+ * results.  The partial sums live in a 16 MiB array in the library's own device image (one copy per GPU, held
+ * until the process ends); the call allocates and frees nothing.  Problems whose partial sums need more than
+ * 16 MiB return CECA_EWORKSPACE with the size in ceca_last_error() -- take consensus_error with a workspace
+ * there.  Up to 512 agents every d fits (the single pass caps its partial sums at 12 MiB); with more agents
+ * the partial sums grow with n * d (n = 1023 on a 16-byte aligned layout: d up to about 60,000), and where only the two-pass form applies
+ * (more than 4095 agents) the fp64 column sums alone take 8 d bytes or more.  The array needs no clearing
+ * (every partial a kernel reads was written earlier in the same call), but all calls on one GPU share it: two calls that
+ * overlap in time on one GPU -- different streams or different threads -- race and give wrong results;
+ * calls on one stream, or on streams the caller orders, are safe.  The device whose array is used is the
+ * calling thread's current device, which must be the one X, out and the stream belong to. */
+int32_t consensus_error_noalloc(const float* X, int32_t n, int64_t d, int64_t ld, double* out,
+                                float* xbar_or_null, void* hip_stream);
+
 /* Consensus observables of both halves of a state S = [x; y] (device, 2n rows of ld floats), each half
  * about its own mean, and the squared norm of the stacked deviation phi that the consensus lemma
  * bounds (App. B.3, definition of phi):

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     ceca_topology_round,
     ceca_state_consensus,
     consensus_error,
+    consensus_error_noalloc,
     consensus_error_workspace_bytes,
     dsgd_ceca_run,
     dsgd_ceca_run_workspace_bytes,

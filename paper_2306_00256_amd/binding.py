@@ -18,7 +18,7 @@ MIX_MAX = 16
 
 EXPORTS = (
     "ceca_tau", "ceca_schedule", "ceca_gossip_round", "ceca_gossip_rounds", "ceca_average", "dsgd_ceca_workspace_bytes", "dsgd_ceca_step", "dsgd_ceca_steps", "dsgd_ceca_run_workspace_bytes", "dsgd_ceca_run",
-    "consensus_error_workspace_bytes", "consensus_error", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_graph_rounds", "ceca_last_error", "ceca_last_hip_error",
+    "consensus_error_workspace_bytes", "consensus_error", "consensus_error_noalloc", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_graph_rounds", "ceca_last_error", "ceca_last_hip_error",
 )
 # include/ceca_test.h: launch-shape overrides and probe kernels for tests and measurement, not the product ABI
 TEST_EXPORTS = ("ceca_set_option", "ceca_reset_options", "ceca_stream_probe")
@@ -94,6 +94,8 @@ def lib():
         L.consensus_error.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int64, C.c_void_p]
         L.consensus_error.restype = C.c_int32
+        L.consensus_error_noalloc.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.consensus_error_noalloc.restype = C.c_int32
         L.ceca_state_consensus.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                            C.c_int64, C.c_void_p]
         L.ceca_state_consensus.restype = C.c_int32
@@ -232,6 +234,12 @@ def consensus_error(X, n: int, d: int, out, xbar=None, workspace=None, ld: Optio
     ld = int(X.stride(0)) if ld is None else ld
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().consensus_error(_ptr(X), n, d, ld, _ptr(out), _ptr(xbar), _ptr(workspace), wbytes, _stream(stream)))
+
+
+def consensus_error_noalloc(X, n: int, d: int, out, xbar=None, ld: Optional[int] = None, stream=None) -> None:
+    """consensus_error without a workspace: the partial sums live in the library's own 16 MiB device array."""
+    ld = int(X.stride(0)) if ld is None else ld
+    _check(lib().consensus_error_noalloc(_ptr(X), n, d, ld, _ptr(out), _ptr(xbar), _stream(stream)))
 
 
 def ceca_state_consensus(S, n: int, d: int, out, workspace=None, ld: Optional[int] = None, stream=None) -> None:

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 #include <numeric>
 
 #include "ceca.h"
@@ -447,6 +448,35 @@ TileShape graph_tile(int32_t n, bool vec4) {
                      if (threads == ceca::kBlock) return n <= 192 ? 8 : ceca::kGraphRows;
                      return n <= 6 * 512 ? 6 : 8;      // 6 rows fit 128 registers; 8 keep 4096 agents at 32-byte rows
                    });
+}
+
+// ---- scratch memory of the allocation-free entry point (consensus_error_noalloc) ----
+// One array per GPU, held from the moment the library's code is loaded on that GPU until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress: the device address it yields
+// (a different one on every GPU) is what kernels and copies are given.
+constexpr int64_t kScratchBytes = 16LL << 20;
+__device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of the scratch array (looked up once per device, with that device current).
+int32_t scratch_of_current_device(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(CECA_EINVAL, "device %d: the allocation-free entry point serves devices 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u) != 0) return fail(CECA_EHIP, "the scratch array has no 256-byte aligned device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = reinterpret_cast<char*>(g_scratch_ptr[dev]);
+  return CECA_OK;
 }
 
 }  // namespace
@@ -1178,6 +1208,23 @@ int32_t consensus_error(const float* X, int32_t n, int64_t d, int64_t ld, double
   if (rc == CECA_EWORKSPACE)
     return fail(CECA_EWORKSPACE, "internal: this launch shape needs %lld bytes of workspace, the bound is %lld", (long long)need,
                 (long long)bound);
+  return rc;
+}
+
+int32_t consensus_error_noalloc(const float* X, int32_t n, int64_t d, int64_t ld, double* out, float* xbar_or_null,
+                                void* hip_stream) {
+  if (!X || !out) return fail(CECA_EINVAL, "null pointer");
+  if (n < 1 || d < 1 || ld < d) return fail(CECA_EINVAL, "need n >= 1 and 1 <= d <= ld");
+  char* w = nullptr;
+  int32_t rc = scratch_of_current_device(&w);
+  if (rc != CECA_OK) return rc;
+  // every partial sum the kernels read was written by an earlier kernel of this same call, so the array
+  // needs no clearing between calls
+  int64_t need = 0;
+  rc = run_consensus(X, n, d, ld, out, xbar_or_null, w, kScratchBytes, &need, (hipStream_t)hip_stream);
+  if (rc == CECA_EWORKSPACE)
+    return fail(CECA_EWORKSPACE, "n = %d, d = %lld needs %lld bytes of scratch memory, the allocation-free entry point holds %lld: "
+                "use consensus_error with a workspace", n, (long long)d, (long long)need, (long long)kScratchBytes);
   return rc;
 }
 
