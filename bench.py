@@ -5,7 +5,11 @@ A step is one pass of the whole hot path over one batch of synthetic input: one 
 (gradient + CECA round fused) for the training workloads, one ceca_gossip_round call for the pure
 gossip workloads.  Inputs are generated on the device before the timed region.  Prints ONE JSON line.
 
+The default run also times every other configuration briefly (`configs`) and, before the process first
+touches the GPU, the CPU oracle on one thread and on all host cores (`cpu_baseline`).
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--others] [--mix-only] [--no-cpu]
+                    [--no-configs] [--eager-only] [--copy-probe] [--write-data FILE | --data-file FILE]
 """
 from __future__ import annotations
 
@@ -17,6 +21,9 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 EAGER_ONLY = False      # --eager-only: minibatch workloads skip the HIP-graph and multi-iteration legs
+NO_GRAPH = False        # --no-graph: minibatch workloads skip only the HIP-graph leg (for hardware-counter passes)
+DATA_FILE = None        # --data-file / --write-data: minibatch inputs handed over by file
+WRITE_DATA = False
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
@@ -79,6 +86,42 @@ class Timer:
         self.event_ms = self.e0.elapsed_time(self.e1)
 
 
+def per_step_events(torch, step, ks):
+    """Milliseconds of each step in `ks`, from HIP events recorded between the launches (a pass of its own,
+    after the timed region: the events must not sit inside the figure that `value` is computed from)."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(ks) + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for j, k in enumerate(ks):
+        step(k)
+        ev[j + 1].record()
+    torch.cuda.synchronize()
+    return [ev[j].elapsed_time(ev[j + 1]) for j in range(len(ks))]
+
+
+def frac_distribution(ms_list, ks, tau, kind, units):
+    """min / median / max over the steps of (algorithmic bytes of that step's round) / time / peak."""
+    rd, rd0, wr = ALG_BYTES[kind]
+    fr = sorted(units * ((rd0 if k % tau == 0 else rd) + wr) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS for ms, k in zip(ms_list, ks))
+    r0 = [units * (rd0 + wr) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS for ms, k in zip(ms_list, ks) if k % tau == 0]
+    out = {"min": fr[0], "median": fr[len(fr) // 2], "max": fr[-1], "steps": len(fr)}
+    if r0:
+        out["round0_median"] = sorted(r0)[len(r0) // 2]
+    return out
+
+
+def probe(torch, P, arrays, cnt, reads, writes, reps=10):
+    """Milliseconds and GB/s of the elementwise probe kernel with this mix of streaming reads and writes."""
+    a, b, c, o1, o2 = arrays
+    for _ in range(3):
+        P.ceca_stream_probe(a, b, c, o1, o2, cnt, reads=reads, writes=writes)
+    with Timer(torch) as tp:
+        for _ in range(reps):
+            P.ceca_stream_probe(a, b, c, o1, o2, cnt, reads=reads, writes=writes)
+    ms = tp.event_ms / reps
+    return ms, 4.0 * (reads + writes) * cnt / (ms * 1e-3) / 1e9
+
+
 def consensus_report(torch, P, X, n, d, ld):
     """Consensus observables of the x rows, measured by the library (outside any timed region)."""
     ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
@@ -112,17 +155,24 @@ def run_quad(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
-    # what the device gives the simplest kernel with this traffic mix (3 streaming reads + 2 streaming writes
-    # per element, same array sizes): out of place, and in place for the one-port workload
+    # the same steps once more with an event after each, for the spread of the per-step fraction of peak
+    ks = list(range(warmup + steps, warmup + 2 * steps))
+    tm.frac = frac_distribution(per_step_events(torch, step, ks), ks, tau, "quad_center", n * d)
+    # what the device gives the simplest kernel with each round's traffic mix (same array sizes, no indexing):
+    # 3 streaming reads + 2 streaming writes per element for a full round, 2 + 2 for round 0 (y is not read);
+    # out of place, and in place (what the one-port rounds do)
     pa, pb = S[:n].reshape(-1), S[n:].reshape(-1)
     po1, po2 = (pa, pb) if port == 1 else (T[:n].reshape(-1), T[n:].reshape(-1))
     cnt = n * ld
-    for _ in range(3):
-        P.ceca_stream_probe(pa, pb, c.reshape(-1), po1, po2, cnt)
-    with Timer(torch) as tp:
-        for _ in range(10):
-            P.ceca_stream_probe(pa, pb, c.reshape(-1), po1, po2, cnt)
-    tm.probe = {"stream_probe_ms": tp.event_ms / 10, "stream_probe_GBs": 20.0 * cnt / (tp.event_ms / 10 * 1e-3) / 1e9}
+    arrays = (pa, pb, c.reshape(-1), po1, po2)
+    ms32, gb32 = probe(torch, P, arrays, cnt, 3, 2)
+    # round 0 reads x and c: the probe's two reads are its first two arrays
+    ms22, gb22 = probe(torch, P, (pa, c.reshape(-1), None, po1, po2), cnt, 2, 2)
+    tm.probe = {"stream_probe_ms": ms32, "stream_probe_GBs": gb32,
+                "stream_probe_round0_ms": ms22, "stream_probe_round0_GBs": gb22}
+    if port == 2:
+        msip, gbip = probe(torch, P, (pa, pb, c.reshape(-1), pa, pb), cnt, 3, 2)
+        tm.probe.update({"stream_probe_in_place_ms": msip, "stream_probe_in_place_GBs": gbip})
     # the same step with gradients the caller supplies (any loss, e.g. from autograd): same traffic, no noise
     # arithmetic; c stands in for the gradient rows
     gl = Bn.make_gradient_loss(c)
@@ -166,6 +216,15 @@ def run_gossip(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tm:
         for k in range(warmup, warmup + steps):
             step(k)
+    ks = list(range(warmup + steps, warmup + 2 * steps))
+    tm.frac = frac_distribution(per_step_events(torch, step, ks), ks, tau, "gossip", n * d)
+    # the simplest kernel with a round's traffic mix: x, y read and written (x only read in round 0)
+    pa, pb = S[:n].reshape(-1), S[n:].reshape(-1)
+    po1, po2 = (pa, pb) if port == 1 else (T[:n].reshape(-1), T[n:].reshape(-1))
+    ms22, gb22 = probe(torch, P, (pa, pb, None, po1, po2), n * ld, 2, 2)
+    ms12, gb12 = probe(torch, P, (pa, None, None, po1, po2), n * ld, 1, 2)
+    tm.probe = {"stream_probe_ms": ms22, "stream_probe_GBs": gb22, "stream_probe_round0_ms": ms12,
+                "stream_probe_round0_GBs": gb12}
     # consensus error after each of the tau rounds from a fresh X(0) (not timed)
     WL.device_normal((n, ld), seed=sp.seed, out=S[:n])
     S[n:] = S[:n]
@@ -190,7 +249,17 @@ def run_gossip(torch, P, Bn, sp, steps, warmup):
 
 def run_minibatch(torch, P, Bn, sp, steps, warmup):
     n, d, port, N, B = sp.n, sp.d, sp.port, sp.N, sp.B
-    if sp.name.startswith("logistic1023"):
+    if DATA_FILE and not WRITE_DATA:
+        # inputs drawn by an earlier process (python bench.py --workload NAME --write-data FILE): this process
+        # then issues no generator kernels before the library's own
+        Ah = np.load(DATA_FILE + ".A.npy", mmap_mode="r")
+        th = np.load(DATA_FILE + ".t.npy")
+        assert Ah.shape == (n, N, d) and th.shape == (n, N), "data file does not match the workload"
+        A = torch.empty((n, N, d), dtype=torch.float32, device="cuda")
+        for i0 in range(0, n, 64):                       # in slices: the host copy is memory-mapped
+            A[i0:i0 + 64].copy_(torch.from_numpy(np.ascontiguousarray(Ah[i0:i0 + 64])))
+        t = torch.from_numpy(th).cuda()
+    elif sp.name.startswith("logistic1023"):
         A, t, _ = WL.device_logistic_sparse(n, N, d, sp.seed)
     else:
         if sp.loss == "lsq":
@@ -198,6 +267,11 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
         else:
             Ah, th, _ = WL.logistic_data_hetero(n, N, d, sp.seed)
         A, t = torch.from_numpy(Ah).cuda(), torch.from_numpy(th).cuda()
+    if WRITE_DATA:
+        np.save(DATA_FILE + ".A.npy", A.cpu().numpy())
+        np.save(DATA_FILE + ".t.npy", t.cpu().numpy())
+        print(f"bench.py: wrote {DATA_FILE}.A.npy and .t.npy", file=sys.stderr)
+        sys.exit(0)
     if sp.B == sp.N:
         idx_h = WL.full_batch_indices(n, N)
     else:
@@ -237,23 +311,24 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
         return tm, launches, minibatch_bytes(B)
     # launch-bound loops: the same iterations captured once as a HIP graph and replayed
     window = 2 * tau * max(1, 16 // tau)          # even number of steps: two-port buffers end where they began
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        for k in range(window):
-            step(k)
-    torch.cuda.current_stream().wait_stream(side)
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        for k in range(window):
-            step(k)
-    reps = max(1, steps // window)
-    graph.replay()
-    with Timer(torch) as tg:
-        for _ in range(reps):
-            graph.replay()
-    tm.graph_ms_per_step = tg.event_ms / (reps * window)
+    if not NO_GRAPH:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for k in range(window):
+                step(k)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for k in range(window):
+                step(k)
+        reps = max(1, steps // window)
+        graph.replay()
+        with Timer(torch) as tg:
+            for _ in range(reps):
+                graph.replay()
+        tm.graph_ms_per_step = tg.event_ms / (reps * window)
     # the same iterations through dsgd_ceca_run (one call for a window of iterations; with many agents one
     # kernel per iteration): needs one step size and a batch table that covers the window
     # (a decaying step size is constant over windows of lr_decay_every iterations: one call per window)
@@ -344,6 +419,8 @@ def measure(torch, P, Bn, name, steps, warmup):
     extra.update(getattr(tm, "probe", {}))
     if hasattr(tm, "final"):
         extra["consensus_after_timed_steps"] = tm.final
+    if hasattr(tm, "frac"):
+        extra["frac_per_step"] = tm.frac
     return {
         **extra,
         "workload": name, "n": sp.n, "d": sp.d, "port": sp.port, "loss": sp.loss, "steps": steps,
@@ -355,62 +432,94 @@ def measure(torch, P, Bn, name, steps, warmup):
     }
 
 
-def measured_traffic(name, steps, warmup):
-    """Mean HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if any."""
+def _shape_key(sh):
+    return ",".join(str(sh[k]) for k in ("rows", "band", "wg_per_cu", "stretch"))
+
+
+def measured_traffic(P, name, steps, warmup):
+    """(mean HBM bytes per launch, note) from the committed rocprofv3 counter summary of this workload.
+    The summary records the launch shape it was measured with (`shape_round0`, `shape_round`: rows in flight,
+    band, workgroups per CU, stretch); a file without them, or with a shape other than the one the library
+    now picks, is refused: its bytes may no longer describe the kernels timed here."""
     path = os.path.join(ROOT, "profiles", f"{name}_traffic.txt")
     if not os.path.exists(path):
-        return None
+        return None, "no counter summary committed for this workload"
     kv = {}
     with open(path) as f:
         for ln in f:
             if ln.strip() and not ln.startswith("#"):
                 k, v = ln.split()
-                kv[k] = float(v)
+                kv[k] = v
     sp = WL.SPECS[name]
     tau = _tau(sp.n)
-    r0 = kv["round0_fetch_kib"] * kv["fetch_scale"] + kv["round0_write_kib"] * kv["write_scale"]
-    rr = kv["round_fetch_kib"] * kv["fetch_scale"] + kv["round_write_kib"] * kv["write_scale"]
+    ld = _ld(sp.d)
+    kind = 1 if sp.loss == "quad_center" else (0 if sp.loss == "none" else 2)
+    in_place = sp.port == 1
+    now0 = _shape_key(P.ceca_describe_step_launch(sp.n, sp.d, ld, 0, sp.port, kind, in_place))
+    now1 = _shape_key(P.ceca_describe_step_launch(sp.n, sp.d, ld, 1 % tau, sp.port, kind, in_place))
+    if kv.get("shape_round0") != now0 or kv.get("shape_round") != now1:
+        return None, (f"stale: the summary was measured with launch shapes {kv.get('shape_round0')} / {kv.get('shape_round')}, "
+                      f"the library now picks {now0} / {now1}")
+    fs, wsc = float(kv["fetch_scale"]), float(kv["write_scale"])
+    if "step_fetch_kib" in kv:
+        # minibatch workloads: the counters summed over the launches of one step, reported per launch
+        return (1024.0 * (float(kv["step_fetch_kib"]) * fs + float(kv["step_write_kib"]) * wsc) / float(kv["launches_per_step"]),
+                "FETCH_SIZE / WRITE_SIZE summary, same launch shapes")
+    r0 = float(kv["round0_fetch_kib"]) * fs + float(kv["round0_write_kib"]) * wsc
+    rr = float(kv["round_fetch_kib"]) * fs + float(kv["round_write_kib"]) * wsc
     rounds = [k % tau for k in range(warmup, warmup + steps)]
-    return 1024.0 * sum(r0 if r == 0 else rr for r in rounds) / len(rounds)
+    return 1024.0 * sum(r0 if r == 0 else rr for r in rounds) / len(rounds), "FETCH_SIZE / WRITE_SIZE summary, same launch shapes"
 
 
-def cpu_baseline(sp, target_s=12.0):
-    """The fp64 oracle, as it stands, on this host's cores, on a bounded sample of the same workload."""
+# ---------------------------------------------------------------------------------------------
+# CPU baseline: the fp64 numpy oracle as it stands, on a bounded sample of the workload, on one thread and on
+# all host cores.  Runs before this process touches the GPU; the workers are fresh interpreters (spawn).
+# ---------------------------------------------------------------------------------------------
+def _cpu_sample(name, block, target_s, barrier=None):
+    """One worker's share: the oracle on block number `block` of the sample, for about target_s seconds.
+    Returns (agent-parameter updates done, seconds, iterations, description of the block)."""
     from oracle import ceca as OC
     from oracle import losses as OL
 
+    sp = WL.SPECS[name]
     n, port = sp.n, sp.port
     if sp.loss in ("quad_center", "none"):
-        # columns are independent instances of the recursion: sample the first 2^18 of them, all agents
+        # columns are independent instances of the recursion: a block is 2^18 of them, all agents
         width = min(sp.d, 1 << 18)
-        cols = np.arange(width, dtype=np.int64)
+        c0 = (block * width) % max(sp.d - width + 1, 1)
+        cols = np.arange(c0, c0 + width, dtype=np.int64)
         if sp.loss == "quad_center":
-            grad = OL.make_quad_center_grad(WL.quad_centers(n, width, sp.seed), sp.noise_std, sp.seed, columns=cols)
+            grad = OL.make_quad_center_grad(WL.quad_centers(n, width, sp.seed + 1000 * block), sp.noise_std, sp.seed, columns=cols)
             x = y = np.zeros((n, width))
         else:
             grad = None
-            x = y = WL.initial_state(n, width, sp.seed).astype(np.float64)
-        what = f"the first {width} of {sp.d} columns, all {n} agents"
-        max_iters = sp.iters or 10 ** 9
+            x = y = WL.initial_state(n, width, sp.seed + 1000 * block).astype(np.float64)
+        what = f"{width} of {sp.d} columns, all {n} agents"
     else:
-        # minibatch losses couple the columns: keep d and B, cut the agent count and the sample pool
+        # minibatch losses couple the columns: keep d and B, cut the agent count and the sample pool; a block
+        # is an independent replica drawn with its own seed
         n = min(n, 127)
         N = min(sp.N, 64)
-        if sp.name.startswith("logistic1023"):
-            A, t, _ = WL.logistic_data_sparse(n, N, sp.d, sp.seed)
+        seed = sp.seed + 1000 * block
+        if name.startswith("logistic1023"):
+            A, t, _ = WL.logistic_data_sparse(n, N, sp.d, seed)
         elif sp.loss == "lsq":
-            A, t, _ = WL.lsq_data(n, N, sp.d, sp.seed)
+            A, t, _ = WL.lsq_data(n, N, sp.d, seed)
         else:
-            A, t, _ = WL.logistic_data_hetero(n, N, sp.d, sp.seed)
-        max_iters = min(sp.iters, 2000)
+            A, t, _ = WL.logistic_data_hetero(n, N, sp.d, seed)
         B = min(sp.B, N)
-        idx = WL.full_batch_indices(n, N) if sp.B == sp.N else WL.batch_indices(n, N, B, max_iters, sp.seed)
+        idx = WL.full_batch_indices(n, N) if sp.B == sp.N else WL.batch_indices(n, N, B, 256, seed)
         grad = OL.make_minibatch_grad(sp.loss, A, t, idx, grad_scale=sp.grad_scale, noise_std=sp.noise_std,
                                       seed=sp.seed)
         x = y = np.zeros((n, sp.d))
         width = sp.d
         what = f"{n} of {sp.n} agents, {N} of {sp.N} samples each, all {sp.d} columns"
     tau = _tau(n)
+    if barrier is not None:
+        try:
+            barrier.wait(timeout=60.0)      # all workers start their timed loops together
+        except Exception:
+            pass                            # a worker that never arrived must not stop the others
     t0 = time.perf_counter()
     iters = 0
     while True:
@@ -420,12 +529,96 @@ def cpu_baseline(sp, target_s=12.0):
             x, y = OC.dsgd_ceca_step(x, y, iters, port, WL.step_size(sp, iters), grad, store32=True)
         iters += 1
         el = time.perf_counter() - t0
-        if el > target_s or iters >= max_iters:
+        if el > target_s:
             break
-    # numpy elementwise code runs on one thread; the small per-agent matrix products of the minibatch
-    # losses are below the size at which the BLAS library would start more
-    return {"value": n * width * iters / el, "unit": "agent-param updates/s", "cores": 1, "kind": "oracle",
-            "sample": f"{iters} iterations of {sp.name} on {what}; fp64 numpy oracle, {el:.1f} s"}
+    return float(n) * width * iters, el, iters, what
+
+
+def _cpu_worker(name, block, target_s, barrier, queue):
+    try:                                    # one thread per worker, also inside the BLAS library
+        import threadpoolctl
+        threadpoolctl.threadpool_limits(1)
+    except Exception:
+        pass
+    try:
+        queue.put((block,) + _cpu_sample(name, block, target_s, barrier))
+    except Exception as e:                  # the parent counts the workers that report
+        queue.put((block, None, repr(e)))
+
+
+def cpu_baseline(sp, target_s=10.0):
+    """The oracle timed twice on bounded samples of the workload: one thread (the oracle is plain numpy: its
+    elementwise code and its small per-agent matrix products run on one thread), then one worker process
+    per host core available to this run, each on its own block of the sample, started together.  The
+    workers are fresh interpreters (spawn) started before this process touches the GPU; every wait on them
+    has a deadline, and a worker that fails only lowers the count of cores reported."""
+    import multiprocessing as mp
+    import queue as queue_mod
+
+    units1, el1, it1, what = _cpu_sample(sp.name, 0, target_s)
+    single = {"value": units1 / el1, "cores": 1, "sample": f"{it1} iterations of {sp.name} on {what}; {el1:.1f} s"}
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    # a one-GPU box gives a run 16 cores' worth whatever the machine has
+    workers = max(1, min(avail, 16))
+    ctx = mp.get_context("spawn")
+    barrier = ctx.Barrier(workers)
+    q = ctx.Queue()
+    procs = [ctx.Process(target=_cpu_worker, args=(sp.name, j, target_s, barrier, q), daemon=True) for j in range(workers)]
+    for pr in procs:
+        pr.start()
+    res = []
+    deadline = time.perf_counter() + target_s + 120.0
+    while len(res) < workers and time.perf_counter() < deadline:
+        try:
+            r = q.get(timeout=1.0)
+        except queue_mod.Empty:
+            if not any(pr.is_alive() for pr in procs):
+                break
+            continue
+        res.append(r)
+    for pr in procs:
+        pr.join(timeout=5.0)
+        if pr.is_alive():
+            pr.terminate()
+    good = [r for r in res if r[1] is not None]
+    base = {"unit": "agent-param updates/s", "kind": "oracle", "single_thread": single,
+            "host_cpu_count": os.cpu_count(), "host_cpus_available": avail}
+    if not good:
+        return {**base, "value": single["value"], "cores": 1,
+                "sample": single["sample"] + "; the all-core leg did not finish: " + "; ".join(str(r[2]) for r in res if r[1] is None)}
+    units = sum(r[1] for r in good)
+    el = max(r[2] for r in good)
+    its = [r[3] for r in good]
+    return {**base, "value": units / el, "cores": len(good),
+            "sample": f"{len(good)} worker processes, each {min(its)}-{max(its)} iterations of {sp.name} on its own block of "
+                      f"{good[0][4]}; fp64 numpy oracle, {el:.1f} s; in all {units / (sp.n * sp.d):.2f} full-width iterations' worth"}
+
+
+def config_entry(res, sp):
+    """One compact line of the `configs` block from a measure() result."""
+    hbm = sp.loss in ("quad_center", "none") or sp.name.startswith("logistic1023")
+    e = {"workload": sp.name, "n": sp.n, "d": sp.d, "port": sp.port, "loss": sp.loss, "steps": res["steps"],
+         "ms_per_step": res["ms_per_step"], "us_per_iteration": res["ms_per_step"] * 1e3,
+         "kernels_per_step": res["kernels_per_step"], "agent_param_updates_per_s": res["agent_param_updates_per_s"]}
+    if hbm:
+        e.update({"bound": "hbm", "bytes_per_agent_param": res["bytes_per_agent_param"],
+                  "algorithmic_bytes_per_step": res["bytes_per_agent_param"] * sp.n * sp.d,
+                  "achieved_GBs": res["achieved_GBs"], "frac": res["achieved_GBs"] / HBM_PEAK_GBS})
+    else:
+        e["bound"] = "launch latency (no bandwidth fraction is claimed)"
+    for k in ("graph_replay_ms_per_step", "run_call_ms_per_step", "run_iterations_per_call", "fused_rounds", "fused_ms",
+              "fused_GBs_on_12B", "frac_per_step", "consensus_after_timed_steps"):
+        if k in res:
+            e[k] = res[k]
+    if "run_call_ms_per_step" in res:
+        # the same iterations through dsgd_ceca_run (one call per window): the fastest way this library runs them
+        e["run_call_agent_param_updates_per_s"] = sp.n * sp.d / (res["run_call_ms_per_step"] * 1e-3)
+        if hbm:
+            e["run_call_frac"] = res["bytes_per_agent_param"] * sp.n * sp.d / (res["run_call_ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+    return e
 
 
 def main():
@@ -434,22 +627,37 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="quad31_2p", choices=sorted(WL.SPECS))
-    ap.add_argument("--others", action="store_true", help="also time the remaining workloads (reported under 'others')")
+    ap.add_argument("--others", action="store_true", help="also time the remaining workloads in full (reported under 'others')")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the short timings of the other configurations (the `configs` block of the default run)")
     ap.add_argument("--mix-only", action="store_true",
                     help="time only the comparison-topology gossip rounds (n = 130 and n = 1026) and exit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--eager-only", action="store_true",
                     help="minibatch workloads: time the eager steps only (no HIP-graph replay, no multi-iteration calls); "
                          "for hardware-counter passes")
+    ap.add_argument("--no-graph", action="store_true", help="minibatch workloads: skip only the HIP-graph replay leg")
     ap.add_argument("--copy-probe", action="store_true",
                     help="first run one plain 1 GiB device copy (calibrates rocprofv3 byte counters)")
+    ap.add_argument("--write-data", metavar="FILE", help="minibatch workloads: draw the inputs, save them as FILE.A.npy / FILE.t.npy and exit")
+    ap.add_argument("--data-file", metavar="FILE", help="minibatch workloads: load the inputs an earlier --write-data run saved")
     args = ap.parse_args()
-    global EAGER_ONLY
+    global EAGER_ONLY, NO_GRAPH, DATA_FILE, WRITE_DATA
     EAGER_ONLY = args.eager_only
+    NO_GRAPH = args.no_graph
+    DATA_FILE = args.write_data or args.data_file
+    WRITE_DATA = bool(args.write_data)
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (all agents are simulated on one device); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    sp = WL.SPECS[args.workload]
+    profiling = args.eager_only or args.no_graph or args.copy_probe or WRITE_DATA or bool(args.data_file)
+
+    # the CPU leg comes first: its worker processes are started from a process that holds no GPU state
+    cpu = None
+    if not (args.no_cpu or args.mix_only or profiling):
+        cpu = cpu_baseline(sp)
 
     import torch
 
@@ -476,7 +684,7 @@ def main():
         torch.cuda.empty_cache()
 
     main_res = measure(torch, P, Bn, args.workload, args.steps, args.warmup)
-    sp = WL.SPECS[args.workload]
+    traffic, traffic_note = measured_traffic(P, args.workload, args.steps, args.warmup)
     out = {
         "metric": "agent-param updates/s per DSGD-CECA round",
         "value": main_res["agent_param_updates_per_s"],
@@ -492,15 +700,23 @@ def main():
             "achieved": main_res["achieved_GBs"],
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": main_res["achieved_GBs"] / HBM_PEAK_GBS,
-            "traffic": measured_traffic(args.workload, args.steps, args.warmup),
+            "traffic": traffic,
+            "traffic_source": traffic_note,
             "algorithmic_bytes_per_launch": main_res["bytes_per_agent_param"] * sp.n * sp.d
             / main_res["kernels_per_step"],
             "bytes_per_agent_param": main_res["bytes_per_agent_param"],
             "kernel_ms": main_res["event_ms_per_step"] / main_res["kernels_per_step"],
             "gather_model_GBs": main_res["gather_model_GBs"],
-            # the simplest elementwise kernel with the same reads and writes per element, timed in this run
+            # spread of the per-step fraction of peak (each step against its own round's bytes), from a second
+            # pass over the same steps with an event after every launch
+            "frac_per_step": main_res.get("frac_per_step"),
+            # the simplest elementwise kernel with the same reads and writes per element, timed in this run:
+            # a full round's mix, round 0's mix, and the full round's mix in place
             "stream_probe_GBs": main_res.get("stream_probe_GBs"),
             "stream_probe_ms": main_res.get("stream_probe_ms"),
+            "stream_probe_round0_GBs": main_res.get("stream_probe_round0_GBs"),
+            "stream_probe_round0_ms": main_res.get("stream_probe_round0_ms"),
+            "stream_probe_in_place_GBs": main_res.get("stream_probe_in_place_GBs"),
         },
     }
     details = {k: main_res[k] for k in ("graph_replay_ms_per_step", "run_call_ms_per_step", "run_iterations_per_call",
@@ -514,13 +730,26 @@ def main():
         out["fused_iterations"] = {k: main_res[k] for k in ("fused_iterations_per_call", "fused_ms_per_iteration",
                                                              "fused_agent_param_updates_per_s")}
         out["fused_iterations"]["speedup_over_value"] = main_res["fused_agent_param_updates_per_s"] / out["value"]
-    if args.workload == "quad31_2p" and not args.others:
+    comp = None
+    if args.workload == "quad31_2p" and not args.others and not profiling:
         # the configuration names one-port CECA, which needs an even number of agents: the same workload at
         # n = 30 with one port (in place, closed pairs) beside the two-port run at the stated n = 31
         comp = measure(torch, P, Bn, "quad30_1p", args.steps, args.warmup)
         out["companion_1p"] = {"workload": "quad30_1p", "n_agents": 30, "port": 1, "ms_per_step": comp["ms_per_step"],
                                "value": comp["agent_param_updates_per_s"], "achieved_GBs": comp["achieved_GBs"],
-                               "frac": comp["achieved_GBs"] / HBM_PEAK_GBS}
+                               "frac": comp["achieved_GBs"] / HBM_PEAK_GBS, "frac_per_step": comp.get("frac_per_step")}
+    if args.workload == "quad31_2p" and not (args.others or args.no_configs or profiling):
+        # every configuration in the one line the default run prints: the five stated ones (the two that ask
+        # for one port at an odd n appear at both readings) and the paper's own least-squares experiment
+        cfgs = [config_entry(main_res, sp)]
+        if comp is not None:
+            cfgs.append(config_entry(comp, WL.SPECS["quad30_1p"]))
+        for name in ("gossip100_1p", "gossip100_2p", "logistic1023_2p", "logistic6_2p", "lsq5_2p", "lsq6_1p",
+                     "paperlsq258_1p", "paperlsq258_2p"):
+            sp_o = WL.SPECS[name]
+            k = 70 if sp_o.loss == "none" else 200
+            cfgs.append(config_entry(measure(torch, P, Bn, name, k, 5), sp_o))
+        out["configs"] = cfgs
     if args.others:
         out["others"] = []
         for name in sorted(WL.SPECS):
@@ -531,8 +760,8 @@ def main():
             out["others"].append(measure(torch, P, Bn, name, k, 5))
         out["others"].append(run_mix(torch, P, Bn, 130, 1 << 20, 20, 3))
         out["others"].append(run_mix(torch, P, Bn, 1026, 1 << 17, 20, 3))
-    if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(sp)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out), flush=True)
 
 

@@ -59,6 +59,17 @@ int32_t ceca_set_option(int32_t option, int32_t value);
 /* Every option of the calling thread back to the library default. */
 int32_t ceca_reset_options(void);
 
+/* Launch shape the library picks (under the calling thread's overrides) for the state-updating kernel of one
+ * ceca_gossip_round (kind = 0), of one dsgd_ceca_step with the quadratic-centre loss (kind = 1) or of one
+ * dsgd_ceca_step with a minibatch loss (kind = 2: the combine from stored messages) on a 16-byte aligned
+ * state of 2n rows of ld floats, out of place (in_place = 0) or in place: out[0] = state rows a thread keeps
+ * in flight, out[1] = column tiles per band of the launch order (0 = one band), out[2] = cap on workgroups
+ * per compute unit (0 = none), out[3] = agents per chain stretch, out[4] = stretches per cycle, out[5] =
+ * floats per column group (4 or 1).  Nothing is launched.  A benchmark uses it to tell whether a stored
+ * hardware-counter profile still describes the kernels it is about to time.  out: host, 6 int32. */
+int32_t ceca_describe_step_launch(int32_t n, int64_t d, int64_t ld, int32_t r, int32_t port, int32_t kind,
+                                  int32_t in_place, int32_t* out);
+
 /* An elementwise kernel with `reads` streaming reads (1..3: a, then b, then c) and `writes` streaming
  * writes (1..2: o1, then o2) per element, so that a benchmark can report, from the same run, the bandwidth
  * the device gives the simplest kernel with a step's traffic mix: 3 reads + 2 writes for a full round of

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     Mix,
     Round,
     ceca_average,
+    ceca_describe_step_launch,
     ceca_gossip_round,
     ceca_gossip_rounds,
     ceca_graph_rounds,

@@ -21,7 +21,7 @@ EXPORTS = (
     "consensus_error_workspace_bytes", "consensus_error", "consensus_error_noalloc", "ceca_state_consensus", "ceca_topology_round", "ceca_mix_rounds", "ceca_graph_rounds", "ceca_last_error", "ceca_last_hip_error",
 )
 # include/ceca_test.h: launch-shape overrides and probe kernels for tests and measurement, not the product ABI
-TEST_EXPORTS = ("ceca_set_option", "ceca_reset_options", "ceca_stream_probe")
+TEST_EXPORTS = ("ceca_set_option", "ceca_reset_options", "ceca_stream_probe", "ceca_describe_step_launch")
 
 
 class CecaError(RuntimeError):
@@ -109,6 +109,9 @@ def lib():
         L.ceca_graph_rounds.restype = C.c_int32
         L.ceca_stream_probe.argtypes = [C.c_void_p] * 5 + [C.c_int64, C.c_int32, C.c_int32, C.c_void_p]
         L.ceca_stream_probe.restype = C.c_int32
+        L.ceca_describe_step_launch.argtypes = [C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                                C.POINTER(C.c_int32)]
+        L.ceca_describe_step_launch.restype = C.c_int32
         L.ceca_reset_options.argtypes = []
         L.ceca_reset_options.restype = C.c_int32
         L.ceca_last_error.restype = C.c_char_p
@@ -253,6 +256,14 @@ def ceca_stream_probe(a, b, c, o1, o2, count: int, reads: int = 3, writes: int =
     """Measurement aid (ceca_test.h): elementwise kernel with `reads` streaming reads (of a, b, c) and `writes`
     streaming writes (of o1, o2) per element."""
     _check(lib().ceca_stream_probe(_ptr(a), _ptr(b), _ptr(c), _ptr(o1), _ptr(o2), count, reads, writes, _stream(stream)))
+
+
+def ceca_describe_step_launch(n: int, d: int, ld: int, r: int, port: int, kind: int, in_place: bool) -> dict:
+    """Launch shape the library picks for the state-updating kernel of a gossip round (kind 0), a fused
+    quadratic-centre step (1) or a minibatch step's combine (2) (ceca_test.h)."""
+    out = (C.c_int32 * 6)()
+    _check(lib().ceca_describe_step_launch(n, d, ld, r, port, int(kind), int(in_place), out))
+    return dict(zip(("rows", "band", "wg_per_cu", "stretch", "stretches_per_cycle", "vec"), list(out)))
 
 
 def ceca_set_option(option: int, value: int) -> None:

@@ -99,41 +99,56 @@ void shape_chain(const ceca_round_t& rd, int32_t n, int32_t port, bool in_place,
   a->segs_per_cycle = (len + seg_len - 1) / seg_len;
 }
 
-int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ceca_round_t& rd, int32_t port,
-                  hipStream_t st) {
+// Launch shape of a chain kernel for this call: rows in flight, band, workgroups per compute unit (written
+// into `a`) and the default stretch length.
+struct ChainPlan { int rows; int32_t default_seg; bool in_place; };
+
+ChainPlan plan_chain(ceca::ChainArgs* a, int mode, int64_t d, int32_t port) {
+  ChainPlan p;
   int rows = g_tuning.rows;
-  a.band = (uint32_t)g_tuning.band;
-  a.wg_per_cu = g_tuning.wg_per_cu;
+  a->band = (uint32_t)g_tuning.band;
+  a->wg_per_cu = g_tuning.wg_per_cu;
   // combining from stored messages reads no other agent's state rows, so it can overwrite the state
   // row by row with any stretch length; the other modes may only run whole cycles in place
-  const bool in_place = a.xin == a.xout && mode != ceca::MODE_FROMV;
-  const bool pairs = port == 1 || a.n == 1;
+  const bool in_place = a->xin == a->xout && mode != ceca::MODE_FROMV;
+  const bool pairs = port == 1 || a->n == 1;
   // rows in flight per thread: closed pairs and in-place cycles of the fused step like the fattest
   // variant (it also runs fewer workgroups per CU); one-row stretches want more, lighter workgroups
   // round 0 of the fused step (y not read: half the traffic is writes) measured best with the lightest
   // variant, two-row stretches, wider bands and at most 4 workgroups per CU
   const bool fused_step = mode == ceca::MODE_QUAD || mode == ceca::MODE_GRAD;     // x, y and one more array stream in
-  const bool quad_round0 = fused_step && !a.read_y && !(pairs || in_place);
+  const bool quad_round0 = fused_step && !a->read_y && !(pairs || in_place);
   // a state that stays in the last-level cache (minibatch losses on many small agents) is not a
   // streaming problem: measured on MI355X at n = 1023, d = 4096, 16-row stretches with two rows in
   // flight beat one-row stretches (fewer, longer workgroups; 18.5 -> 14 us for the combine)
   // (only when one-row stretches would make thousands of workgroups: a handful of agents or columns
   // needs every workgroup it can get)
   const bool cached = mode == ceca::MODE_FROMV && !(pairs || in_place) &&
-                      2 * (int64_t)a.n * a.ld * (int64_t)sizeof(float) <= (64LL << 20) &&
-                      (int64_t)a.n * ((d + 4 * ceca::kBlock - 1) / (4 * ceca::kBlock)) >= 2048;
-  const int32_t default_seg = quad_round0 ? 2 : (cached ? 16 : 1);
+                      2 * (int64_t)a->n * a->ld * (int64_t)sizeof(float) <= (64LL << 20) &&
+                      (int64_t)a->n * ((d + 4 * ceca::kBlock - 1) / (4 * ceca::kBlock)) >= 2048;
+  p.default_seg = quad_round0 ? 2 : (cached ? 16 : 1);
   if (rows == 0) rows = quad_round0 ? 1 : cached ? 2 : (fused_step && (pairs || in_place)) ? 8 : 4;
-  if (cached && a.band == 0) a.band = 2;
+  if (cached && a->band == 0) a->band = 2;
   if (quad_round0) {
-    if (a.band == 0) a.band = 512;
-    if (a.wg_per_cu == 0) a.wg_per_cu = 4;
+    if (a->band == 0) a->band = 512;
+    if (a->wg_per_cu == 0) a->wg_per_cu = 4;
   }
   // band: about 7-10 MB of traffic between a row's own read and its re-read as a message, so that the
   // re-read hits L2 (32 MB over 8 XCDs; a tile and its successor land on the same XCD when the band
   // is a multiple of 8)
   // closed stretches re-read nothing: they sweep whole rows, one pair or cycle after the other
-  if (a.band == 0 && !(pairs || in_place)) a.band = fused_step ? 256 : 512;
+  if (a->band == 0 && !(pairs || in_place)) a->band = fused_step ? 256 : 512;
+  p.rows = rows;
+  p.in_place = in_place;
+  return p;
+}
+
+int32_t run_chain(ceca::ChainArgs a, int mode, int64_t d, bool can_vec, const ceca_round_t& rd, int32_t port,
+                  hipStream_t st) {
+  const ChainPlan pl = plan_chain(&a, mode, d, port);
+  const int rows = pl.rows;
+  const bool in_place = pl.in_place;
+  const int32_t default_seg = pl.default_seg;
   const int64_t d4 = can_vec ? d / 4 : 0;
   if (d4 > 0) {
     a.col0 = 0;
@@ -1114,6 +1129,36 @@ int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d,
     const hipError_t e = ceca::launch_graph_rounds(g, false, st);
     if (e != hipSuccess) return hip_fail(e, "graph gossip kernel launch (scalar columns)");
   }
+  return CECA_OK;
+}
+
+int32_t ceca_describe_step_launch(int32_t n, int64_t d, int64_t ld, int32_t r, int32_t port, int32_t kind,
+                                  int32_t in_place, int32_t* out) {
+  if (!out) return fail(CECA_EINVAL, "null pointer");
+  if (kind < 0 || kind > 2) return fail(CECA_EINVAL, "kind must be 0 (gossip round), 1 (fused quadratic-centre step) or 2 (combine of a minibatch step)");
+  // stand-in addresses (never dereferenced): only their equality and alignment enter the launch shape
+  const float* S_in = reinterpret_cast<const float*>(uintptr_t(1) << 20);
+  float* S_out = in_place ? const_cast<float*>(S_in) : reinterpret_cast<float*>(uintptr_t(1) << 50);
+  ceca_round_t rd;
+  const int32_t rc = check_state_call(S_in, S_out, n, d, ld, r, port, &rd);
+  if (rc != CECA_OK) return rc;
+  ceca::ChainArgs a{};
+  a.xin = S_in;  a.yin = S_in + (int64_t)n * ld;
+  a.xout = S_out; a.yout = S_out + (int64_t)n * ld;
+  a.ld = ld;
+  a.n = n;
+  set_weights(rd, n, /*gossip_only=*/kind == 0, &a);
+  const int mode = kind == 1 ? ceca::MODE_QUAD : (kind == 2 ? ceca::MODE_FROMV : ceca::MODE_GOSSIP);
+  const ChainPlan pl = plan_chain(&a, mode, d, port);
+  const bool vec = ld % 4 == 0;
+  const int64_t groups = vec ? d / 4 : d;
+  shape_chain(rd, n, port, pl.in_place, pl.default_seg, std::max<int64_t>(groups, 1), &a);
+  out[0] = pl.rows;
+  out[1] = (int32_t)a.band;
+  out[2] = a.wg_per_cu;
+  out[3] = a.seg_len;
+  out[4] = a.segs_per_cycle;
+  out[5] = vec ? 4 : 1;
   return CECA_OK;
 }
 

@@ -26,11 +26,28 @@ def test_row_pitch_is_256_byte_aligned():
         assert ld >= d and ld % 64 == 0 and ld - d < 64
 
 
-def test_traffic_summary_parses():
-    t = bench.measured_traffic("quad31_2p", 50, 5)
+def test_traffic_summary_parses_and_goes_stale_with_the_launch_shape():
+    import paper_2306_00256_amd as P
+    from paper_2306_00256_amd import binding as Bn
+    t, note = bench.measured_traffic(P, "quad31_2p", 50, 5)
     alg = 19.2 * WL.SPECS["quad31_2p"].n * WL.SPECS["quad31_2p"].d
     assert alg < t < 1.1 * alg          # measured HBM bytes sit a few per cent above the algorithmic count
-    assert bench.measured_traffic("lsq5_2p", 50, 5) is None
+    assert bench.measured_traffic(P, "lsq5_2p", 50, 5)[0] is None
+    for name in ("quad30_1p", "gossip100_1p", "gossip100_2p", "logistic1023_2p"):
+        assert bench.measured_traffic(P, name, 50, 5)[0] is not None, name
+    # a launch shape other than the one the counters were read with: the stored bytes are refused
+    P.ceca_set_option(Bn.OPT_BAND, 64)
+    try:
+        t, note = bench.measured_traffic(P, "quad31_2p", 50, 5)
+        assert t is None and note.startswith("stale")
+    finally:
+        P.ceca_reset_options()
+    assert bench.measured_traffic(P, "quad31_2p", 50, 5)[0] is not None
+
+
+def test_cpu_sample_runs_the_oracle_on_a_block():
+    units, el, iters, what = bench._cpu_sample("lsq5_2p", 1, 0.05)
+    assert iters >= 1 and units == 5 * 1000 * iters and el > 0 and "agents" in what
 
 
 def test_more_than_one_gpu_is_refused():

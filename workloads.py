@@ -180,6 +180,7 @@ def device_logistic_sparse(n: int, N: int, d: int, seed: int, device: str = "cud
     gen = torch.Generator(device=device)
     gen.manual_seed(int(seed))
     w_star = torch.empty(d, dtype=torch.float32, device=device).normal_(generator=gen)
+    w64 = w_star.double()
     A = torch.empty((n, N, d), dtype=torch.float32, device=device)
     lab = torch.empty((n, N), dtype=torch.float32, device=device)
     for i in range(n):
@@ -187,7 +188,8 @@ def device_logistic_sparse(n: int, N: int, d: int, seed: int, device: str = "cud
         Ai.normal_(generator=gen)
         mask = torch.empty((N, d), dtype=torch.float32, device=device).uniform_(generator=gen) < density
         Ai.mul_(mask)
-        s = Ai.double() @ w_star.double()
+        # elementwise product and row sums in fp64: no matrix-product library is pulled in just to draw labels
+        s = (Ai.double() * w64).sum(dim=1)
         y = torch.where(s >= 0, 1.0, -1.0).float()
         fl = torch.empty(N, dtype=torch.float32, device=device).uniform_(generator=gen) < flip
         lab[i] = torch.where(fl, -y, y)
