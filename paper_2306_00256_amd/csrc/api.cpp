@@ -395,26 +395,37 @@ TileShape pick_tile(int32_t n, bool vec4, int32_t cap_lo, int32_t cap_hi_256, in
 // Fused gossip rounds (x and y of every row in registers); with_y = false: exact averaging, which
 // stores no y.
 TileShape rounds_tile(int32_t n, bool vec4, bool with_y = true) {
-  // Measured on MI355X (n = 16 ... 4096): 512-thread workgroups with up to 9 rows per thread (128
-  // registers: two workgroups per compute unit) make the rows of the tile two to four times wider than
-  // 256-thread ones and run 1.25x (n = 130, 258) to 3x (n = 1026) faster; beyond 9 x 128 agents only a
-  // 1024-thread workgroup keeps the rows at 64 bytes (4.6x at n = 2050).  Up to 256 agents, when 9 rows
-  // per thread need as many row lanes as 8 do, the 256-thread tile has the same rows per thread at
-  // half the width (still >= 128 bytes) and measured 0-10 % ahead (n = 16 ... 200).
-  // 256-thread tiles: 8 rows leave room for twice as many workgroups per CU as 16 (1.5x faster at
-  // n = 100) as long as a row of the tile stays at least 128 bytes wide; many agents need the full 16
-  // Exact averaging writes a third of the bytes: up to 128 agents 5 rows per thread (rows of the tile
-  // still >= 128 bytes, twice the resident workgroups) measured 5-10 % ahead (n = 31, 64, 100).
-  if (!with_y && n <= 128)
+  // Measured on MI355X (n = 16 ... 4096).  Up to 256 agents: 256-thread workgroups with up to 9 rows per
+  // thread (rows of the tile at least 128 bytes wide).  Exact averaging writes a third of the bytes: up to 80
+  // agents 5 rows per thread (rows still >= 128 bytes, twice the resident workgroups) measured 5-10 % ahead
+  // (n = 31, 64), beyond that the fuller tile does (n = 100: 186 against 205 us).
+  // More agents: 512-thread workgroups with up to 9 rows per thread (128 registers: two workgroups per
+  // compute unit) make the rows of the tile two to four times wider than 256-thread ones and run 1.25x
+  // (n = 258) to 3x (n = 1026) faster; beyond 9 x 128 agents only a 1024-thread workgroup keeps the rows at
+  // 64 bytes (4.6x at n = 2050).
+  if (n <= 256) {
+    const int32_t cap = (!with_y && n <= 80) ? 5 : 9;
     return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows, [](int32_t) { return ceca::kBlock; },
-                     [](int32_t threads) { return threads == ceca::kBlock ? 5 : 9; });
+                     [cap](int32_t threads) { return threads == ceca::kBlock ? cap : 9; });
+  }
   return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows,
-                   [](int32_t m) {
-                     if (m > 9 * 128) return 1024;
-                     const bool same_lanes = shape_tile(m, true, 512, 9).row_lanes == shape_tile(m, true, ceca::kBlock, 8).row_lanes;
-                     return (m <= 256 && same_lanes) ? ceca::kBlock : 512;
-                   },
-                   [n](int32_t threads) { return threads == ceca::kBlock ? (n <= 256 ? 8 : ceca::kMultiRows) : 9; });
+                   [](int32_t m) { return m > 9 * 128 ? 1024 : 512; },
+                   [](int32_t threads) { return threads == ceca::kBlock ? ceca::kMultiRows : 9; });
+}
+
+// Register-lean form of the fused-rounds kernel for a 256-thread tile with this many rows per thread (the
+// wavefronts per SIMD it is compiled for; 0 = the plain form).  Measured on MI355X: with 5 to 7 rows the
+// lean form keeps five workgroups per compute unit instead of three, so that some load or store while
+// others exchange (n = 100: exact averaging 225 -> 186 us, n = 200: 258 -> 216 us); 9 rows fit four
+// (n = 130: 386 us with 512-thread tiles -> 327 us); with 8 rows the plain form measured ahead (n = 31, 64),
+// and 5 wavefronts would spill there.
+int32_t rounds_lean(const TileShape& t, bool vec4) {
+  const int32_t forced = g_tuning.lean_tiles;
+  if (!vec4 || t.threads != ceca::kBlock || forced == 1) return 0;
+  if (forced >= 4) return forced;
+  if (t.rows_per_thread >= 5 && t.rows_per_thread <= 7) return 5;
+  if (t.rows_per_thread == 9) return 4;
+  return 0;
 }
 
 // Fused iterations (x, y and c of every row in registers).
@@ -545,6 +556,10 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
     case CECA_OPT_CHUNKED_GRADIENT:
       t.never_chunked = value == 0;
       return CECA_OK;
+    case CECA_OPT_LEAN_TILES:
+      if (value != 0 && value != 1 && (value < 4 || value > 6)) return fail(CECA_EINVAL, "lean tiles must be 0, 1, 4, 5 or 6");
+      t.lean_tiles = value;
+      return CECA_OK;
     case CECA_OPT_PROBE_WAVES:
       if (value < 0 || value > (1 << 20)) return fail(CECA_EINVAL, "probe wavefronts must be 0..2^20");
       t.probe_waves = value;
@@ -637,6 +652,7 @@ int32_t ceca_gossip_rounds(const float* S_in, float* S_out, int32_t n, int64_t d
     m.xout = S_out;  m.yout = S_out + (int64_t)n * ld;
     m.ld = ld;
     m.n = n;  m.port = port;  m.rounds = cnt;
+    m.lean = rounds_lean(tv, true);
     for (int32_t t = 0; t < cnt; ++t) {
       ceca::fill_round(n, (t0 + t) % tau, port, &rd);
       ceca::MultiRound& R = m.round[t];
@@ -677,6 +693,7 @@ int32_t ceca_average(const float* X_in, float* X_out, int32_t n, int64_t d, int6
   m.xout = X_out;  m.yout = nullptr;
   m.ld = ld;
   m.n = n;  m.port = port;  m.rounds = tau;          // n = 1: no rounds, the kernel copies
+  m.lean = rounds_lean(tv, true);
   ceca_round_t rd;
   for (int32_t t = 0; t < tau; ++t) {
     ceca::fill_round(n, t, port, &rd);

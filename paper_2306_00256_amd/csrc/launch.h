@@ -66,6 +66,8 @@ struct MultiArgs {
   int32_t row_lanes;   // power of two, row_lanes * rows_per_thread >= n: threads of a workgroup that share a column group
   int32_t threads;     // threads per workgroup of the gossip-rounds kernel: 0 = 256, or 512 / 1024 (16-byte groups only);
                        // 512 / 1024 keep at most 9 rows per thread in registers without spilling
+  int32_t lean;        // gossip-rounds kernel, 256 threads, 16-byte groups: 4, 5 or 6 = register-lean form compiled
+                       // for that many wavefronts per SIMD (0 = the plain form)
   MultiRound round[kMultiMaxRounds];
 };
 
@@ -198,6 +200,7 @@ struct Tuning {
   int32_t cons_strips;          // strips one wavefront of the consensus kernel takes in turn
   int32_t plain_tile_order;     // 1: register-tile kernels never use the XCD-contiguous tile order
   int32_t graph_tables_in_memory;  // 1: graph gossip reads its tables from memory at every look-up
+  int32_t lean_tiles;           // gossip-rounds kernel with 256 threads: 4, 5, 6 = the register-lean form for that many wavefronts per SIMD
   int32_t probe_waves;          // probe kernels: that many long-lived wavefronts instead of one thread per column group
 };
 extern thread_local Tuning g_tuning;

@@ -29,9 +29,14 @@ static int32_t xcd_run(int row_bytes, int64_t* blocks) {
 // 512-thread ones per compute unit); 256-thread workgroups take what their rows need.
 template <int THREADS>
 constexpr int multi_round_waves() { return THREADS > 256 ? 4 : 1; }
+// The gossip-rounds kernel with 256 threads also comes in a register-lean form (LEAN > 0: that many
+// wavefronts per SIMD, peers read from LDS two rows at a time): more workgroups are resident, so that some
+// load or store while others exchange.
+template <int THREADS, int LEAN>
+constexpr int rounds_waves() { return LEAN > 0 ? LEAN : multi_round_waves<THREADS>(); }
 
-template <int VEC, int RT, int THREADS>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(multi_round_waves<THREADS>())))
+template <int VEC, int RT, int THREADS, int LEAN>
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(rounds_waves<THREADS, LEAN>())))
 void multi_round_kernel(const MultiArgs M) {
   using V = typename VecOf<VEC>::T;
   extern __shared__ float lds_z[];                 // [n][lanes] groups of VEC floats
@@ -69,7 +74,7 @@ void multi_round_kernel(const MultiArgs M) {
   const bool alternate = M.row_lanes == 1;
   const bool rg_odd = (rg & 1) != 0;
   // rows whose messages are read from LDS together: all of them, or a few at a time where registers are short
-  constexpr int KB = (THREADS > 256 && RT > 4) ? (RT > 7 ? 2 : 4) : RT;
+  constexpr int KB = ((THREADS > 256 || LEAN > 0) && RT > 4) ? (RT > 7 || LEAN > 0 ? 2 : 4) : RT;
   for (int t = 0; t < M.rounds; ++t) {
     const MultiRound R = M.round[t];
     // the round's flags are the same for every thread: branches, not per-element selects
@@ -336,22 +341,22 @@ hipError_t launch_multi_step(const StepsArgs& s, bool vec4, hipStream_t st) {
   return launch_steps_wide<1024>(ss, (unsigned)blocks, lds, st);
 }
 
-template <int VEC, int RT, int THREADS>
+template <int VEC, int RT, int THREADS, int LEAN>
 static hipError_t launch_rounds(const MultiArgs& mm, unsigned blocks, size_t lds, hipStream_t st) {
   if (lds > 64 * 1024) {
     // more than 64 KB of LDS per workgroup has to be asked for
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&multi_round_kernel<VEC, RT, THREADS>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&multi_round_kernel<VEC, RT, THREADS, LEAN>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  multi_round_kernel<VEC, RT, THREADS><<<dim3(blocks), dim3(THREADS), lds, st>>>(mm);
+  multi_round_kernel<VEC, RT, THREADS, LEAN><<<dim3(blocks), dim3(THREADS), lds, st>>>(mm);
   return hipGetLastError();
 }
 
-template <int VEC, int THREADS>
+template <int VEC, int THREADS, int LEAN = 0>
 static hipError_t launch_rounds_rt(const MultiArgs& mm, unsigned blocks, size_t lds, hipStream_t st) {
   switch (mm.rows_per_thread) {
-#define CECA_RT(RT) case RT: return launch_rounds<VEC, RT, THREADS>(mm, blocks, lds, st)
+#define CECA_RT(RT) case RT: return launch_rounds<VEC, RT, THREADS, LEAN>(mm, blocks, lds, st)
     CECA_RT(1); CECA_RT(2); CECA_RT(3); CECA_RT(4); CECA_RT(5); CECA_RT(6); CECA_RT(7); CECA_RT(8);
     CECA_RT(9); CECA_RT(10); CECA_RT(11); CECA_RT(12); CECA_RT(13); CECA_RT(14); CECA_RT(15); CECA_RT(16);
 #undef CECA_RT
@@ -378,6 +383,9 @@ hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st) {
   const size_t lds = (size_t)m.n * lanes * (vec4 ? 16 : 4);
   if (lds > kMultiMaxLds) return hipErrorInvalidValue;
   if (!vec4) return launch_rounds_rt<1, 256>(mm, (unsigned)blocks, lds, st);
+  if (threads == 256 && m.lean == 4) return launch_rounds_rt<4, 256, 4>(mm, (unsigned)blocks, lds, st);
+  if (threads == 256 && m.lean == 5) return launch_rounds_rt<4, 256, 5>(mm, (unsigned)blocks, lds, st);
+  if (threads == 256 && m.lean == 6) return launch_rounds_rt<4, 256, 6>(mm, (unsigned)blocks, lds, st);
   if (threads == 256) return launch_rounds_rt<4, 256>(mm, (unsigned)blocks, lds, st);
   if (threads == 512) return launch_rounds_rt<4, 512>(mm, (unsigned)blocks, lds, st);
   return launch_rounds_rt<4, 1024>(mm, (unsigned)blocks, lds, st);

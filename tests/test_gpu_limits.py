@@ -263,6 +263,17 @@ def test_workgroup_widths_of_the_fused_rounds_give_the_same_bits(env, n, port):
                 X = torch.from_numpy(x0).cuda()
                 P.ceca_average(X, X, n, d, port)
                 assert torch.equal(X, avg_ref[:n]), (threads, rows, "average")
+                if threads == 256:
+                    # the register-lean forms of the 256-thread kernel (4, 5 or 6 wavefronts per SIMD) and the plain one
+                    for lean in (1, 4, 5, 6):
+                        P.ceca_set_option(Bn.OPT_LEAN_TILES, lean)
+                        T.fill_(float("nan"))
+                        P.ceca_gossip_rounds(S, T, n, d, rounds, port)
+                        assert torch.equal(T, ref), (threads, rows, "lean", lean)
+                        X = torch.from_numpy(x0).cuda()
+                        P.ceca_average(X, X, n, d, port)
+                        assert torch.equal(X, avg_ref[:n]), (threads, rows, "average, lean", lean)
+                    P.ceca_set_option(Bn.OPT_LEAN_TILES, 0)
                 A = make_state(torch, x0, y0=y0)
                 B = torch.full_like(A, float("nan"))
                 P.dsgd_ceca_steps(A, B, n, d, Bn.make_quad_center_loss(cdev, 0.01, 5, 3), 0.1, 1 % max(tau, 1), 4, port)
@@ -275,8 +286,7 @@ def test_workgroup_widths_of_the_fused_rounds_give_the_same_bits(env, n, port):
                         mixed[name] = Y                     # first pass: 256-thread tiles, checked against the oracle below
                     assert torch.equal(Y, mixed[name]), (threads, rows, name)
     finally:
-        P.ceca_set_option(Bn.OPT_TILE_THREADS, 0)
-        P.ceca_set_option(Bn.OPT_ROWS, 0)
+        P.ceca_reset_options()
     otop = {"ring": [OT.ring(n)], "static": [OT.static_exponential(n)],
             "one_peer": [OT.one_peer_exponential(n, k) for k in range(max(tau, 1))]}
     for name, specs in otop.items():
