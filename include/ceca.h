@@ -201,7 +201,13 @@ int64_t consensus_error_workspace_bytes(int32_t n, int64_t d);
 
 /* Consensus observables of X (device, n rows of ld floats), accumulated in fp64:
  *   out[0] = ||X - 1 xbar^T||_F^2      (consensus distance of the descent lemma, App. B.3)
- *   out[1] = sum_i ||x_i - xbar||      (the residue plotted in Sec. 5, with xbar the current mean)
+ *   out[1] = sum_i ||x_i - xbar||      (the residue of Sec. 5 taken about the CURRENT row mean xbar; the paper's
+ *                                       residue is about x* = the mean of the initial x_i(0).  The two agree
+ *                                       whenever the rounds preserve the mean: gradient-free CECA from
+ *                                       y(0) = x(0), and the doubly stochastic comparison topologies.  They
+ *                                       differ along a DSGD trajectory, where xbar moves by -lr ebar per
+ *                                       iteration, and for graph weights that do not preserve the mean: there
+ *                                       out[1] / n is the mean distance to the averaged model, not to x*)
  *   out[2] = max_i ||x_i - xbar||
  *   out[3] = ||xbar||
  *   out[4] = n

@@ -402,13 +402,14 @@ def test_many_agent_logistic_full_length(env, capsys):
     assert abs(g_norm - want["mean_norm"]) <= diff_f / np.sqrt(n) + 1e-9 * want["mean_norm"]
 
 
-@pytest.mark.parametrize("name", ["paperlsq258_1p", "paperlsq258_2p"])
-def test_paper_least_squares_experiment(env, name):
+@pytest.mark.parametrize("name,run", [("paperlsq258_1p", 0), ("paperlsq258_2p", 0), ("paperlsq258_2p", 1), ("paperlsq258_1p", 3)])
+def test_paper_least_squares_experiment(env, name, run):
     """The paper's own least-squares setting (Sec. 5): n = 258, d = 10, N = 50, full gradient of
-    1/2 ||A_i x - b_i||^2 plus N(0, 25 I) noise, step 0.02 / 1.5^(k // 20).  d = 10 takes the scalar kernels."""
+    1/2 ||A_i x - b_i||^2 plus N(0, 25 I) noise, step 0.02 / 1.5^(k // 20).  d = 10 takes the scalar kernels.
+    The paper averages five independent runs: run 0 and other seeds are gated alike."""
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
-    sp = WL.SPECS[name]
+    sp = WL.for_run(WL.SPECS[name], run)
     n, d, N = sp.n, sp.d, sp.N
     A, b, xs = WL.lsq_data(n, N, d, sp.seed, obs_noise=sp.obs_noise)
     idx = WL.full_batch_indices(n, N)

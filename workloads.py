@@ -74,6 +74,13 @@ def step_size(spec: WorkloadSpec, k: int) -> float:
     return spec.lr
 
 
+def for_run(spec: WorkloadSpec, run: int) -> WorkloadSpec:
+    """The same workload with the seed of independent run number `run` (run 0 is the workload itself): the
+    paper averages its least-squares experiment over five runs and its consensus comparison over three
+    (Sec. 5)."""
+    return dataclasses.replace(spec, seed=spec.seed + 7919 * run)
+
+
 def full_batch_indices(n: int, N: int) -> np.ndarray:
     """Every agent uses all of its N rows: shape (1, n, N) int32 (one entry serves every iteration)."""
     return np.tile(np.arange(N, dtype=np.int32), (1, n, 1))
