@@ -352,6 +352,40 @@ def run_minibatch(torch, P, Bn, sp, steps, warmup):
     return tm, launches, minibatch_bytes(B)
 
 
+def run_consensus(torch, P, Bn, steps=20, warmup=3):
+    """consensus_error (x read once: 4 algorithmic bytes per agent-parameter) at the sizes of the three
+    configurations that report it, on the row pitch the other legs use; the allocation-free entry point beside
+    it; and the read-only probe on the same bytes."""
+    out = []
+    for name in ("quad31_2p", "gossip100_2p", "logistic1023_2p"):
+        sp = WL.SPECS[name]
+        n, d, ld = sp.n, sp.d, _ld(sp.d)
+        X = torch.empty((n, ld), dtype=torch.float32, device="cuda")
+        WL.device_normal((n, ld), sp.seed, out=X)
+        ws = torch.empty(P.consensus_error_workspace_bytes(n, d) + 256, dtype=torch.uint8, device="cuda")
+        ws = ws[(-ws.data_ptr()) % 256:]
+        res = torch.zeros(5, dtype=torch.float64, device="cuda")
+        e = {"workload": name, "n": n, "d": d, "algorithmic_bytes": 4.0 * n * d}
+        for key, call in (("consensus_error", lambda: P.consensus_error(X, n, d, res, workspace=ws, ld=ld)),
+                          ("consensus_error_noalloc", lambda: P.consensus_error_noalloc(X, n, d, res, ld=ld))):
+            for _ in range(warmup):
+                call()
+            with Timer(torch) as tm:
+                for _ in range(steps):
+                    call()
+            ms = tm.event_ms / steps
+            e[key] = {"ms_per_call": ms, "GBs": 4.0 * n * d / (ms * 1e-3) / 1e9, "frac": 4.0 * n * d / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        flat = X.reshape(-1)
+        ms, gbs = probe(torch, P, (flat, None, None, flat, None), n * ld, 1, 0)
+        e["read_only_probe_GBs"] = gbs
+        if 4.0 * n * d < 64e6:
+            e["bound"] = "launch latency (two launches, 17 MB): microseconds, not a bandwidth fraction"
+        out.append(e)
+        del X, ws
+        torch.cuda.empty_cache()
+    return out
+
+
 def paper_lsq_runs(torch, P, Bn, name, runs=5):
     """The paper's least-squares experiment (Sec. 5) as the paper reports it: mean over `runs` independent
     runs (data, x(0) and gradient noise redrawn) of the final distance of the averaged model to x* and of
@@ -679,6 +713,8 @@ def main():
     ap.add_argument("--others", action="store_true", help="also time the remaining workloads in full (reported under 'others')")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the short timings of the other configurations (the `configs` block of the default run)")
+    ap.add_argument("--consensus-only", action="store_true",
+                    help="time only consensus_error at the configuration sizes and exit")
     ap.add_argument("--mix-only", action="store_true",
                     help="time only the comparison-topology gossip rounds (n = 130 and n = 1026) and exit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
@@ -705,7 +741,7 @@ def main():
 
     # the CPU leg comes first: its worker processes are started from a process that holds no GPU state
     cpu = None
-    if not (args.no_cpu or args.mix_only or profiling):
+    if not (args.no_cpu or args.mix_only or args.consensus_only or profiling):
         cpu = cpu_baseline(sp)
 
     import torch
@@ -722,6 +758,16 @@ def main():
     if args.mix_only:
         print(json.dumps({"mix": [run_mix(torch, P, Bn, 130, 1 << 20, args.steps, args.warmup),
                                   run_mix(torch, P, Bn, 1026, 1 << 17, args.steps, args.warmup)]}), flush=True)
+        return
+
+    if args.consensus_only:
+        if args.copy_probe:
+            src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+            dst = torch.empty_like(src)
+            dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        print(json.dumps({"consensus": run_consensus(torch, P, Bn, args.steps, args.warmup)}), flush=True)
         return
 
     if args.copy_probe:
@@ -801,6 +847,7 @@ def main():
             if name.startswith("paperlsq258"):
                 cfgs[-1]["mean_over_5_runs"] = paper_lsq_runs(torch, P, Bn, name)
         out["configs"] = cfgs
+        out["consensus"] = run_consensus(torch, P, Bn)
     if args.others:
         out["others"] = []
         for name in sorted(WL.SPECS):

@@ -49,13 +49,18 @@ extern "C" {
  *                     0..4096 (raised where the partial sums would outgrow their 12 MiB share of the workspace)
  *   CECA_OPT_LEAN_TILES  fused gossip rounds / exact averaging with 256-thread workgroups: 4, 5 or 6 = the
  *                     register-lean form compiled for that many wavefronts per SIMD, 1 = always the plain form
+ *   CECA_OPT_HALF_STEP_RUN  1 (default): dsgd_ceca_run keeps the state in half-step form between fused iterations
+ *                     (no message buffers); 0: it keeps full states and two message buffers
+ *   CECA_OPT_PROBE_VARIANT  the 3-read / 2-write probe in another shape: 100 * policy (0 streaming loads and stores,
+ *                     1 plain loads, 2 plain stores, 3 both plain) + 10 * threads code (1 = 256, 2 = 512,
+ *                     4 = 1024 per workgroup) + column groups per thread (1, 2, 4, 8 with 256 threads)
  *   CECA_OPT_PROBE_WAVES  ceca_stream_probe: that many long-lived wavefronts walk the arrays (each thread keeps four
  *                     column groups of every array in flight) instead of one short-lived thread per column group
  * Returns CECA_EINVAL for an unknown option or value. */
 enum { CECA_OPT_SEGMENT = 1, CECA_OPT_ROWS = 2, CECA_OPT_BAND = 3, CECA_OPT_WG_PER_CU = 4, CECA_OPT_ONEPASS = 5,
        CECA_OPT_AGENTS_PER_WG = 7, CECA_OPT_CONS_SINGLE_PASS = 8, CECA_OPT_XCD_TILE_ORDER = 9,
        CECA_OPT_TILE_THREADS = 10, CECA_OPT_GRAPH_STAGE = 11, CECA_OPT_CHUNKED_GRADIENT = 12,
-       CECA_OPT_CONS_STRIPS = 13, CECA_OPT_PROBE_WAVES = 14, CECA_OPT_LEAN_TILES = 15 };
+       CECA_OPT_CONS_STRIPS = 13, CECA_OPT_PROBE_WAVES = 14, CECA_OPT_LEAN_TILES = 15, CECA_OPT_PROBE_VARIANT = 16, CECA_OPT_HALF_STEP_RUN = 17 };
 int32_t ceca_set_option(int32_t option, int32_t value);
 
 /* Every option of the calling thread back to the library default. */

@@ -12,7 +12,7 @@ CECA_OK, CECA_EINVAL, CECA_EODD1P, CECA_EWORKSPACE, CECA_EHIP = 0, -1, -2, -3, -
 LOSS_LSQ, LOSS_LOGISTIC, LOSS_QUAD_CENTER, LOSS_GRADIENT = 0, 1, 2, 3
 # options of the test and measurement interface (include/ceca_test.h)
 OPT_SEGMENT, OPT_ROWS, OPT_BAND, OPT_WG_PER_CU, OPT_ONEPASS, OPT_AGENTS_PER_WG, OPT_CONS_SINGLE_PASS, OPT_XCD_TILE_ORDER, OPT_TILE_THREADS = 1, 2, 3, 4, 5, 7, 8, 9, 10
-OPT_GRAPH_STAGE, OPT_CHUNKED_GRADIENT, OPT_CONS_STRIPS, OPT_PROBE_WAVES, OPT_LEAN_TILES = 11, 12, 13, 14, 15
+OPT_GRAPH_STAGE, OPT_CHUNKED_GRADIENT, OPT_CONS_STRIPS, OPT_PROBE_WAVES, OPT_LEAN_TILES, OPT_PROBE_VARIANT, OPT_HALF_STEP_RUN = 11, 12, 13, 14, 15, 16, 17
 TOPO_RING, TOPO_STATIC_EXP, TOPO_ONE_PEER_EXP = 0, 1, 2
 MIX_MAX = 16
 

@@ -556,9 +556,16 @@ int32_t ceca_set_option(int32_t option, int32_t value) {
     case CECA_OPT_CHUNKED_GRADIENT:
       t.never_chunked = value == 0;
       return CECA_OK;
+    case CECA_OPT_HALF_STEP_RUN:
+      t.no_half_step = value == 0;
+      return CECA_OK;
     case CECA_OPT_LEAN_TILES:
       if (value != 0 && value != 1 && (value < 4 || value > 6)) return fail(CECA_EINVAL, "lean tiles must be 0, 1, 4, 5 or 6");
       t.lean_tiles = value;
+      return CECA_OK;
+    case CECA_OPT_PROBE_VARIANT:
+      if (value < 0 || value > 399) return fail(CECA_EINVAL, "probe variant must be 0..399");
+      t.probe_variant = value;
       return CECA_OK;
     case CECA_OPT_PROBE_WAVES:
       if (value < 0 || value > (1 << 20)) return fail(CECA_EINVAL, "probe wavefronts must be 0..2^20");
@@ -922,6 +929,55 @@ int32_t dsgd_ceca_run(const float* S_in, float* S_out, int32_t n, int64_t d, int
       if (rc != CECA_OK) return rc;
     }
     return CECA_OK;
+  }
+  if (copy_fits && !g_tuning.no_half_step) {
+    // Between the iterations of this call the state lives in half-step form: rows xs = x - lr e, ys = y - lr e,
+    // of which the travelling one is the iteration's message bit for bit (Eqs. (8), (9) combine exactly these).
+    // Iteration t's kernel combines its agent's two rows with one row of its peer in registers, takes the
+    // gradient at the new z and writes the next half-step rows to the other of two buffers (the copy in the
+    // workspace and S_out): no message buffers, x+ and y+ never stored -- 20 bytes of state traffic per
+    // agent-parameter and iteration instead of 28.  A closing combine (a gossip round's arithmetic on the
+    // last half-step rows) writes x, y into S_out; the buffers alternate so that it reads the copy.
+    float* W = reinterpret_cast<float*>(w + 2 * p.v_bytes + p.partial_bytes);
+    auto H = [&](int32_t t) { return ((iters - 1 - t) & 1) == 0 ? W : S_out; };
+    ceca::GemvArgs g{};
+    g.ld = ld;  g.ldo = ld;
+    g.A = loss->A;  g.lda = loss->lda;  g.t = loss->t;
+    g.ldv = p.ldv;
+    g.d = d;
+    g.n = n;  g.N = loss->N;  g.B = loss->B;  g.kind = loss->kind;
+    g.lr = lr;
+    g.scale = loss->grad_scale > 0.0f ? loss->grad_scale : 1.0f / (float)loss->B;
+    g.noise_std = loss->noise_std;
+    g.seed = loss->seed;
+    ceca_round_t prev{};
+    for (int32_t t = 0; t < iters; ++t) {
+      ceca::fill_round(n, (r0 + t) % tau, port, &rd);
+      g.batch_idx = batch_idx + (int64_t)t * nb;
+      g.k = loss->k + (uint32_t)t;
+      const float* src = t == 0 ? S_in : H(t - 1);
+      float* dst = H(t);
+      g.px = src;  g.py = src + (int64_t)n * ld;
+      g.ox = dst;  g.oy = dst + (int64_t)n * ld;
+      g.p_first = t == 0;
+      g.p_shift = prev.shift;  g.p_port = port;
+      g.p_exch_y = prev.exchange_y;  g.p_read_y = prev.b_num != 0;
+      g.pa = prev.a;  g.pap = prev.a_peer;  g.pb = prev.b;  g.pbp = prev.b_peer;
+      g.new_exch_y = rd.exchange_y;
+      hipError_t e = hipSuccess;
+      if (!ceca::launch_grad_half(g, vec, st, &e)) return fail(CECA_EINVAL, "internal: fused gradient kernel does not cover this shape");
+      if (e != hipSuccess) return hip_fail(e, "gradient kernel launch");
+      prev = rd;
+    }
+    // x+ = a xs + (1 - a) v_peer, y+ = b ys + (1 - b) v_peer with v = the travelling half-step row: the
+    // gradient-free round's kernel with the last iteration's weights, from the copy into S_out
+    ceca::ChainArgs a{};
+    a.xin = W;  a.yin = W + (int64_t)n * ld;
+    a.xout = S_out;  a.yout = S_out + (int64_t)n * ld;
+    a.ld = ld;
+    a.n = n;
+    set_weights(prev, n, /*gossip_only=*/true, &a);
+    return run_chain(a, ceca::MODE_GOSSIP, d, vec && aligned16(S_out), prev, port, st);
   }
   float* V[2] = {reinterpret_cast<float*>(w), reinterpret_cast<float*>(w + p.v_bytes)};
   ceca::GemvArgs g{};

@@ -243,8 +243,13 @@ __global__ __launch_bounds__(THREADS) void grad_onepass_kernel(const GemvArgs P)
 // message and its peer's (Eqs. (8), (9), with the arithmetic of the combine kernel, operation for
 // operation) -- stores them, and takes the gradient at the new z.  One launch per iteration instead
 // of two, and the state rows (cache resident at these sizes) are touched once.
+// FUSE = 2: the state between iterations is kept in half-step form -- rows xs = x - lr e, ys = y - lr e of
+// the iteration before (the travelling one of the two IS that iteration's message, bit for bit) -- so the
+// prologue reads its own two rows and one row of its peer, combines in registers without storing x+, y+,
+// and the epilogue writes the new half-step rows to the other buffer: 20 bytes of state traffic per
+// agent-parameter and iteration instead of 28, with the arithmetic of FUSE = 1 operation for operation.
 // VEC = 1 is the same kernel on single columns, for layouts that are not 16-byte aligned.
-template <int VEC, int THREADS, int CH, int G, bool FUSE>
+template <int VEC, int THREADS, int CH, int G, int FUSE>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(G == 1 ? 8 : 4, 8)))
 void grad_chunked_kernel(const GemvArgs P) {
   using V = typename VecOf<VEC>::T;
@@ -256,6 +261,7 @@ void grad_chunked_kernel(const GemvArgs P) {
   int64_t col[G];
   bool on[G];
   V z[G], e[G];
+  V other[FUSE == 2 ? G : 1];              // FUSE = 2: the variable that does not travel this iteration, after the combine
 #pragma unroll
   for (int u = 0; u < G; ++u) {
     const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * VEC;
@@ -279,11 +285,33 @@ void grad_chunked_kernel(const GemvArgs P) {
   };
   // without the prologue the first rows are requested before z; with it they follow it: the prologue
   // needs 24 registers of its own, and loads return in order anyway
-  if (!FUSE) request_rows(0);
+  if (FUSE == 0) request_rows(0);
 #pragma unroll
   for (int u = 0; u < G; ++u) {
     V zv;
-    if (FUSE) {
+    if (FUSE == 2) {
+#pragma clang fp contract(off)
+      const int64_t off = (int64_t)agent * P.ld + col[u];
+      const V hx = ld_plain<V>(P.px + off);
+      const V hy = ld_plain<V>(P.py + off);
+      V xn = hx, yn = hy;                  // the call's first iteration starts from x, y themselves
+      if (!P.p_first) {
+        int p;
+        if (P.p_port == 2) {
+          p = agent - P.p_shift; if (p < 0) p += P.n;
+        } else {
+          p = (agent & 1) ? agent - P.p_shift : agent + P.p_shift;
+          if (p < 0) p += P.n;
+          if (p >= P.n) p -= P.n;
+        }
+        // the peer's message is the travelling row of its half-step state
+        const V msg = ld_plain<V>((P.p_exch_y ? P.py : P.px) + (int64_t)p * P.ld + col[u]);
+        xn = combine(P.pa, hx, P.pap, msg);
+        yn = P.p_read_y ? combine(P.pb, hy, P.pbp, msg) : P.pbp * msg;
+      }
+      zv = P.new_exch_y ? yn : xn;
+      other[u] = P.new_exch_y ? xn : yn;
+    } else if (FUSE == 1) {
 #pragma clang fp contract(off)
       int p;
       if (P.p_port == 2) {
@@ -314,7 +342,7 @@ void grad_chunked_kernel(const GemvArgs P) {
     z[u] = on[u] ? zv : V(0.0f);
     e[u] = V(0.0f);
   }
-  if (FUSE) request_rows(0);
+  if (FUSE != 0) request_rows(0);
   int turn = 0;
   for (int c0 = 0; c0 < P.B; c0 += CH, turn ^= 1) {
     float m[CH];
@@ -346,14 +374,27 @@ void grad_chunked_kernel(const GemvArgs P) {
   for (int u = 0; u < G; ++u) {
     V ee = e[u];
     if (P.noise_std != 0.0f) ee += P.noise_std * noise_group<V>(col[u], noise_keys(P.seed, P.k, (uint32_t)agent));
-    if (on[u]) *reinterpret_cast<V*>(P.v + (int64_t)agent * P.ldv + col[u]) = z[u] - P.lr * ee;
+    const V v = z[u] - P.lr * ee;
+    if (FUSE == 2) {
+      // half-step rows for the next iteration's combine: the travelling variable becomes the message itself,
+      // the other moves by the same -lr e = v - z (the arithmetic of the combine kernel on stored messages)
+      const V dz = v - z[u];
+      const V moved = other[u] + dz;
+      if (on[u]) {
+        const int64_t off = (int64_t)agent * P.ldo + col[u];
+        *reinterpret_cast<V*>(P.ox + off) = P.new_exch_y ? moved : v;
+        *reinterpret_cast<V*>(P.oy + off) = P.new_exch_y ? v : moved;
+      }
+    } else {
+      if (on[u]) *reinterpret_cast<V*>(P.v + (int64_t)agent * P.ldv + col[u]) = v;
+    }
   }
 }
 
 // The chunked kernel for rows of d4 16-byte groups.  Workgroup size and column groups per thread are a
 // function of d4 alone and equal those of the one-pass variant for the same d4, so either kernel (and
 // the fused form) produces the same bits.
-template <bool FUSE>
+template <int FUSE>
 static hipError_t launch_chunked(const GemvArgs& g, hipStream_t st) {
   const int64_t d4 = g.d / 4;
   dim3 grid((unsigned)g.n);
@@ -365,7 +406,7 @@ static hipError_t launch_chunked(const GemvArgs& g, hipStream_t st) {
 }
 
 // Layouts that are not 16-byte aligned: one column per thread, rows of at most 1024 columns, any batch.
-template <bool FUSE>
+template <int FUSE>
 static hipError_t launch_chunked_scalar(const GemvArgs& g, hipStream_t st) {
   dim3 grid((unsigned)g.n);
   if (g.d <= 64) grad_chunked_kernel<1, 64, 8, 1, FUSE><<<grid, dim3(64), 0, st>>>(g);
@@ -395,7 +436,15 @@ bool grad_fused_covers(int32_t n, int64_t d, int32_t B, bool vec4) {
 
 bool launch_grad_fused(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t* err) {
   if (!grad_fused_covers(g.n, g.d, g.B, vec4)) return false;
-  *err = vec4 ? launch_chunked<true>(g, st) : launch_chunked_scalar<true>(g, st);
+  *err = vec4 ? launch_chunked<1>(g, st) : launch_chunked_scalar<1>(g, st);
+  return true;
+}
+
+// The same with the state kept in half-step form between iterations (px, py -> ox, oy: two different buffers).
+bool launch_grad_half(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t* err) {
+  if (!grad_fused_covers(g.n, g.d, g.B, vec4)) return false;
+  if (g.px == g.ox && !g.p_first) { *err = hipErrorInvalidValue; return true; }     // peers' rows are read while rows are written
+  *err = vec4 ? launch_chunked<2>(g, st) : launch_chunked_scalar<2>(g, st);
   return true;
 }
 
@@ -403,7 +452,7 @@ bool launch_grad_fused(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t*
 // for one workgroup (then the two-pass kernels run).
 bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   if (g.d > 1024) return false;
-  *err = launch_chunked_scalar<false>(g, st);
+  *err = launch_chunked_scalar<0>(g, st);
   return true;
 }
 
@@ -414,7 +463,7 @@ bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err) {
   // many agents, long rows: the chunked kernel (any B up to 64, d up to 16384), two workgroups per
   // compute unit; a handful of agents cannot fill the device that way and stays with the kernels below
   if (chunked_by_default(g.n, d4) && !g_tuning.never_chunked) {
-    *err = launch_chunked<false>(g, st);
+    *err = launch_chunked<0>(g, st);
     return true;
   }
   // 1024-thread workgroups fill a compute unit alone: one per unit, each looping over its agents;

@@ -100,6 +100,7 @@ struct GemvArgs {
   int32_t p_shift, p_port, p_exch_y, p_read_y;
   float pa, pap, pb, pbp; // its weights
   int32_t new_exch_y;
+  int32_t p_first;        // half-step form only: 1 = no iteration before (px, py are x, y themselves)
 };
 
 struct ConsensusArgs {
@@ -200,7 +201,9 @@ struct Tuning {
   int32_t cons_strips;          // strips one wavefront of the consensus kernel takes in turn
   int32_t plain_tile_order;     // 1: register-tile kernels never use the XCD-contiguous tile order
   int32_t graph_tables_in_memory;  // 1: graph gossip reads its tables from memory at every look-up
+  int32_t no_half_step;         // 1: dsgd_ceca_run keeps full states and message buffers between fused iterations
   int32_t lean_tiles;           // gossip-rounds kernel with 256 threads: 4, 5, 6 = the register-lean form for that many wavefronts per SIMD
+  int32_t probe_variant;        // 3-read / 2-write probe: policy * 100 + threads code * 10 + column groups per thread
   int32_t probe_waves;          // probe kernels: that many long-lived wavefronts instead of one thread per column group
 };
 extern thread_local Tuning g_tuning;
@@ -212,6 +215,9 @@ bool launch_grad_onepass(const GemvArgs& g, hipStream_t st, hipError_t* err);
 // gradient kernel with the previous iteration's combine as its prologue; false when the shape is not covered
 bool launch_grad_fused(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t* err);
 bool grad_fused_covers(int32_t n, int64_t d, int32_t B, bool vec4);
+// the fused form with the state in half-step rows between iterations: reads px, py (pitch ld), writes ox, oy
+// (pitch ldo, another buffer unless p_first); false when the shape is not covered
+bool launch_grad_half(const GemvArgs& g, bool vec4, hipStream_t st, hipError_t* err);
 // single-step gradient for layouts that are not 16-byte aligned (rows up to 1024 columns); false otherwise
 bool launch_grad_scalar(const GemvArgs& g, hipStream_t st, hipError_t* err);
 hipError_t launch_multi_round(const MultiArgs& m, bool vec4, hipStream_t st);

@@ -60,11 +60,63 @@ __global__ __launch_bounds__(kBlock) void stream_probe_loop_kernel(const float* 
   }
 }
 
+// Variants of the 3-read / 2-write probe for exploring what the memory system rewards: U consecutive
+// column groups per thread (a workgroup then covers U * THREADS * 16 contiguous bytes of every array,
+// thread t taking groups t, t + THREADS, ...), THREADS per workgroup, streaming (nontemporal) or plain
+// loads and stores.
+template <int U, int THREADS, bool NTL, bool NTS>
+__global__ __launch_bounds__(THREADS) void stream_probe_variant_kernel(const float* a, const float* b, const float* c,
+                                                                       float* o1, float* o2, int64_t ngroups) {
+  const int64_t base = (int64_t)blockIdx.x * (U * THREADS) + threadIdx.x;
+  vf4 x[U], y[U], z[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int64_t g = base + u * THREADS < ngroups ? base + u * THREADS : 0;
+    x[u] = NTL ? ld_stream<vf4>(a + 4 * g) : ld_plain<vf4>(a + 4 * g);
+    y[u] = NTL ? ld_stream<vf4>(b + 4 * g) : ld_plain<vf4>(b + 4 * g);
+    z[u] = NTL ? ld_stream<vf4>(c + 4 * g) : ld_plain<vf4>(c + 4 * g);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int64_t g = base + u * THREADS;
+    if (g >= ngroups) continue;
+    const vf4 p = 0.5f * x[u] + 0.5f * (y[u] - 0.1f * (y[u] - z[u]));
+    const vf4 q = 0.4f * y[u] + 0.6f * (x[u] - 0.1f * (x[u] - z[u]));
+    if (NTS) { st_stream<vf4>(o1 + 4 * g, p); st_stream<vf4>(o2 + 4 * g, q); }
+    else { *reinterpret_cast<vf4*>(o1 + 4 * g) = p; *reinterpret_cast<vf4*>(o2 + 4 * g) = q; }
+  }
+}
+
+template <int U, int THREADS>
+static hipError_t launch_probe_variant(const float* a, const float* b, const float* c, float* o1, float* o2,
+                                       int64_t ngroups, int policy, hipStream_t st) {
+  const int64_t blocks = (ngroups + (int64_t)U * THREADS - 1) / ((int64_t)U * THREADS);
+  if (blocks < 1 || blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+  const dim3 grid((unsigned)blocks), block(THREADS);
+  switch (policy) {
+    case 0: stream_probe_variant_kernel<U, THREADS, true, true><<<grid, block, 0, st>>>(a, b, c, o1, o2, ngroups); break;
+    case 1: stream_probe_variant_kernel<U, THREADS, false, true><<<grid, block, 0, st>>>(a, b, c, o1, o2, ngroups); break;
+    case 2: stream_probe_variant_kernel<U, THREADS, true, false><<<grid, block, 0, st>>>(a, b, c, o1, o2, ngroups); break;
+    default: stream_probe_variant_kernel<U, THREADS, false, false><<<grid, block, 0, st>>>(a, b, c, o1, o2, ngroups); break;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_stream_probe(const float* a, const float* b, const float* c, float* o1, float* o2, int64_t ngroups,
                                int reads, int writes, hipStream_t st) {
   const int64_t blocks = (ngroups + kBlock - 1) / kBlock;
   if (blocks < 1 || blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
   const dim3 grid((unsigned)blocks), block(kBlock);
+  const int variant = g_tuning.probe_variant;       // decimal digits: policy (0..3), threads (1 = 256, 2 = 512, 4 = 1024), groups per thread
+  if (variant > 0 && reads == 3 && writes == 2) {
+    const int U = variant % 10, T = (variant / 10) % 10, pol = (variant / 100) % 10;
+#define CECA_PV(UU, TT, THR) if (U == UU && T == TT) return launch_probe_variant<UU, THR>(a, b, c, o1, o2, ngroups, pol, st);
+    CECA_PV(1, 1, 256) CECA_PV(2, 1, 256) CECA_PV(4, 1, 256) CECA_PV(8, 1, 256)
+    CECA_PV(1, 2, 512) CECA_PV(2, 2, 512) CECA_PV(4, 2, 512)
+    CECA_PV(1, 4, 1024) CECA_PV(2, 4, 1024) CECA_PV(4, 4, 1024)
+#undef CECA_PV
+    return hipErrorInvalidValue;
+  }
   const int waves = g_tuning.probe_waves;
   if (waves > 0) {
     // long-lived wavefronts, in workgroups of one wavefront so that they spread over the SIMDs

@@ -60,23 +60,35 @@ def test_run_equals_single_steps_and_oracle(env, kind, n, port, d, B, ld):
     ws1 = _aligned(torch, P.dsgd_ceca_workspace_bytes(n, d, mk(0)))
     S = make_state(torch, x0, y0=y0, ld=ld)
     T = S if port == 1 else make_state(torch, np.zeros_like(x0), ld=ld)
+    mid = None
     for t_ in range(iters):
+        if t_ == iters - 1:
+            mid = S.clone()                                  # the state after iters - 1 iterations
         P.dsgd_ceca_step(S, T, n, d, mk(k0 + t_), idxd[t_], lr, (k0 + t_) % tau, port, workspace=ws1)
         if T is not S:
             S, T = T, S
     rx, ry = split_state(S, n, d)
     ws = _aligned(torch, P.dsgd_ceca_run_workspace_bytes(n, d, mk(0)))
-    for inplace in (False, True):
-        A_ = make_state(torch, x0, y0=y0, ld=ld)
-        B_ = A_ if inplace else make_state(torch, np.zeros_like(x0), ld=ld)
-        P.dsgd_ceca_run(A_, B_, n, d, mk(k0), idxd, lr, k0 % tau, iters, port, workspace=ws)
-        gx, gy = split_state(B_, n, d)
-        assert np.array_equal(gx, rx) and np.array_equal(gy, ry), inplace
-        if not inplace:
-            ax, ay = split_state(A_, n, d)
-            assert np.array_equal(ax, x0.astype(np.float64)) and np.array_equal(ay, y0.astype(np.float64))
-        if ld is not None:
-            assert bool((B_[:, d:] == 12345.0).all())
+    # fused iterations keep the state in half-step form between them (default) or as full states with two
+    # message buffers; shapes on the two-pass gradient are not affected by the switch
+    for half in (1, 0):
+        P.ceca_set_option(Bn.OPT_HALF_STEP_RUN, half)
+        for inplace in (False, True):
+            for count in (iters, iters - 1):                 # odd and even: the closing combine always reads the copy
+                A_ = make_state(torch, x0, y0=y0, ld=ld)
+                B_ = A_ if inplace else make_state(torch, np.zeros_like(x0), ld=ld)
+                P.dsgd_ceca_run(A_, B_, n, d, mk(k0), idxd, lr, k0 % tau, count, port, workspace=ws)
+                if count == iters:
+                    gx, gy = split_state(B_, n, d)
+                    assert np.array_equal(gx, rx) and np.array_equal(gy, ry), (half, inplace)
+                else:
+                    assert torch.equal(B_[:, :d], mid[:, :d]), (half, inplace, "one iteration fewer")
+                if not inplace:
+                    ax, ay = split_state(A_, n, d)
+                    assert np.array_equal(ax, x0.astype(np.float64)) and np.array_equal(ay, y0.astype(np.float64))
+                if ld is not None:
+                    assert bool((B_[:, d:] == 12345.0).all())
+    P.ceca_reset_options()
     grad = OL.make_minibatch_grad(kind, A, t, idx, k0=k0, noise_std=noise, seed=9)
     x, y = OC.run(x0, port, lr, grad, iters, store32=True, y0=y0, k0=k0)
     assert max(rel_err(rx, x)) <= 1e-4 and max(rel_err(ry, y)) <= 1e-4
