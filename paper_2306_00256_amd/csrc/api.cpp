@@ -238,7 +238,7 @@ struct ConsPlan {
   // two-pass form
   int64_t ntiles;
   int32_t agent_groups, agents_per_group, dev_agents;
-  int64_t off_norm, off_devpart, off_dev2, off_counter, two_pass_total;
+  int64_t off_norm, off_devpart, off_dev2, two_pass_total;
   // TILE form: rows per thread (0 = not available for this n), row lanes, tiles for 16-byte / scalar groups
   int32_t rows_per_thread, row_lanes;
   int64_t tile_ntiles_vec, tile_ntiles_scalar;
@@ -250,7 +250,7 @@ struct ConsPlan {
   int64_t bound;               // workspace that covers every form and launch shape
 };
 
-struct ConsWave { int64_t strips, nwaves, off_dev2, off_counter, total; };
+struct ConsWave { int64_t strips, nwaves, off_dev2, total; };
 
 // The WAVE form's launch for this layout: strips of wave_cgs column groups, strips per wavefront.
 ConsWave cons_wave(const ConsPlan& p, int32_t n, int64_t d, bool vec4) {
@@ -266,8 +266,7 @@ ConsWave cons_wave(const ConsPlan& p, int32_t n, int64_t d, bool vec4) {
   per = std::max(per, (w.strips + p.wave_cap - 1) / p.wave_cap);
   w.nwaves = (w.strips + per - 1) / per;
   w.off_dev2 = round_up(((int64_t)n + 1) * w.nwaves * 8, 256);
-  w.off_counter = w.off_dev2 + round_up(((int64_t)n + 1) * 8, 256);
-  w.total = w.off_counter + 256;
+  w.total = w.off_dev2 + round_up(((int64_t)n + 1) * 8, 256);
   return w;
 }
 
@@ -292,7 +291,6 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
   p.off_norm = off;     off += round_up(p.ntiles * 8, 256);
   p.off_devpart = off;  off += round_up((int64_t)n * p.ntiles * 8, 256);
   p.off_dev2 = off;     off += round_up((int64_t)n * 8, 256);
-  p.off_counter = off;  off += 256;
   p.two_pass_total = off;
   p.bound = off;
   // TILE form: every agent's column tile in one workgroup (x-only tiling of the fused-round kernels)
@@ -320,7 +318,7 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
     }
     if (p.rows_per_thread > 0) {
       p.tile_total = round_up(p.tile_ntiles_scalar * 8, 256) + round_up((int64_t)n * p.tile_ntiles_scalar * 8, 256) +
-                     round_up((int64_t)n * 8, 256) + 256;
+                     round_up((int64_t)n * 8, 256);
     }
   }
   // WAVE form
@@ -348,7 +346,7 @@ ConsPlan cons_plan(int32_t n, int64_t d) {
   // the WAVE form never exceeds its cap whatever its launch shape; the TILE form's share follows the
   // calling thread's tuning (ask for the size after setting the options)
   const int64_t wave_bound = round_up(((int64_t)n + 1) * std::max<int64_t>(kConsWavePartialBytes / (((int64_t)n + 1) * 8), 64) * 8, 256) +
-                             round_up(((int64_t)n + 1) * 8, 256) + 256;
+                             round_up(((int64_t)n + 1) * 8, 256);
   p.bound = std::max(p.bound, wave_bound);
   p.bound = std::max(p.bound, p.tile_total);
   return p;
@@ -1276,16 +1274,13 @@ int32_t run_consensus(const float* X, int32_t n, int64_t d, int64_t ld, double* 
     c.strips = cw.strips;  c.nwaves = cw.nwaves;
     c.devpart = reinterpret_cast<double*>(w);
     c.dev2 = reinterpret_cast<double*>(w + cw.off_dev2);
-    c.counter = reinterpret_cast<uint32_t*>(w + cw.off_counter);
   } else if (form == CONS_TILE) {
     // single pass over x; the workspace then holds only the partials: normpart[ntiles], devpart[n][ntiles], dev2[n]
     c.ntiles = vec ? p.tile_ntiles_vec : p.tile_ntiles_scalar;
     const int64_t off_devpart = round_up(c.ntiles * 8, 256);
     const int64_t off_dev2 = off_devpart + round_up((int64_t)n * c.ntiles * 8, 256);
-    const int64_t off_counter = off_dev2 + round_up((int64_t)n * 8, 256);
-    *need = off_counter + 256;
+    *need = off_dev2 + round_up((int64_t)n * 8, 256);
     if (have < *need) return CECA_EWORKSPACE;
-    c.counter = reinterpret_cast<uint32_t*>(w + off_counter);
     c.rows_per_thread = p.rows_per_thread;
     c.row_lanes = p.row_lanes;
     c.normpart = reinterpret_cast<double*>(w);
@@ -1302,7 +1297,6 @@ int32_t run_consensus(const float* X, int32_t n, int64_t d, int64_t ld, double* 
     c.normpart = reinterpret_cast<double*>(w + p.off_norm);
     c.devpart = reinterpret_cast<double*>(w + p.off_devpart);
     c.dev2 = reinterpret_cast<double*>(w + p.off_dev2);
-    c.counter = reinterpret_cast<uint32_t*>(w + p.off_counter);
   }
   const hipError_t e = ceca::launch_consensus(c, vec, st);
   if (e != hipSuccess) return hip_fail(e, "consensus kernels launch");

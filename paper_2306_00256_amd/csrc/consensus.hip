@@ -39,7 +39,6 @@ __global__ __launch_bounds__(kBlock) void colsum_kernel(const ConsensusArgs C) {
 // slice 0 of colsum <- mean; optional fp32 copy; per-workgroup partial of ||xbar||^2
 __global__ __launch_bounds__(kBlock) void mean_kernel(const ConsensusArgs C) {
   __shared__ double red[kBlock / 64];
-  if (blockIdx.x == 0 && threadIdx.x == 0) *C.counter = 0u;      // the closing kernel counts its workgroups from zero
   double sq = 0.0;
   const int64_t base = (int64_t)blockIdx.x * kConsTile;
   for (int q = 0; q < (int)(kConsTile / kBlock); ++q) {
@@ -120,7 +119,6 @@ __global__ __launch_bounds__(kBlock) void cons_tile_kernel(const ConsensusArgs C
   const int cg = threadIdx.x % lanes;
   const int rg = threadIdx.x / lanes;
   const int64_t tile = blockIdx.x;
-  if (blockIdx.x == 0 && threadIdx.x == 0) *C.counter = 0u;      // the closing kernel counts its workgroups from zero
   const int64_t g = tile * lanes + cg;
   const int64_t ngroups = (C.d + VEC - 1) / VEC;   // d is a multiple of VEC on the vector path
   const bool on = g < ngroups;
@@ -184,7 +182,6 @@ __global__ __launch_bounds__(kBlock) void cons_wave_kernel(const ConsensusArgs C
   constexpr int LOG_RTP = RTP == 1 ? 0 : RTP == 2 ? 1 : RTP == 4 ? 2 : RTP == 8 ? 3 : RTP == 16 ? 4 : 5;
   const int lane = threadIdx.x & 63;
   const int64_t w = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (blockIdx.x == 0 && threadIdx.x == 0) *C.counter = 0u;      // the closing kernel counts its workgroups from zero
   if (w >= C.nwaves) return;                        // the whole wavefront leaves
   const int cgs = C.wave_cgs;                       // column groups per strip: a power of two, 1..64
   const int cg = lane & (cgs - 1);
@@ -269,39 +266,13 @@ __global__ __launch_bounds__(kBlock) void cons_wave_kernel(const ConsensusArgs C
   if (lane == 0) C.devpart[(int64_t)C.n * C.nwaves + w] = nrm;
 }
 
-// Closing kernel, a workgroup per row (or few rows) of devpart: dev2[row] = sum over tiles (or wavefronts)
-// of devpart[row][.]; the workgroup that finishes last (a counter that an earlier kernel of the same call set
-// to zero tells it) then reduces dev2 and the partials of ||xbar||^2 to the five results.  Every sum runs in
-// a fixed order, so which workgroup happens to be last does not change a bit of the result.  The grid is
-// capped (kCloseBlocks): each workgroup's device-wide fence has a cost that must not grow with n.
-constexpr int kCloseBlocks = 32;
-__global__ __launch_bounds__(kBlock) void close_kernel(const ConsensusArgs C) {
-  __shared__ double red[kBlock / 64];
-  __shared__ bool last;
-  for (int i = blockIdx.x; i < C.close_rows; i += gridDim.x) {
-    double s = 0.0;
-    for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) s += C.devpart[(int64_t)i * C.ntiles + t];
-    s = wave_sum(s);
-    __syncthreads();                                 // red[] of the previous row has been consumed
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      double t = 0.0;
-      for (int w = 0; w < kBlock / 64; ++w) t += red[w];
-      C.dev2[i] = t;
-    }
-  }
-  if (threadIdx.x == 0) {
-    __threadfence();                                 // my dev2 entries are visible device-wide before the count goes up
-    last = atomicAdd(C.counter, 1u) == gridDim.x - 1;
-  }
-  __syncthreads();
-  if (!last) return;
-  __threadfence();                                   // every other workgroup's dev2 entry is visible from here on
+// The five results from the per-agent squared deviations dev2[0..n) and the partials of ||xbar||^2 (every
+// sum in a fixed order).  One workgroup.
+__device__ __forceinline__ void finish_results(const ConsensusArgs& C, const double* dev2) {
   __shared__ double r0[kBlock / 64], r1[kBlock / 64], r2[kBlock / 64], r3[kBlock / 64];
   double frob = 0.0, resid = 0.0, mx = 0.0, nrm = 0.0;
   for (int a = threadIdx.x; a < C.n; a += kBlock) {
-    const double d2 = C.dev2[a];
+    const double d2 = dev2[a];
     const double dv = sqrt(d2);
     frob += d2; resid += dv; mx = fmax(mx, dv);
   }
@@ -316,6 +287,58 @@ __global__ __launch_bounds__(kBlock) void close_kernel(const ConsensusArgs C) {
     double a = 0.0, b = 0.0, c = 0.0, d = 0.0;
     for (int w = 0; w < kBlock / 64; ++w) { a += r0[w]; b += r1[w]; c = fmax(c, r2[w]); d += r3[w]; }
     C.out[0] = a; C.out[1] = b; C.out[2] = c; C.out[3] = sqrt(d); C.out[4] = (double)C.n;
+  }
+}
+
+// dev2[row] = sum over tiles (or wavefronts) of devpart[row][.]; one workgroup per row
+__global__ __launch_bounds__(kBlock) void devsum_kernel(const ConsensusArgs C) {
+  __shared__ double red[kBlock / 64];
+  const int i = blockIdx.x;
+  double s = 0.0;
+  for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) s += C.devpart[(int64_t)i * C.ntiles + t];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+    C.dev2[i] = t;
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void finish_kernel(const ConsensusArgs C) { finish_results(C, C.dev2); }
+
+// Few partials in all (small problems, where every launch counts): one workgroup sums the rows of devpart in
+// turn (same order of additions as devsum_kernel) and finishes, in one launch.
+__global__ __launch_bounds__(kBlock) void close_small_kernel(const ConsensusArgs C) {
+  __shared__ double red[kBlock / 64];
+  for (int i = 0; i < C.close_rows; ++i) {
+    double s = 0.0;
+    for (int64_t t = threadIdx.x; t < C.ntiles; t += kBlock) s += C.devpart[(int64_t)i * C.ntiles + t];
+    s = wave_sum(s);
+    __syncthreads();                                 // red[] of the row before has been consumed
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      for (int w = 0; w < kBlock / 64; ++w) t += red[w];
+      C.dev2[i] = t;
+    }
+  }
+  __threadfence_block();
+  __syncthreads();                                   // this workgroup wrote dev2 itself: visible to all its threads
+  finish_results(C, C.dev2);
+}
+
+// Closes a consensus call: dev2 from the partials of `rows` rows (n, or n + 1 with ||xbar||^2 as the last), then
+// the results.
+static void launch_close(ConsensusArgs& c, int rows, hipStream_t st) {
+  c.close_rows = rows;
+  if ((int64_t)rows * c.ntiles <= 16384) {
+    close_small_kernel<<<dim3(1), dim3(kBlock), 0, st>>>(c);
+  } else {
+    devsum_kernel<<<dim3((unsigned)rows), dim3(kBlock), 0, st>>>(c);
+    finish_kernel<<<dim3(1), dim3(kBlock), 0, st>>>(c);
   }
 }
 
@@ -350,8 +373,7 @@ static hipError_t launch_cons_tile(ConsensusArgs c, bool vec4, hipStream_t st) {
   else CECA_CONS1(32);
 #undef CECA_CONS4
 #undef CECA_CONS1
-  c.close_rows = c.n;
-  close_kernel<<<dim3((unsigned)(c.n < kCloseBlocks ? c.n : kCloseBlocks)), block, 0, st>>>(c);
+  launch_close(c, c.n, st);
   return hipGetLastError();
 }
 
@@ -389,8 +411,7 @@ static hipError_t launch_cons_wave(const ConsensusArgs& c0, bool vec4, hipStream
   }
 #undef CECA_CW4
 #undef CECA_CW1
-  c.close_rows = c.n + 1;
-  close_kernel<<<dim3((unsigned)(c.n + 1 < kCloseBlocks ? c.n + 1 : kCloseBlocks)), dim3(kBlock), 0, st>>>(c);
+  launch_close(c, c.n + 1, st);
   return hipGetLastError();
 }
 
@@ -417,8 +438,7 @@ hipError_t launch_consensus(const ConsensusArgs& c0, bool vec4, hipStream_t st) 
     if (vec4) dev_kernel<4><<<grid, block, 0, st>>>(c);
     else dev_kernel<1><<<grid, block, 0, st>>>(c);
   }
-  c.close_rows = c.n;
-  close_kernel<<<dim3((unsigned)(c.n < kCloseBlocks ? c.n : kCloseBlocks)), block, 0, st>>>(c);
+  launch_close(c, c.n, st);
   return hipGetLastError();
 }
 

@@ -127,8 +127,7 @@ struct ConsensusArgs {
   int64_t strips;          // column strips in all
   int64_t nwaves;          // wavefronts launched; wavefront w takes strips w, w + nwaves, ...
   int64_t norm_count;      // entries of normpart (set by the launcher)
-  int32_t close_rows;      // rows of devpart the closing kernel reduces (set by the launcher)
-  uint32_t* counter;       // workgroups of the closing kernel that are done (zeroed by the call's first big kernel)
+  int32_t close_rows;      // rows of devpart the closing kernels reduce (set by the launcher)
 };
 
 // Fused iterations with the quadratic-centre loss: the rounds of MultiArgs plus what the gradient needs.
