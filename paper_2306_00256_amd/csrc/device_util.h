@@ -177,11 +177,14 @@ template <> __device__ __forceinline__ float noise_group<float>(int64_t col, Noi
   return (col & 1) ? b : a;
 }
 
-// w * self + wp * msg, with one fixed rounding order wherever it is evaluated.
+// w * self + wp * msg, with one fixed rounding order wherever it is evaluated: the product with self is
+// rounded, then the peer's term is added by a fused multiply-add.  In this order the result can replace
+// self in its own register (multiply in place, accumulate in place): kernels that carry self across a loop
+// need no copy per element and round.
 __device__ __forceinline__ float combine(float w, float self, float wp, float msg) {
 #pragma clang fp contract(off)
-  const float t = wp * msg;
-  return __builtin_fmaf(w, self, t);
+  const float t = w * self;
+  return __builtin_fmaf(wp, msg, t);
 }
 __device__ __forceinline__ vf4 combine(float w, vf4 self, float wp, vf4 msg) {
   vf4 o;

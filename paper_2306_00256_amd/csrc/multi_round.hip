@@ -35,6 +35,24 @@ constexpr int multi_round_waves() { return THREADS > 256 ? 4 : 1; }
 template <int THREADS, int LEAN>
 constexpr int rounds_waves() { return LEAN > 0 ? LEAN : multi_round_waves<THREADS>(); }
 
+// Peer slots of a round, per thread: my row k < RT - 1 sits in slot tid + k * THREADS and reads the slot
+// `shift` rows before it (two ports), or `shift` rows ahead (even rows) / back (odd rows) with one port
+// (Eq. (7)), modulo the tile.  base[p] is that slot for k = 0 with p the parity of k (my rows share one
+// parity unless I hold consecutive rows); row k adds k * THREADS, which can pass the end of the tile once.
+struct PeerSlots {
+  int base[2];
+  int last;     // peer slot of my last row (which may shadow agent n - 1)
+};
+template <int THREADS>
+__device__ __forceinline__ int peer_slot(const PeerSlots& P, int k, int wrap) {
+  const int t = P.base[k & 1] + k * THREADS;               // in [0, 2 * wrap)
+  return (int)min((unsigned)t, (unsigned)(t - wrap));      // t - wrap when that is not negative
+}
+__device__ __forceinline__ int wrap_slot(int s, int wrap) {   // s in (-wrap, 2 * wrap)
+  if (s < 0) s += wrap;
+  return (int)min((unsigned)s, (unsigned)(s - wrap));
+}
+
 template <int VEC, int RT, int THREADS, int LEAN>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(rounds_waves<THREADS, LEAN>())))
 void multi_round_kernel(const MultiArgs M) {
@@ -59,7 +77,7 @@ void multi_round_kernel(const MultiArgs M) {
     // surrounds a load, so all of a thread's rows are in flight together
     const int i = min(rg + k * M.row_lanes, M.n - 1);
     x[k] = ld_stream<V>(M.xin + (int64_t)i * M.ld + col);
-    y[k] = V(0.0f);                                // round 0 has b = 0: y(0) is never used
+    y[k] = V(-0.0f);                               // y(0) is never read: the first round has b = 0
   }
   V* zs = reinterpret_cast<V*>(lds_z);
   // Row i, column group c sits in LDS slot i * lanes + c, so my row k is slot tid + k * THREADS
@@ -70,14 +88,19 @@ void multi_round_kernel(const MultiArgs M) {
   const int slot_last = last_mine ? tid + L * THREADS : (M.n - 1) * lanes + cg;
   const int wrap = M.n * lanes;
   // one port: even rows look ahead, odd rows back (Eq. (7)); my rows rg + k * row_lanes share rg's parity
-  // unless I hold consecutive rows (row_lanes = 1)
-  const bool alternate = M.row_lanes == 1;
-  const bool rg_odd = (rg & 1) != 0;
+  // unless I hold consecutive rows (row_lanes = 1, then rg = 0 and row k has the parity of k)
+  const bool odd0 = (rg & 1) != 0;
+  const bool odd1 = M.row_lanes == 1 ? !odd0 : odd0;
+  const bool odd_last = ((min(rg + L * M.row_lanes, M.n - 1)) & 1) != 0;
+  // a thread with no row below its last one (RT = 1 past the last agent) keeps tid inside the tile
+  const int slot0 = min(tid, wrap - 1);
   // rows whose messages are read from LDS together: all of them, or a few at a time where registers are short
   constexpr int KB = ((THREADS > 256 || LEAN > 0) && RT > 4) ? (RT > 7 || LEAN > 0 ? 2 : 4) : RT;
+  // The loop body below is one straight line that replaces x and y where they are: the round's flags only
+  // steer which variable is published and whether y restarts, never two versions of the arithmetic (with
+  // several bodies to choose from, the compiler keeps a second copy of the tile and moves it back every round).
   for (int t = 0; t < M.rounds; ++t) {
     const MultiRound R = M.round[t];
-    // the round's flags are the same for every thread: branches, not per-element selects
     if (R.exch_y) {
 #pragma unroll
       for (int k = 0; k < L; ++k) zs[tid + k * THREADS] = y[k];
@@ -87,8 +110,19 @@ void multi_round_kernel(const MultiArgs M) {
       for (int k = 0; k < L; ++k) zs[tid + k * THREADS] = x[k];
       if (last_mine) zs[slot_last] = x[L];
     }
-    __syncthreads();
+    // b = 0 (round 0 of a cycle): y is not used.  From y = -0 the combine below gives b_peer * z to the
+    // bit (0 * -0 = -0, and adding -0 changes nothing, not even the sign of a zero).
+    if (!R.read_y) {
+#pragma unroll
+      for (int k = 0; k < RT; ++k) y[k] = V(-0.0f);
+    }
     const int back = R.shift * lanes;
+    const int fwd = M.port == 2 ? -back : back;    // two ports: every row reads `shift` rows back
+    PeerSlots P;
+    P.base[0] = wrap_slot(slot0 + (odd0 ? -back : fwd), wrap);
+    P.base[1] = wrap_slot(slot0 + (odd1 ? -back : fwd), wrap);
+    P.last = wrap_slot(slot_last + (odd_last ? -back : fwd), wrap);
+    __syncthreads();
 #pragma unroll
     for (int k0 = 0; k0 < RT; k0 += KB) {
       // no branch around the LDS reads, so the reads of a batch issue back to back
@@ -96,32 +130,15 @@ void multi_round_kernel(const MultiArgs M) {
 #pragma unroll
       for (int j = 0; j < KB; ++j) {
         const int k = k0 + j;
-        if (k < RT) {
-          const int s = (k == L) ? slot_last : tid + k * THREADS;
-          int q;
-          if (M.port == 2) {
-            q = s - back;
-            if (q < 0) q += wrap;
-          } else {
-            const bool odd = alternate ? ((k & 1) != 0) : rg_odd;
-            q = odd ? s - back : s + back;
-            if (q < 0) q += wrap;
-            if (q >= wrap) q -= wrap;
-          }
-          zp[j] = zs[q];
-        }
+        if (k < RT) zp[j] = zs[k == L ? P.last : peer_slot<THREADS>(P, k, wrap)];
       }
 #pragma unroll
-      for (int j = 0; j < KB; ++j)
-        if (k0 + j < RT) x[k0 + j] = combine(R.a, x[k0 + j], R.ap, zp[j]);
-      if (R.read_y) {
-#pragma unroll
-        for (int j = 0; j < KB; ++j)
-          if (k0 + j < RT) y[k0 + j] = combine(R.b, y[k0 + j], R.bp, zp[j]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < KB; ++j)
-          if (k0 + j < RT) y[k0 + j] = R.bp * zp[j];
+      for (int j = 0; j < KB; ++j) {
+        const int k = k0 + j;
+        if (k < RT) {
+          x[k] = combine(R.a, x[k], R.ap, zp[j]);
+          y[k] = combine(R.b, y[k], R.bp, zp[j]);
+        }
       }
       if (KB < RT) __builtin_amdgcn_sched_barrier(0);    // keep the batches apart
     }
