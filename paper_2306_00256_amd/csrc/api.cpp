@@ -396,19 +396,23 @@ TileShape rounds_tile(int32_t n, bool vec4, bool with_y = true) {
   // Measured on MI355X (n = 16 ... 4096).  Up to 256 agents: 256-thread workgroups with up to 9 rows per
   // thread (rows of the tile at least 128 bytes wide).  Exact averaging writes a third of the bytes: up to 80
   // agents 5 rows per thread (rows still >= 128 bytes, twice the resident workgroups) measured 5-10 % ahead
-  // (n = 31, 64), beyond that the fuller tile does (n = 100: 186 against 205 us).
-  // More agents: 512-thread workgroups with up to 9 rows per thread (128 registers: two workgroups per
-  // compute unit) make the rows of the tile two to four times wider than 256-thread ones and run 1.25x
-  // (n = 258) to 3x (n = 1026) faster; beyond 9 x 128 agents only a 1024-thread workgroup keeps the rows at
-  // 64 bytes (4.6x at n = 2050).
+  // (n = 31, 64), beyond that the fuller tile does.
+  // More agents: 512-thread workgroups with up to 10 rows per thread (the tile then takes at most half of
+  // a compute unit's LDS: two workgroups per compute unit) make the rows of the tile two to four times wider
+  // than 256-thread ones; 12 rows per thread carry them to 12 x 128 agents (n = 1500: 0.75 ms against 0.79
+  // with 1024 threads), beyond that only a 1024-thread workgroup keeps the rows at 64 bytes.  Exact averaging, which is lighter on memory, does better with
+  // 256-thread workgroups holding up to 16 rows per thread where the rows stay 128 bytes wide (up to 512
+  // agents; n = 400: 0.26 ms against 0.34) or a thread gets at least 12 rows (705 to 1024 agents; n = 800:
+  // 0.31 ms against 0.40).
   if (n <= 256) {
     const int32_t cap = (!with_y && n <= 80) ? 5 : 9;
     return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows, [](int32_t) { return ceca::kBlock; },
                      [cap](int32_t threads) { return threads == ceca::kBlock ? cap : 9; });
   }
+  const bool narrow_group = !with_y && (n <= 512 || (n > 704 && n <= 1024));
   return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows,
-                   [](int32_t m) { return m > 9 * 128 ? 1024 : 512; },
-                   [](int32_t threads) { return threads == ceca::kBlock ? ceca::kMultiRows : 9; });
+                   [narrow_group](int32_t m) { return narrow_group ? ceca::kBlock : (m > 12 * 128 ? 1024 : 512); },
+                   [n](int32_t threads) { return threads == ceca::kBlock ? ceca::kMultiRows : (threads == 512 ? (n > 10 * 128 ? 12 : 10) : 9); });
 }
 
 // Register-lean form of the fused-rounds kernel for a 256-thread tile with this many rows per thread (the
