@@ -755,28 +755,30 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
-    if args.mix_only:
-        print(json.dumps({"mix": [run_mix(torch, P, Bn, 130, 1 << 20, args.steps, args.warmup),
-                                  run_mix(torch, P, Bn, 1026, 1 << 17, args.steps, args.warmup)]}), flush=True)
-        return
-
-    if args.consensus_only:
-        if args.copy_probe:
-            src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-            dst = torch.empty_like(src)
-            dst.copy_(src)
-            torch.cuda.synchronize()
-            del src, dst
-        print(json.dumps({"consensus": run_consensus(torch, P, Bn, args.steps, args.warmup)}), flush=True)
-        return
-
-    if args.copy_probe:
+    def copy_probe():
+        # a plain copy of known size (1 GiB read, 1 GiB written): calibrates the byte counters of a --pmc run
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.mix_only:
+        if args.copy_probe:
+            copy_probe()
+        print(json.dumps({"mix": [run_mix(torch, P, Bn, 130, 1 << 20, args.steps, args.warmup),
+                                  run_mix(torch, P, Bn, 1026, 1 << 17, args.steps, args.warmup)]}), flush=True)
+        return
+
+    if args.consensus_only:
+        if args.copy_probe:
+            copy_probe()
+        print(json.dumps({"consensus": run_consensus(torch, P, Bn, args.steps, args.warmup)}), flush=True)
+        return
+
+    if args.copy_probe:
+        copy_probe()
 
     main_res = measure(torch, P, Bn, args.workload, args.steps, args.warmup)
     traffic, traffic_note = measured_traffic(P, args.workload, args.steps, args.warmup)

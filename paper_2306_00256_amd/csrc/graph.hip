@@ -23,8 +23,8 @@ constexpr int graph_waves() { return THREADS > 256 ? 4 : 1; }
 // Same tiling as the shift-invariant mixing kernel: a workgroup keeps a column tile of every agent's x in
 // registers (RT rows per thread), publishes it in LDS once per round, and every row picks up its
 // neighbours there; the neighbour table of the round comes from memory (a few KB, cached), neighbour by
-// neighbour for all of a thread's rows at once.  Per row the order of operations is t = w_0 z_0,
-// t = fma(w_j, z_j, t), x+ = fma(w_self, x, t) -- that of the shift-invariant kernel, so a circulant
+// neighbour for all of a thread's rows at once.  Per row the order of operations is t = w_self x, then
+// t = fma(w_j, z_j, t) neighbour after neighbour -- that of the shift-invariant kernel, so a circulant
 // graph gives the same bits there and here.
 // STAGE: the round's table (n * m entries of index and weight) is copied into LDS behind the tile --
 // once for a static graph, every round for a time-varying one (each thread requests its share of the
@@ -79,7 +79,7 @@ void graph_rounds_kernel(const GraphArgs M) {
     const int32_t* nbr = M.nbr + base * M.m;
     const float* w = M.w + base * M.m;
     const int next_spec = (spec + 1 == M.period) ? 0 : spec + 1;
-    float ws[RT];                                  // requested before the barrier, used after the neighbours
+    float ws[RT];                                  // requested before the barrier, used after it
 #pragma unroll
     for (int k = 0; k < RT; ++k) ws[k] = M.w_self[base + row[k]];
 #pragma unroll
@@ -95,7 +95,8 @@ void graph_rounds_kernel(const GraphArgs M) {
     }
     __syncthreads();
     if (STAGE && M.period > 1 && t + 1 < M.rounds) request_share(next_spec);
-    V acc[RT];
+#pragma unroll
+    for (int k = 0; k < RT; ++k) x[k] = ws[k] * x[k];             // the new x grows in the registers of the old one
     for (int j = 0; j < M.m; ++j) {
       int idx[RT];
       float wt[RT];
@@ -110,16 +111,9 @@ void graph_rounds_kernel(const GraphArgs M) {
           wt[k] = w[(int64_t)row[k] * M.m + j];
         }
       }
-      if (j == 0) {
 #pragma unroll
-        for (int k = 0; k < RT; ++k) acc[k] = wt[k] * xs[idx[k] * lanes + cg];
-      } else {
-#pragma unroll
-        for (int k = 0; k < RT; ++k) acc[k] = fma_rows(wt[k], xs[idx[k] * lanes + cg], acc[k]);
-      }
+      for (int k = 0; k < RT; ++k) x[k] = fma_rows(wt[k], xs[idx[k] * lanes + cg], x[k]);
     }
-#pragma unroll
-    for (int k = 0; k < RT; ++k) x[k] = fma_rows(ws[k], x[k], acc[k]);
     __syncthreads();
     spec = next_spec;
   }

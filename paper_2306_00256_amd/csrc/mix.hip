@@ -67,31 +67,21 @@ void mix_rounds_kernel(const MixArgs M) {
       if (last_mine) xs[slot_last] = x[L];
       __syncthreads();
       // peer by peer, all of the thread's rows at once: the RT LDS reads of a peer are independent and
-      // issue back to back (row by row they would each wait for the one before).  The order of
-      // operations per row is still t = w_0 z_0, t = fma(w_j, z_j, t), x+ = fma(w_self, x, t).
-      V acc[RT];
-      {
-        const int back = M.shift[j0] * lanes;
-        const float w = M.w[j0];
+      // issue back to back (row by row they would each wait for the one before).  Per row the order of
+      // operations is t = w_self x, then t = fma(w_j, z_j, t) peer after peer -- with one peer that of the
+      // CECA combine -- so the new x grows in the registers of the old one.
 #pragma unroll
-        for (int k = 0; k < RT; ++k) {
-          int q = ((k == L) ? slot_last : tid + k * THREADS) - back;
-          if (q < 0) q += wrap;
-          acc[k] = w * xs[q];
-        }
-      }
-      for (int j = j0 + 1; j < j1; ++j) {
+      for (int k = 0; k < RT; ++k) x[k] = ws * x[k];
+      for (int j = j0; j < j1; ++j) {
         const int back = M.shift[j] * lanes;
         const float w = M.w[j];
 #pragma unroll
         for (int k = 0; k < RT; ++k) {
           int q = ((k == L) ? slot_last : tid + k * THREADS) - back;
           if (q < 0) q += wrap;
-          acc[k] = fma_each(w, xs[q], acc[k]);
+          x[k] = fma_each(w, xs[q], x[k]);
         }
       }
-#pragma unroll
-      for (int k = 0; k < RT; ++k) x[k] = fma_each(ws, x[k], acc[k]);
       __syncthreads();
     }
     if (++spec == M.period) spec = 0;
