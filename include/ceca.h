@@ -244,8 +244,8 @@ int32_t ceca_state_consensus(const float* S, int32_t n, int64_t d, int64_t ld, d
 /* ---- Shift-invariant gossip averaging (the comparison topologies of Table 1 and of the consensus
  * comparison in Sec. 5; their definitions are those of the works cited there) ----
  * One round:  x_i+ = w_self x_i + sum_{j < m} w[j] x_{(i - shift[j]) mod n}   on x alone (n rows).
- * Evaluated as t = w[0] z_0, t = fma(w[j], z_j, t) for j = 1.., x+ = fma(w_self, x, t), so a round with
- * m = 1 has the bits of a CECA round with the same weights. */
+ * Evaluated as t = w_self x (rounded), then t = fma(w[j], z_j, t) for j = 0, 1, .. in that order, x+ = t, so a
+ * round with m = 1 has the bits of a CECA round with the same weights. */
 #define CECA_MIX_MAX 16
 typedef struct {
   int32_t m;                      /* 0 .. CECA_MIX_MAX peers */
@@ -281,8 +281,8 @@ int32_t ceca_mix_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, i
  * (k0 + t) mod period.  nbr: device, period*n*m int32 (0-based vertices; rows with fewer than m neighbours
  * are padded with any valid vertex at weight 0; values outside [0, n) are clamped into it rather than
  * followed); w: device, period*n*m floats; w_self: device, period*n floats.  The tables must not overlap
- * X_out.  Evaluated as t = w_0 z_0, t = fma(w_j, z_j, t), x+ = fma(w_self, x, t): a circulant graph gives
- * the bits of ceca_mix_rounds.  X_out may be X_in or disjoint from it.  Limits: n <= 4096, 1 <= m <= 64. */
+ * X_out.  Evaluated as t = w_self x (rounded), then t = fma(w_j, z_j, t) in the order of the table: a circulant
+ * graph gives the bits of ceca_mix_rounds.  X_out may be X_in or disjoint from it.  Limits: n <= 4096, 1 <= m <= 64. */
 int32_t ceca_graph_rounds(const float* X_in, float* X_out, int32_t n, int64_t d, int64_t ld,
                           const int32_t* nbr, const float* w, const float* w_self, int32_t m,
                           int32_t period, int32_t k0, int32_t rounds, void* hip_stream);

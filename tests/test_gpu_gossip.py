@@ -164,7 +164,8 @@ def test_full_size_gossip_sampled_columns(env, port):
 
 
 @pytest.mark.parametrize("n,port", [(2, 1), (3, 2), (5, 2), (6, 1), (16, 2), (17, 2), (31, 2), (32, 1), (33, 2),
-                                    (100, 1), (100, 2), (258, 1), (1023, 2), (1026, 1)])
+                                    (100, 1), (100, 2), (258, 1), (400, 2), (640, 1), (641, 2), (800, 2), (1023, 2),
+                                    (1026, 1), (1200, 1), (1281, 2), (1500, 2), (1537, 2)])
 def test_fused_rounds_equal_separate_rounds(env, n, port):
     """ceca_gossip_rounds: same bits as the sequence of single rounds, and the oracle's values."""
     torch, P = env
@@ -257,7 +258,8 @@ def test_finite_time_consensus_residue(env, n, port):
 
 
 @pytest.mark.parametrize("n,port", [(1, 2), (2, 1), (3, 2), (5, 2), (6, 1), (31, 2), (30, 1), (100, 1), (100, 2), (130, 1),
-                                    (1023, 2), (1026, 1), (4096, 2)])
+                                    (258, 1), (400, 2), (512, 1), (513, 2), (704, 1), (705, 2), (800, 2), (1023, 2), (1026, 1),
+                                    (1200, 1), (1500, 2), (4096, 2)])
 @pytest.mark.parametrize("d,pad,off", [(1037, 3, 0), (256, 0, 1)])
 def test_exact_averaging_call(env, n, port, d, pad, off):
     """ceca_average: every output row is the plain column mean (the definition; 1e-6 relative to its
