@@ -261,7 +261,10 @@ void grad_chunked_kernel(const GemvArgs P) {
   int64_t col[G];
   bool on[G];
   V z[G], e[G];
-  V other[FUSE == 2 ? G : 1];              // FUSE = 2: the variable that does not travel this iteration, after the combine
+  // FUSE = 2: the variable that does not travel this iteration, after the combine.  It is needed again only in
+  // the epilogue and waits in LDS meanwhile (in registers it pushed three others out to scratch memory,
+  // 8 MB of extra writes per iteration at n = 1023, d = 4096); a thread reads back what it wrote itself.
+  __shared__ V other_s[FUSE == 2 ? THREADS * G : 1];
 #pragma unroll
   for (int u = 0; u < G; ++u) {
     const int64_t c = ((int64_t)u * THREADS + threadIdx.x) * VEC;
@@ -310,7 +313,7 @@ void grad_chunked_kernel(const GemvArgs P) {
         yn = P.p_read_y ? combine(P.pb, hy, P.pbp, msg) : P.pbp * msg;
       }
       zv = P.new_exch_y ? yn : xn;
-      other[u] = P.new_exch_y ? xn : yn;
+      other_s[u * THREADS + threadIdx.x] = P.new_exch_y ? xn : yn;
     } else if (FUSE == 1) {
 #pragma clang fp contract(off)
       int p;
@@ -379,7 +382,7 @@ void grad_chunked_kernel(const GemvArgs P) {
       // half-step rows for the next iteration's combine: the travelling variable becomes the message itself,
       // the other moves by the same -lr e = v - z (the arithmetic of the combine kernel on stored messages)
       const V dz = v - z[u];
-      const V moved = other[u] + dz;
+      const V moved = other_s[u * THREADS + threadIdx.x] + dz;
       if (on[u]) {
         const int64_t off = (int64_t)agent * P.ldo + col[u];
         *reinterpret_cast<V*>(P.ox + off) = P.new_exch_y ? moved : v;
