@@ -242,8 +242,18 @@ def run_gossip(torch, P, Bn, sp, steps, warmup):
     with Timer(torch) as tf:
         for _ in range(reps):
             P.ceca_gossip_rounds(S, T, n, d, tau, port, ld=ld)
+    # all of them as exact averaging (x in, x out: 8 bytes), and the simplest kernels with those two mixes
+    for _ in range(2):
+        P.ceca_average(S[:n], T[:n], n, d, port, ld=ld)
+    with Timer(torch) as ta:
+        for _ in range(reps):
+            P.ceca_average(S[:n], T[:n], n, d, port, ld=ld)
+    ms11, gb11 = probe(torch, P, (pa, None, None, po1, None), n * ld, 1, 1)
     tm.fused = {"fused_rounds": tau, "fused_ms": tf.event_ms / reps, **tm.consensus,
-                "fused_GBs_on_12B": n * d * 12.0 / (tf.event_ms / reps * 1e-3) / 1e9}
+                "fused_GBs_on_12B": n * d * 12.0 / (tf.event_ms / reps * 1e-3) / 1e9,
+                "fused_probe_1r2w_ms": ms12,
+                "average_ms": ta.event_ms / reps, "average_GBs_on_8B": n * d * 8.0 / (ta.event_ms / reps * 1e-3) / 1e9,
+                "average_probe_1r1w_ms": ms11}
     return tm, 1, chain_bytes("gossip", port, [k % tau for k in range(warmup, warmup + steps)])
 
 
@@ -484,6 +494,9 @@ def run_mix(torch, P, Bn, n, d, steps, warmup):
         ms = tm.event_ms / steps
         out[f"ceca_{port}p"] = {"ms_per_call": ms, "GBs": 8.0 * n * d / (ms * 1e-3) / 1e9,
                                 "agent_param_rounds_per_s": tau * n * d / (ms * 1e-3)}
+    # the simplest kernel with the same traffic (one streaming read, one streaming write per element)
+    ms11, gb11 = probe(torch, P, (X.reshape(-1), None, None, Y.reshape(-1), None), n * ld, 1, 1)
+    out["stream_probe_1r1w"] = {"ms_per_call": ms11, "GBs": gb11}
     return out
 
 
@@ -693,7 +706,8 @@ def config_entry(res, sp):
     else:
         e["bound"] = "launch latency (no bandwidth fraction is claimed)"
     for k in ("graph_replay_ms_per_step", "run_call_ms_per_step", "run_iterations_per_call", "fused_rounds", "fused_ms",
-              "fused_GBs_on_12B", "frac_per_step", "consensus_after_timed_steps"):
+              "fused_GBs_on_12B", "fused_probe_1r2w_ms", "average_ms", "average_GBs_on_8B", "average_probe_1r1w_ms",
+              "frac_per_step", "consensus_after_timed_steps"):
         if k in res:
             e[k] = res[k]
     if "run_call_ms_per_step" in res:
@@ -817,7 +831,8 @@ def main():
         },
     }
     details = {k: main_res[k] for k in ("graph_replay_ms_per_step", "run_call_ms_per_step", "run_iterations_per_call",
-                                        "fused_rounds", "fused_ms", "fused_GBs_on_12B", "caller_gradient_step_ms",
+                                        "fused_rounds", "fused_ms", "fused_GBs_on_12B", "fused_probe_1r2w_ms", "average_ms",
+                                        "average_GBs_on_8B", "average_probe_1r1w_ms", "caller_gradient_step_ms",
                                         "max_dev_over_mean_norm_after_round", "consensus_after_timed_steps")
                if k in main_res}
     if details:
