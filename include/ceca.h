@@ -107,6 +107,8 @@ int32_t ceca_schedule(int32_t n, int32_t r, int32_t port, ceca_round_t* out, int
 
 /* One gradient-free CECA round (Sec. 3.1 / 3.2 "Main recursions" with I = x, J = y):
  *   x_i+ = a x_i + (1-a) z_peer(i),   y_i+ = b y_i + (1-b) z_peer(i),   z = x or y by delta_r.
+ * Every kernel of the library evaluates such a combination as t = a x (rounded to fp32), then fma(a_peer, z, t)
+ * with the float weights of ceca_round_t, so single rounds, fused rounds and fused steps agree bit for bit.
  * S_in, S_out: device, 2n rows of ld floats (d used); S_out is either disjoint from S_in or S_in
  * itself.  In place, a thread reads every row of a pair (port 1) or of a whole shift cycle (port 2)
  * before it writes it; out of place, two-port rounds are cut into one-row stretches that sweep the
