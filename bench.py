@@ -865,6 +865,10 @@ def main():
                 cfgs[-1]["mean_over_5_runs"] = paper_lsq_runs(torch, P, Bn, name)
         out["configs"] = cfgs
         out["consensus"] = run_consensus(torch, P, Bn)
+        # the consensus comparison at the paper's sizes (Sec. 5): ring, static and one-peer exponential gossip,
+        # gossip over a torus, CECA's exact averaging and the streaming probe with their traffic, tau rounds per call
+        torch.cuda.empty_cache()
+        out["mix"] = [run_mix(torch, P, Bn, 130, 1 << 20, 10, 2), run_mix(torch, P, Bn, 1026, 1 << 17, 10, 2)]
     if args.others:
         out["others"] = []
         for name in sorted(WL.SPECS):
