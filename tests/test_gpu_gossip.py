@@ -288,6 +288,36 @@ def test_exact_averaging_call(env, n, port, d, pad, off):
     assert torch.equal(X[:, :d], Y[:, :d])
 
 
+@pytest.mark.parametrize("n,port", [(130, 2), (400, 2), (640, 1), (800, 2), (1026, 1), (1200, 2), (1500, 2)])
+def test_exact_averaging_at_bench_sizes(env, n, port):
+    """ceca_average and ceca_gossip_rounds on 2^27 elements, every tile of the launch (the sizes of the paper's
+    consensus comparison and the agent counts where the tile shape changes): each output row is the plain
+    column mean, which is the definition of what tau rounds reach (Sec. 3.1 problem statement), to 1e-6 of
+    its norm; sampled columns follow the oracle round by round; the x rows of both calls have the same bits."""
+    torch, P = env
+    d = (1 << 27) // n // 64 * 64
+    tau = OS.num_rounds(n)
+    X = WL.device_normal((n, d), seed=900 + n)
+    mean = X.double().mean(0)
+    Y = torch.empty_like(X)
+    P.ceca_average(X, Y, n, d, port)
+    dev = (Y.double() - mean).norm(dim=1).max().item()
+    assert dev <= TOL_CONS * mean.norm().item()
+    S = torch.empty((2 * n, d), dtype=torch.float32, device="cuda")
+    S[:n] = X
+    S[n:] = float("nan")                                     # y(0) must not be read
+    T = torch.empty_like(S)
+    P.ceca_gossip_rounds(S, T, n, d, tau, port)
+    assert torch.equal(T[:n], Y)
+    cols = np.unique(np.concatenate([np.arange(0, 70), np.arange(d - 70, d),
+                                     np.random.default_rng(n).integers(0, d, 200)]))
+    ct = torch.from_numpy(cols).cuda()
+    x0 = X[:, ct].cpu().numpy()
+    xo, yo = OC.run(x0, port, 0.0, None, tau, store32=True)
+    gx, gy = T[:n][:, ct].cpu().numpy(), T[n:][:, ct].cpu().numpy()
+    assert max(rel_err(gx, xo)) <= TOL_ROUND and max(rel_err(gy, yo)) <= TOL_ROUND
+
+
 def test_exact_averaging_errors(env):
     torch, P = env
     from paper_2306_00256_amd import binding as Bn
