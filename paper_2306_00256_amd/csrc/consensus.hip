@@ -198,11 +198,16 @@ __global__ __launch_bounds__(kBlock) void cons_wave_kernel(const ConsensusArgs C
     const int64_t g = strip * cgs + cg;
     on = g < ngroups;
     col = (on ? g : 0) * VEC;
+    // my rows lie row_lanes rows apart: one address, stepped (only the last row may need the clamp)
+    const float* p = C.X + (int64_t)rg * C.ld + col;
+    const int64_t step = (int64_t)row_lanes * C.ld;
 #pragma unroll
-    for (int k = 0; k < RT; ++k) {
-      const int i = min(rg + k * row_lanes, C.n - 1);
-      x[k] = ld_stream<V>(C.X + (int64_t)i * C.ld + col);
+    for (int k = 0; k < RT - 1; ++k) {
+      x[k] = ld_stream<V>(p);
+      p += step;
     }
+    const int i = min(rg + (RT - 1) * row_lanes, C.n - 1);
+    x[RT - 1] = ld_stream<V>(C.X + (int64_t)i * C.ld + col);
   };
   V x[RT];
   bool on;
@@ -212,10 +217,13 @@ __global__ __launch_bounds__(kBlock) void cons_wave_kernel(const ConsensusArgs C
   while (true) {
     const int64_t next = strip + C.nwaves;
     const bool more = next < C.strips;              // the same for the whole wavefront
+    // rows per lane is the least that covers n, so only a lane's last row can lie past the last agent: the
+    // others need no test
+    const bool last_mine = rg + (RT - 1) * row_lanes < C.n;
     double s[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int k = 0; k < RT; ++k)
-      if (rg + k * row_lanes < C.n) acc4(s, x[k]);
+    for (int k = 0; k < RT - 1; ++k) acc4(s, x[k]);
+    if (last_mine) acc4(s, x[RT - 1]);
     // the row lanes of a column group sit cgs lanes apart: sum across them (every lane ends with the total)
 #define CECA_ROWSUM(O)                                                \
     if (cgs <= O) {                                                   \
@@ -226,9 +234,11 @@ __global__ __launch_bounds__(kBlock) void cons_wave_kernel(const ConsensusArgs C
     double m[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int q = 0; q < VEC; ++q) m[q] = s[q] / (double)C.n;
+    if (on) {
 #pragma unroll
-    for (int k = 0; k < RT; ++k)
-      if (on && rg + k * row_lanes < C.n) acc[k] += sqdev(x[k], m);
+      for (int k = 0; k < RT - 1; ++k) acc[k] += sqdev(x[k], m);
+      if (last_mine) acc[RT - 1] += sqdev(x[RT - 1], m);
+    }
     if (rg == 0 && on) {
 #pragma unroll
       for (int q = 0; q < VEC; ++q) nrm += m[q] * m[q];
@@ -382,7 +392,9 @@ static hipError_t launch_cons_wave(const ConsensusArgs& c0, bool vec4, hipStream
   const int cgs = c.wave_cgs;
   if (cgs < 1 || cgs > 64 || (cgs & (cgs - 1)) != 0 || (1 << c.cg_shift) != cgs) return hipErrorInvalidValue;
   const int row_lanes = 64 / cgs;
-  if (c.rows_per_thread < 1 || c.rows_per_thread > 32 || (int64_t)c.rows_per_thread * row_lanes < c.n)
+  // the kernel relies on rows_per_thread being the least that covers n
+  if (c.rows_per_thread < 1 || c.rows_per_thread > 32 || (int64_t)c.rows_per_thread * row_lanes < c.n ||
+      (int64_t)(c.rows_per_thread - 1) * row_lanes >= c.n)
     return hipErrorInvalidValue;
   if (c.nwaves < 1 || c.nwaves > c.strips || c.nwaves >= (1LL << 30)) return hipErrorInvalidConfiguration;
   // few wavefronts: one per workgroup, so that they spread over the compute units
