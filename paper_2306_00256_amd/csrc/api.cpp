@@ -393,19 +393,22 @@ TileShape pick_tile(int32_t n, bool vec4, int32_t cap_lo, int32_t cap_hi_256, in
 // Fused gossip rounds (x and y of every row in registers); with_y = false: exact averaging, which
 // stores no y.
 TileShape rounds_tile(int32_t n, bool vec4, bool with_y = true) {
-  // Measured on MI355X (n = 16 ... 4096).  Up to 256 agents: 256-thread workgroups with up to 9 rows per
-  // thread (rows of the tile at least 128 bytes wide).  Exact averaging writes a third of the bytes: up to 80
-  // agents 5 rows per thread (rows still >= 128 bytes, twice the resident workgroups) measured 5-10 % ahead
-  // (n = 31, 64), beyond that the fuller tile does.
+  // Measured on MI355X (n = 8 ... 4096) with the straight-line round body.  Up to 256 agents: 256-thread
+  // workgroups.  The fused rounds, two thirds of whose traffic is writes, do best with many small
+  // workgroups while the rows of the tile stay wide: up to 80 agents 5 rows per thread (n = 8: 0.30 against
+  // 0.36 ms, n = 31: 0.29 against 0.31, n = 72: 0.29 against 0.32 for 9 rows), beyond that up to 9.  Exact
+  // averaging, lighter on memory, prefers fewer row lanes and up to 12 rows per thread between 33 and 128
+  // agents (n = 56: 0.19 against 0.225 ms, n = 72: 0.20 against 0.24, n = 90: 0.21 against 0.24) and 5 rows
+  // below that (n = 8: 0.18 against 0.21).
   // More agents: 512-thread workgroups with up to 10 rows per thread (the tile then takes at most half of
   // a compute unit's LDS: two workgroups per compute unit) make the rows of the tile two to four times wider
   // than 256-thread ones; 12 rows per thread carry them to 12 x 128 agents (n = 1500: 0.75 ms against 0.79
-  // with 1024 threads), beyond that only a 1024-thread workgroup keeps the rows at 64 bytes.  Exact averaging, which is lighter on memory, does better with
-  // 256-thread workgroups holding up to 16 rows per thread where the rows stay 128 bytes wide (up to 512
-  // agents; n = 400: 0.26 ms against 0.34) or a thread gets at least 12 rows (705 to 1024 agents; n = 800:
-  // 0.31 ms against 0.40).
+  // with 1024 threads), beyond that only a 1024-thread workgroup keeps the rows at 64 bytes.  Exact averaging
+  // does better with 256-thread workgroups holding up to 16 rows per thread where the rows stay 128 bytes
+  // wide (up to 512 agents; n = 400: 0.26 ms against 0.34) or a thread gets at least 12 rows (705 to 1024
+  // agents; n = 800: 0.31 ms against 0.40).
   if (n <= 256) {
-    const int32_t cap = (!with_y && n <= 80) ? 5 : 9;
+    const int32_t cap = with_y ? (n <= 80 ? 5 : 9) : (n <= 32 ? 5 : (n <= 128 ? 12 : 9));
     return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows, [](int32_t) { return ceca::kBlock; },
                      [cap](int32_t threads) { return threads == ceca::kBlock ? cap : 9; });
   }
@@ -416,16 +419,15 @@ TileShape rounds_tile(int32_t n, bool vec4, bool with_y = true) {
 }
 
 // Register-lean form of the fused-rounds kernel for a 256-thread tile with this many rows per thread (the
-// wavefronts per SIMD it is compiled for; 0 = the plain form).  Measured on MI355X: with 5 to 7 rows the
-// lean form keeps five workgroups per compute unit instead of three, so that some load or store while
-// others exchange (n = 100: exact averaging 225 -> 186 us, n = 200: 258 -> 216 us); 9 rows fit four
-// (n = 130: 386 us with 512-thread tiles -> 327 us); with 8 rows the plain form measured ahead (n = 31, 64),
-// and 5 wavefronts would spill there.
+// wavefronts per SIMD it is compiled for, peers read from LDS two rows at a time; 0 = the plain form, all of
+// a thread's peers read at once).  Measured on MI355X: with 5 to 8 rows five wavefronts per SIMD (n = 128,
+// 8 rows: exact averaging 0.235 -> 0.21 ms), with 9 rows four; from 10 rows on the lean forms spill and the
+// plain form is the one to use.
 int32_t rounds_lean(const TileShape& t, bool vec4) {
   const int32_t forced = g_tuning.lean_tiles;
   if (!vec4 || t.threads != ceca::kBlock || forced == 1) return 0;
   if (forced >= 4) return forced;
-  if (t.rows_per_thread >= 5 && t.rows_per_thread <= 7) return 5;
+  if (t.rows_per_thread >= 5 && t.rows_per_thread <= 8) return 5;
   if (t.rows_per_thread == 9) return 4;
   return 0;
 }
