@@ -397,8 +397,8 @@ TileShape rounds_tile(int32_t n, bool vec4, bool with_y = true) {
   // workgroups.  The fused rounds, two thirds of whose traffic is writes, do best with many small
   // workgroups while the rows of the tile stay wide: up to 80 agents 5 rows per thread (n = 8: 0.30 against
   // 0.36 ms, n = 31: 0.29 against 0.31, n = 72: 0.29 against 0.32 for 9 rows), beyond that up to 9.  Exact
-  // averaging, lighter on memory, prefers fewer row lanes and up to 12 rows per thread between 33 and 128
-  // agents (n = 56: 0.19 against 0.225 ms, n = 72: 0.20 against 0.24, n = 90: 0.21 against 0.24) and 5 rows
+  // averaging, lighter on memory, prefers fewer row lanes and up to 12 rows per thread between 33 and 192
+  // agents (n = 56: 0.19 against 0.225 ms, n = 72: 0.20 against 0.24, n = 176: 0.23 against 0.26) and 5 rows
   // below that (n = 8: 0.18 against 0.21).
   // More agents: 512-thread workgroups with up to 10 rows per thread (the tile then takes at most half of
   // a compute unit's LDS: two workgroups per compute unit) make the rows of the tile two to four times wider
@@ -408,7 +408,7 @@ TileShape rounds_tile(int32_t n, bool vec4, bool with_y = true) {
   // wide (up to 512 agents; n = 400: 0.26 ms against 0.34) or a thread gets at least 12 rows (705 to 1024
   // agents; n = 800: 0.31 ms against 0.40).
   if (n <= 256) {
-    const int32_t cap = with_y ? (n <= 80 ? 5 : 9) : (n <= 32 ? 5 : (n <= 128 ? 12 : 9));
+    const int32_t cap = with_y ? (n <= 80 ? 5 : 9) : (n <= 32 ? 5 : (n <= 192 ? 12 : 9));
     return pick_tile(n, vec4, 4, ceca::kMultiRows, ceca::kMultiRows, [](int32_t) { return ceca::kBlock; },
                      [cap](int32_t threads) { return threads == ceca::kBlock ? cap : 9; });
   }
