@@ -453,18 +453,28 @@ TileShape steps_tile(int32_t n, bool vec4, int32_t steps) {
 // Mixing rounds of the comparison topologies (x of every row in registers); heavy = four or more
 // peers in some round.
 TileShape mix_tile(int32_t n, bool vec4, bool heavy) {
-  // Measured on MI355X (n = 31 ... 4096, all three topologies): 256-thread workgroups are best up to
-  // about 512 agents; 512-thread ones (13 rows per thread in 128 registers, two per compute unit) gain
-  // 1.2x at n = 1026, and beyond 13 x 128 agents a 1024-thread workgroup keeps the rows of the tile at
-  // 64 bytes (1.7x at n = 2050, 2.5x at n = 4096).
-  // 256 threads (n = 31, 130, 258, 1026): one or two peers per round want wide row segments, many
-  // peers per round (LDS-read bound) want more resident workgroups
+  // Measured on MI355X (n = 31 ... 4096, all three topologies; x alone in registers, 67 registers at 9 rows
+  // per thread).  What counts is how many workgroups a compute unit holds: the LDS tile is n x tile row.
+  // Up to 256 agents: 256 threads, up to 12 rows per thread (n = 64 ring: 0.20 against 0.25 ms with 16,
+  // n = 100: 0.215 against 0.24).  257 to 512 agents: one or two peers per round run 512-thread workgroups
+  // with up to 9 rows (n = 258 ring: 0.33 against 0.40 ms), many peers per round (LDS-read bound) 256 threads
+  // with up to 16.  Up to 9 x 128 agents: 512 threads x at most 9 rows, i.e. 64-byte tile rows and three
+  // workgroups per compute unit rather than 128-byte rows and one (n = 800: ring 0.31 against 0.50 ms, static
+  // exponential 0.81 against 1.20).  Beyond: 512 threads x 13 rows up to 13 x 128 agents and 1024 threads
+  // after that for few peers; many peers keep 512 threads x 9 rows up to 2304 agents (n = 1500: 0.98 against
+  // 1.51 ms, n = 2050: 1.34 against 1.59).
   return pick_tile(n, vec4, 4, 32, 16,
-                   [](int32_t m) { return m <= 512 ? ceca::kBlock : (m <= 13 * 128 ? 512 : 1024); },
+                   [heavy](int32_t m) {
+                     if (m <= 256) return ceca::kBlock;
+                     if (m <= 512) return heavy ? ceca::kBlock : 512;
+                     if (m <= 9 * 128) return 512;
+                     if (heavy) return m <= 9 * 256 ? 512 : 1024;
+                     return m <= 13 * 128 ? 512 : 1024;
+                   },
                    [n, heavy](int32_t threads) {
-                     return threads != ceca::kBlock
-                                ? 13
-                                : n <= 32 ? 12 : (n <= 192 ? (heavy ? 8 : 16) : (n <= 512 ? 16 : (heavy ? 16 : 24)));
+                     if (threads == ceca::kBlock) return n <= 256 ? 12 : (n <= 512 ? 16 : (heavy ? 16 : 24));
+                     if (threads == 512) return (heavy || n <= 9 * 128) ? 9 : 13;
+                     return 13;
                    });
 }
 
