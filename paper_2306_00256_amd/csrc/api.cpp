@@ -479,14 +479,16 @@ TileShape mix_tile(int32_t n, bool vec4, bool heavy) {
 }
 
 // Gossip over an arbitrary graph (x of every row in registers, plus a neighbour index and weight per row
-// in flight).  Measured on MI355X (ring, torus, hypercube; n = 130 ... 2048): 256-thread workgroups are
-// best up to about 258 agents, 1024-thread ones from 512 on (1.6-3.3x there: wider rows of the tile).
+// in flight).  Measured on MI355X (ring, torus; n = 130 ... 2048): 256-thread workgroups up to about 384
+// agents, 512-thread ones up to 768 (n = 520: torus 0.81 -> 0.72 ms, ring 0.59 -> 0.53 against 1024 threads),
+// 1024-thread ones beyond, with up to 8 rows per thread so that the rows of the tile stay 64 bytes wide up to
+// 2048 agents (n = 2048 ring: 1.13 -> 0.70 ms against 6 rows and 32-byte rows).
 TileShape graph_tile(int32_t n, bool vec4) {
   return pick_tile(n, vec4, 4, ceca::kGraphRows, 8,
-                   [](int32_t m) { return m <= 384 ? ceca::kBlock : 1024; },
+                   [](int32_t m) { return m <= 384 ? ceca::kBlock : (m <= 768 ? 512 : 1024); },
                    [n](int32_t threads) {
                      if (threads == ceca::kBlock) return n <= 192 ? 8 : ceca::kGraphRows;
-                     return n <= 6 * 512 ? 6 : 8;      // 6 rows fit 128 registers; 8 keep 4096 agents at 32-byte rows
+                     return 8;
                    });
 }
 
